@@ -1,0 +1,428 @@
+/*
+ * Plain CPU oracle for the SparseK attention hot path (arXiv 2406.16747).
+ *
+ * THIS IS TEST INFRASTRUCTURE, not the product: it is slow on purpose, follows the
+ * paper's definitions step by step, computes in fp64, and shares no code, header,
+ * table or helper with the HIP library.  Only tests, the smoke check and the
+ * cpu_baseline leg of the benchmark may call it.
+ *
+ * Conventions (0-indexed): n sequence length, d head dim, k selected pairs,
+ * w sliding window; prefix t means scores u[0..t] (t+1 entries); query i attends the
+ * window keys [max(0,i-w+1), i] with gate 1 and, when T=i-w >= 0, the hard top-k
+ * keys of prefix T, each carrying its soft SPARSEK gate clip(u_j - tau_T, 0, 1)
+ * (Sec. 3.2 selection equations, Sec. 3.4 sliding-window combination).
+ *
+ * Readings taken where the paper is silent (all listed in the design notes):
+ *  - ties in the top-k use the total order "larger score first, then older first";
+ *  - a prefix with at most k entries selects everything with gate 1 and stores
+ *    tau = min(prefix) - 1; in general tau = sup{tau : sum clip(z - tau,0,1) >= min(k,m)},
+ *    which also fixes tau on a flat segment (w* == u*) to z_(k) - 1;
+ *  - k == 0: mask identically zero, tau = max(prefix);
+ *  - gate_mode 0 gates keys and values (Eq. for selected attention with the soft
+ *    selection matrix), 1 gates values only (Sec. 3.5 hard-K/soft-V), 2 gates nothing
+ *    (forward of the straight-through estimator, Sec. 3.4);
+ *  - the softmax denominator is never re-weighted by the gate.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------------- */
+/* SPARSEK operator: one shot, Sec. 3.3 solution + App. A.2 sweep             */
+/* ------------------------------------------------------------------------- */
+
+static int cmp_desc(const void *a, const void *b)
+{
+    double x = *(const double *)a, y = *(const double *)b;
+    return (x < y) - (x > y);
+}
+
+static double clip01(double x) { return x < 0.0 ? 0.0 : (x > 1.0 ? 1.0 : x); }
+
+/* tau for sorted coordinates zs[0..m-1] (descending) with cumulative sums
+ * cs (cs[i] = zs[0]+..+zs[i-1]).  Sweeps the 2m breakpoints {z_j} U {z_j - 1} in
+ * descending order (App. A.2); at each breakpoint beta the step functions
+ * u(beta) = #{z >= beta+1}, w(beta) = #{z > beta} only grow, so two pointers follow
+ * them, and f(beta) = sum_j clip(z_j - beta, 0, 1) = u + sum_{u<j<=w} z_(j) - (w-u) beta.
+ * The sweep stops at the first breakpoint with f(beta) >= keff; the closed form
+ * (Eq. for tau with u*, w*) is then applied on the segment to its right.
+ * Returns u* and w* as well. */
+static double tau_sorted(const double *zs, const double *cs, int m, int k, int *ustar, int *wstar)
+{
+    int keff = k < m ? k : m;
+    if (k == 0) { /* degenerate: empty mask */
+        *ustar = 0;
+        *wstar = 0;
+        return zs[0];
+    }
+    int a = 0, b = 0;   /* next breakpoint candidates: zs[a] and zs[b]-1 */
+    int uu = 0, ww = 0; /* u(beta), w(beta) */
+    double beta = 0.0, f = 0.0;
+    while (a < m || b < m) {
+        double ba = a < m ? zs[a] : -INFINITY;
+        double bb = b < m ? zs[b] - 1.0 : -INFINITY;
+        if (ba >= bb) { beta = ba; a++; } else { beta = bb; b++; }
+        while (uu < m && zs[uu] >= beta + 1.0) uu++;
+        if (ww < uu) ww = uu;
+        while (ww < m && zs[ww] > beta) ww++;
+        f = (double)uu + (cs[ww] - cs[uu]) - (double)(ww - uu) * beta;
+        if (f >= (double)keff) break; /* reached at the latest at beta = z_(m)-1, f = m */
+    }
+    /* counts just to the right of beta: u' = #{z > beta+1}, w' = #{z > beta} */
+    int u1 = 0, w1 = 0;
+    while (u1 < m && zs[u1] > beta + 1.0) u1++;
+    w1 = u1;
+    while (w1 < m && zs[w1] > beta) w1++;
+    double tau;
+    if (w1 == u1 || f == (double)keff) {
+        tau = beta; /* flat segment or exact hit: the sup of the level set is beta */
+    } else {
+        tau = ((cs[w1] - cs[u1]) + (double)u1 - (double)keff) / (double)(w1 - u1);
+        if (tau < beta) tau = beta; /* rounding guard; the root lies in [beta, next) */
+    }
+    int us = 0, ws = 0;
+    while (us < m && zs[us] >= tau + 1.0) us++;
+    ws = us;
+    while (ws < m && zs[ws] > tau) ws++;
+    *ustar = us;
+    *wstar = ws;
+    return tau;
+}
+
+/* SPARSEK(z, k) for one vector: tau, mask p = clip(z - tau, 0, 1), u*, w*.
+ * p may be NULL.  Returns 0, or -1 on bad arguments / allocation failure. */
+int orc_sparsek(const float *z, int m, int k, double *tau_out, double *p, int *ustar, int *wstar)
+{
+    if (m < 1 || k < 0) return -1;
+    double *zs = (double *)malloc(sizeof(double) * (size_t)m);
+    double *cs = (double *)malloc(sizeof(double) * (size_t)(m + 1));
+    if (!zs || !cs) { free(zs); free(cs); return -1; }
+    for (int j = 0; j < m; j++) zs[j] = (double)z[j];
+    qsort(zs, (size_t)m, sizeof(double), cmp_desc);
+    cs[0] = 0.0;
+    for (int j = 0; j < m; j++) cs[j + 1] = cs[j] + zs[j];
+    int us, ws;
+    double tau = tau_sorted(zs, cs, m, k, &us, &ws);
+    *tau_out = tau;
+    if (ustar) *ustar = us;
+    if (wstar) *wstar = ws;
+    if (p) for (int j = 0; j < m; j++) p[j] = (k == 0) ? 0.0 : clip01((double)z[j] - tau);
+    free(zs);
+    free(cs);
+    return 0;
+}
+
+/* tau_t, u*_t, w*_t for every causal prefix t of one score row.  The sorted
+ * coordinates of prefix t are those of prefix t-1 with u[t] inserted; everything
+ * else is the one-shot evaluation above, redone for each prefix. */
+int orc_tau_prefixes(const float *u, int n, int k, double *tau, int *ustar, int *wstar)
+{
+    if (n < 1 || k < 0) return -1;
+    double *zs = (double *)malloc(sizeof(double) * (size_t)n);
+    double *cs = (double *)malloc(sizeof(double) * (size_t)(n + 1));
+    if (!zs || !cs) { free(zs); free(cs); return -1; }
+    for (int t = 0; t < n; t++) {
+        double z = (double)u[t];
+        int pos = t;
+        while (pos > 0 && zs[pos - 1] < z) { zs[pos] = zs[pos - 1]; pos--; }
+        zs[pos] = z;
+        int m = t + 1;
+        cs[0] = 0.0;
+        for (int j = 0; j < m; j++) cs[j + 1] = cs[j] + zs[j];
+        int us, ws;
+        tau[t] = tau_sorted(zs, cs, m, k, &us, &ws);
+        if (ustar) ustar[t] = us;
+        if (wstar) wstar[t] = ws;
+    }
+    free(zs);
+    free(cs);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Hard top-k selection (Sec. 3.2), total order: larger score, then older     */
+/* ------------------------------------------------------------------------- */
+
+/* 1 if entry a precedes entry b in the selection order */
+static int precedes(const float *u, int a, int b)
+{
+    return (u[a] > u[b]) || (u[a] == u[b] && a < b);
+}
+
+/* sel(t): the min(k,t+1) first entries of prefix t in the selection order, written
+ * in ascending position; returns their number. */
+int orc_select_prefix(const float *u, int t, int k, int32_t *idx)
+{
+    int cnt = 0;
+    for (int j = 0; j <= t; j++) {
+        int before = 0;
+        for (int i = 0; i <= t; i++) if (i != j && precedes(u, i, j)) before++;
+        if (before < k) idx[cnt++] = j;
+    }
+    return cnt;
+}
+
+/* death[j]: first prefix t >= j whose top-k does not contain j (n if none).
+ * j is in sel(t) iff fewer than k entries of prefix t precede it; that count only
+ * grows with t, which is the irreversibility of Sec. 3.2. */
+int orc_death(const float *u, int n, int k, int32_t *death)
+{
+    if (n < 1 || k < 0) return -1;
+    for (int j = 0; j < n; j++) {
+        int before = 0;
+        for (int i = 0; i < j; i++) if (precedes(u, i, j)) before++;
+        int dj = n;
+        if (before >= k) dj = j;
+        else {
+            for (int t = j + 1; t < n; t++) {
+                if (precedes(u, t, j)) before++;
+                if (before >= k) { dj = t; break; }
+            }
+        }
+        death[j] = dj;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Gated attention, one query, straight from the definition                   */
+/* ------------------------------------------------------------------------- */
+
+typedef struct {
+    int n, d, k, w, gate_mode;
+    double scale;
+} orc_cfg;
+
+/* Attention of query i over explicit key/gate lists (selected-attention equations of
+ * Sec. 3.2 with the gating variants).  keys[0..nk), gates[0..nk).  o has d entries. */
+static void attend_list(const float *qi, const float *K, const float *V, int d, const int *keys,
+                        const double *gates, int nk, int gate_mode, double scale, double *o,
+                        double *lse, double *p_out, double *qk_out)
+{
+    double *s = (double *)malloc(sizeof(double) * (size_t)(nk > 0 ? nk : 1));
+    double smax = -INFINITY;
+    for (int a = 0; a < nk; a++) {
+        const float *kj = K + (size_t)keys[a] * d;
+        double dot = 0.0;
+        for (int c = 0; c < d; c++) dot += (double)qi[c] * (double)kj[c];
+        if (qk_out) qk_out[a] = dot;
+        double gk = (gate_mode == 0) ? gates[a] : 1.0;
+        s[a] = scale * gk * dot;
+        if (s[a] > smax) smax = s[a];
+    }
+    double den = 0.0;
+    for (int a = 0; a < nk; a++) den += exp(s[a] - smax);
+    for (int c = 0; c < d; c++) o[c] = 0.0;
+    for (int a = 0; a < nk; a++) {
+        double p = exp(s[a] - smax) / den;
+        if (p_out) p_out[a] = p;
+        double gv = (gate_mode == 2) ? 1.0 : gates[a];
+        const float *vj = V + (size_t)keys[a] * d;
+        for (int c = 0; c < d; c++) o[c] += p * gv * (double)vj[c];
+    }
+    if (lse) *lse = smax + log(den);
+    free(s);
+}
+
+/* Key list of query i from per-prefix thresholds and lifetimes: selected part first
+ * (ascending position), then the window.  Returns the list length. */
+static int build_keys(const float *u, const double *tau, const int32_t *death, int i, int k, int w,
+                      int *keys, double *gates)
+{
+    int nk = 0;
+    int T = i - w;
+    if (T >= 0 && k > 0) {
+        for (int j = 0; j <= T; j++)
+            if (death[j] > T) {
+                keys[nk] = j;
+                gates[nk] = clip01((double)u[j] - tau[T]);
+                nk++;
+            }
+    }
+    int lo = i - w + 1;
+    if (lo < 0) lo = 0;
+    for (int j = lo; j <= i; j++) {
+        keys[nk] = j;
+        gates[nk] = 1.0;
+        nk++;
+    }
+    return nk;
+}
+
+/* One query, everything recomputed from scratch by definition: sort-based tau of
+ * prefix T, counting-based top-k of prefix T, then the attention.  O(n^2) per call;
+ * exists so that the faster whole-sequence routine below can be checked against it. */
+int orc_attn_query_bydef(const float *q, const float *K, const float *V, const float *u, int n,
+                         int d, int k, int w, int gate_mode, double scale, int i, double *o,
+                         double *lse)
+{
+    if (i < 0 || i >= n || k < 0 || w < 0 || k + w < 1) return -1;
+    int *keys = (int *)malloc(sizeof(int) * (size_t)(n + 1));
+    double *gates = (double *)malloc(sizeof(double) * (size_t)(n + 1));
+    int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n + 1));
+    int nk = 0;
+    int T = i - w;
+    if (T >= 0 && k > 0) {
+        double tauT;
+        orc_sparsek(u, T + 1, k, &tauT, NULL, NULL, NULL);
+        int ns = orc_select_prefix(u, T, k, idx);
+        for (int a = 0; a < ns; a++) {
+            keys[nk] = idx[a];
+            gates[nk] = clip01((double)u[idx[a]] - tauT);
+            nk++;
+        }
+    }
+    int lo = i - w + 1;
+    if (lo < 0) lo = 0;
+    for (int j = lo; j <= i; j++) { keys[nk] = j; gates[nk] = 1.0; nk++; }
+    attend_list(q + (size_t)i * d, K, V, d, keys, gates, nk, gate_mode, scale, o, lse, NULL, NULL);
+    free(keys);
+    free(gates);
+    free(idx);
+    return 0;
+}
+
+/* Rows [i_begin, i_end) of one head, given that head's score row with its
+ * thresholds and lifetimes.  o: [(i_end-i_begin), d], lse: [(i_end-i_begin)] or NULL. */
+int orc_attn_rows(const float *q, const float *K, const float *V, const float *u, const double *tau,
+                  const int32_t *death, int n, int d, int k, int w, int gate_mode, double scale,
+                  int i_begin, int i_end, double *o, double *lse)
+{
+    if (i_begin < 0 || i_end > n || k < 0 || w < 0 || k + w < 1) return -1;
+    int *keys = (int *)malloc(sizeof(int) * (size_t)(n + 1));
+    double *gates = (double *)malloc(sizeof(double) * (size_t)(n + 1));
+    for (int i = i_begin; i < i_end; i++) {
+        int nk = build_keys(u, tau, death, i, k, w, keys, gates);
+        attend_list(q + (size_t)i * d, K, V, d, keys, gates, nk, gate_mode, scale,
+                    o + (size_t)(i - i_begin) * d, lse ? lse + (i - i_begin) : NULL, NULL, NULL);
+    }
+    free(keys);
+    free(gates);
+    return 0;
+}
+
+/* All B*H heads; q,k,v [B,H,n,d] fp32 (bf16 inputs are widened by the caller),
+ * u [B,Gu,n], tau [B,Gu,n] fp64, death [B,Gu,n].  o [B,H,n,d] fp64, lse [B,H,n].
+ * Heads are independent; they are spread over nthreads OpenMP threads.
+ * Returns the number of threads used, or -1. */
+int orc_attn_fwd(const float *q, const float *K, const float *V, const float *u, const double *tau,
+                 const int32_t *death, int B, int H, int Gu, int n, int d, int k, int w,
+                 int gate_mode, double scale, double *o, double *lse, int nthreads)
+{
+    if (B < 1 || H < 1 || (Gu != 1 && Gu != H)) return -1;
+    int used = 1;
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+    used = nthreads > 0 ? nthreads : omp_get_max_threads();
+#endif
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; bh++) {
+        int b = bh / H, h = bh % H;
+        int g = (Gu == 1) ? 0 : h;
+        size_t row = ((size_t)b * Gu + g) * (size_t)n;
+        size_t off = (size_t)bh * n * d;
+        int rc = orc_attn_rows(q + off, K + off, V + off, u + row, tau + row, death + row, n, d, k,
+                               w, gate_mode, scale, 0, n, o + off, lse ? lse + (size_t)bh * n : NULL);
+        if (rc) bad = 1;
+    }
+    return bad ? -1 : used;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Gradient of L = sum(dO * O) with respect to the scores u (App. A.3)        */
+/* ------------------------------------------------------------------------- */
+
+/* One head.  For every query i with T=i-w >= 0: g_j = dL/dm_ij for the selected keys
+ * of prefix T (0 for everything else), then the SPARSEK Jacobian-vector product
+ * s * (g - mean_{S*} g) over S*_T = {j <= T : tau_T < u_j < tau_T + 1} is added into
+ * du.  The hard top-k set is treated as a constant.  du [n] is accumulated into. */
+int orc_mask_bwd_head(const float *q, const float *K, const float *V, const float *u,
+                      const double *tau, const int32_t *death, const float *dO, int n, int d, int k,
+                      int w, int gate_mode, double scale, double *du)
+{
+    if (k < 0 || w < 0 || k + w < 1) return -1;
+    int *keys = (int *)malloc(sizeof(int) * (size_t)(n + 1));
+    double *gates = (double *)malloc(sizeof(double) * (size_t)(n + 1));
+    double *p = (double *)malloc(sizeof(double) * (size_t)(n + 1));
+    double *qk = (double *)malloc(sizeof(double) * (size_t)(n + 1));
+    double *g = (double *)malloc(sizeof(double) * (size_t)n);
+    double *o = (double *)malloc(sizeof(double) * (size_t)d);
+    for (int i = w; i < n && k > 0 && gate_mode != 2; i++) {
+        int T = i - w;
+        int nk = build_keys(u, tau, death, i, k, w, keys, gates);
+        attend_list(q + (size_t)i * d, K, V, d, keys, gates, nk, gate_mode, scale, o, NULL, p, qk);
+        const float *dOi = dO + (size_t)i * d;
+        double D = 0.0;
+        for (int c = 0; c < d; c++) D += (double)dOi[c] * o[c];
+        for (int j = 0; j <= T; j++) g[j] = 0.0;
+        for (int a = 0; a < nk; a++) {
+            int j = keys[a];
+            if (j > T) continue; /* window keys carry the constant gate 1 */
+            const float *vj = V + (size_t)j * d;
+            double dov = 0.0;
+            for (int c = 0; c < d; c++) dov += (double)dOi[c] * (double)vj[c];
+            double gj = p[a] * dov; /* through the value gate */
+            if (gate_mode == 0)     /* through the key gate: ds = p (m dO.v - D) */
+                gj += scale * qk[a] * p[a] * (gates[a] * dov - D);
+            g[j] = gj;
+        }
+        int cntS = 0;
+        double sumg = 0.0;
+        for (int j = 0; j <= T; j++) {
+            double uj = (double)u[j];
+            if (uj > tau[T] && uj < tau[T] + 1.0) { cntS++; sumg += g[j]; }
+        }
+        if (cntS == 0) continue;
+        double ghat = sumg / (double)cntS;
+        for (int j = 0; j <= T; j++) {
+            double uj = (double)u[j];
+            if (uj > tau[T] && uj < tau[T] + 1.0) du[j] += g[j] - ghat;
+        }
+    }
+    free(keys); free(gates); free(p); free(qk); free(g); free(o);
+    return 0;
+}
+
+/* All heads; du [B,Gu,n] fp64 is zeroed, then every head adds into its group's row. */
+int orc_mask_bwd(const float *q, const float *K, const float *V, const float *u, const double *tau,
+                 const int32_t *death, const float *dO, int B, int H, int Gu, int n, int d, int k,
+                 int w, int gate_mode, double scale, double *du, int nthreads)
+{
+    if (B < 1 || H < 1 || (Gu != 1 && Gu != H)) return -1;
+    memset(du, 0, sizeof(double) * (size_t)B * Gu * n);
+    int used = 1;
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+    used = nthreads > 0 ? nthreads : omp_get_max_threads();
+#endif
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; bh++) {
+        int b = bh / H, h = bh % H;
+        int g = (Gu == 1) ? 0 : h;
+        size_t row = ((size_t)b * Gu + g) * (size_t)n;
+        size_t off = (size_t)bh * n * d;
+        double *tmp = (double *)calloc((size_t)n, sizeof(double));
+        int rc = orc_mask_bwd_head(q + off, K + off, V + off, u + row, tau + row, death + row,
+                                   dO + off, n, d, k, w, gate_mode, scale, tmp);
+        if (rc) bad = 1;
+#pragma omp critical
+        for (int j = 0; j < n; j++) du[row + j] += tmp[j];
+        free(tmp);
+    }
+    return bad ? -1 : used;
+}
+
+int orc_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
