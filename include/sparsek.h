@@ -1,0 +1,140 @@
+/*
+ * libsparsek -- SparseK attention hot path for AMD MI355X (gfx950), C ABI.
+ *
+ * Method: "Sparser is Faster and Less is More: Efficient Sparse Attention for
+ * Long-Range Transformers" (arXiv 2406.16747).  Three stages, all on the GPU:
+ *   (1) SPARSEK mask operator for every causal prefix of the KV importance scores
+ *       (Sec. 3.3: projection onto {0<=m<=1, sum m = k}, m = clip(u - tau, 0, 1));
+ *   (2) hard top-k selection per prefix (Sec. 3.2), stored compactly as one lifetime
+ *       per key, which the irreversibility of the selection makes possible;
+ *   (3) causal attention over the gated top-k pairs plus a sliding window (Sec. 3.2
+ *       selected-attention equations, Sec. 3.4 window combination, Sec. 3.5 hard-K /
+ *       soft-V variant), and the same as a constant-memory one-token decode step.
+ *
+ * Conventions.  0-indexed positions.  n sequence length, d head dim (64 or 128 for
+ * bf16, any multiple of 4 up to 128 for fp32), k selected pairs, w window size.
+ * "prefix t" = scores u[0..t].  Query i attends the window keys max(0,i-w+1)..i with
+ * gate 1 and, if T = i-w >= 0, the top-k keys of prefix T with gates
+ * clip(u_j - tau_T, 0, 1).  Heads h of batch b use score row (b, g) with g = 0 when
+ * Gu == 1 and g = h when Gu == H.
+ *
+ * All tensor pointers are DEVICE pointers to caller-owned, contiguous memory; the
+ * library never allocates, frees or synchronises (except sparsek_decode_status).
+ * Every call validates its arguments on the host, enqueues its kernels on `stream`
+ * (a hipStream_t passed as void*, NULL = the default stream) and returns at once.
+ * Return value: 0 on success; a negative SPARSEK_ERR_* code when nothing was enqueued.
+ * Scores must not be NaN (undefined result); -0.0 and +0.0 compare equal.
+ */
+#ifndef SPARSEK_H
+#define SPARSEK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPARSEK_OK 0
+#define SPARSEK_ERR_INVALID_ARG (-1)    /* null pointer, n<1, k<0, w<0, k+w<1, Gu not in {1,H}, bad range */
+#define SPARSEK_ERR_UNSUPPORTED (-2)    /* head dim / dtype / size outside what the kernels handle */
+#define SPARSEK_ERR_WORKSPACE (-3)      /* workspace or state buffer smaller than the *_bytes query says */
+#define SPARSEK_ERR_LAUNCH (-5)         /* the HIP runtime refused a launch */
+
+#define SPARSEK_F32 0
+#define SPARSEK_BF16 1
+
+/* gate_mode: where the soft gate m_ij multiplies.
+ *   0  keys and values: s_ij = scale * m_ij * q_i.k_j, o_i = sum_j p_ij m_ij v_j  (soft selection matrix on K and V)
+ *   1  values only:     s_ij = scale * q_i.k_j,        o_i = sum_j p_ij m_ij v_j  (Sec. 3.5)
+ *   2  nowhere:         plain attention over the selected + window keys (straight-through forward, Sec. 3.4)
+ * p_i = softmax_j(s_ij) over the attended keys; the denominator is never gated. */
+typedef struct {
+    int32_t B, H, Gu, n, d, k, w;
+    int32_t dtype;     /* SPARSEK_F32 or SPARSEK_BF16: storage type of q, k, v, o, dO */
+    int32_t gate_mode; /* 0, 1 or 2 */
+    float softmax_scale;
+} sparsek_cfg;
+
+const char *sparsek_strerror(int code);
+
+/* ---- stages 1+2: thresholds and lifetimes (Sec. 3.3 solution equations; Sec. 3.2) ----
+ * u     in  [B,Gu,n] fp32 scores.
+ * tau   out [B,Gu,n] fp32: tau[t] = sup{ x : sum_{j<=t} clip(u_j - x, 0, 1) >= min(k, t+1) };
+ *           for t+1 <= k this is min(u[0..t]) - 1 (all gates 1); on a flat segment
+ *           (w* == u*) it is z_(k) - 1; for k == 0 it is max(u[0..t]) (all gates 0).
+ * death out [B,Gu,n] int32: key j belongs to the top-k of prefix t exactly for
+ *           j <= t < death[j]  (death[j] == j: never selected; == n: still selected at the end).
+ *           Order of the top-k: larger score first, among equal scores the older key.
+ * ws    scratch of at least sparsek_mask_workspace_bytes(cfg) bytes (uses cfg->B, Gu, n, k). */
+size_t sparsek_mask_workspace_bytes(const sparsek_cfg *cfg);
+int sparsek_mask(const sparsek_cfg *cfg, const float *u, float *tau, int32_t *death, void *ws,
+                 size_t ws_bytes, void *stream);
+
+/* ---- stage 2, explicit form (verification aid; O((t_end-t_begin)*k) memory) ----
+ * For every prefix t in [t_begin, t_end): idx [B,Gu,t_end-t_begin,k] int32 = positions of the
+ * top-k of prefix t in ascending order, padded with -1; gate (same shape, fp32, may be NULL)
+ * = clip(u_j - tau_t, 0, 1) of those positions, 0 in the padding. */
+int sparsek_materialize(const sparsek_cfg *cfg, const float *u, const float *tau,
+                        const int32_t *death, int32_t t_begin, int32_t t_end, int32_t *idx,
+                        float *gate, void *stream);
+
+/* ---- stage 3: gated attention forward (Sec. 3.2, 3.4, 3.5) ----
+ * q,k,v in  [B,H,n,d] of cfg->dtype;  u,tau,death as produced by sparsek_mask.
+ * o     out [B,H,n,d] of cfg->dtype;  lse out [B,H,n] fp32 (natural log of the softmax
+ *           denominator, including the running maximum), may be NULL.
+ * ws    scratch of at least sparsek_attn_fwd_workspace_bytes(cfg) bytes. */
+size_t sparsek_attn_fwd_workspace_bytes(const sparsek_cfg *cfg);
+int sparsek_attn_fwd(const sparsek_cfg *cfg, const void *q, const void *k, const void *v,
+                     const float *u, const float *tau, const int32_t *death, void *o, float *lse,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/* ---- SPARSEK mask backward (App. A.3 Jacobian) ----
+ * du out [B,Gu,n] fp32 = gradient of L = sum(dO * O) with respect to the scores through the
+ * soft gates (the hard top-k set is a constant): for every prefix T, with g_j = dL/dm_{T+w,j},
+ * du += s * (g - mean_{S*} g), S* = { j <= T : tau_T < u_j < tau_T + 1 }.  Heads of one score
+ * group add into the same row.  o and lse are the outputs of sparsek_attn_fwd on the same inputs.
+ * gate_mode 2 has no gate in the forward, so du = 0. */
+size_t sparsek_mask_bwd_workspace_bytes(const sparsek_cfg *cfg);
+int sparsek_mask_bwd(const sparsek_cfg *cfg, const void *q, const void *k, const void *v,
+                     const float *u, const float *tau, const int32_t *death, const void *o,
+                     const float *lse, const void *dO, float *du, void *ws, size_t ws_bytes,
+                     void *stream);
+
+/* ---- constant-memory decode (Sec. 3.2 irreversibility; Sec. 3.3 incremental evaluation) ----
+ * The state holds, per (b,h), k+w key/value slots and, per (b,g), the scores of the window,
+ * of the selected keys and of every other key still above the threshold (at most cand_cap of
+ * them: the bounded-heap variant of Sec. 3.3; when more would be needed the smallest are
+ * dropped and bit 0 of that row's status word is set -- tau is then approximate).
+ * One step appends position t: the key leaving the window (position t-w) joins the SPARSEK
+ * prefix, tau and the top-k are updated incrementally, an evicted key frees its slot, and the
+ * new query attends the k selected + w window slots exactly as query t of the prefill would. */
+typedef struct {
+    int32_t B, H, Gu, d, k, w;
+    int32_t cand_cap;  /* capacity for scores above tau outside the top-k; 0 = default 4*max(k,16) */
+    int32_t dtype;     /* SPARSEK_BF16 (fp32 also accepted) */
+    int32_t gate_mode;
+    float softmax_scale;
+} sparsek_decode_cfg;
+
+size_t sparsek_decode_state_bytes(const sparsek_decode_cfg *cfg);
+/* empty context (next position 0) */
+int sparsek_decode_init(const sparsek_decode_cfg *cfg, void *state, size_t state_bytes, void *stream);
+/* state after consuming positions 0..n_ctx-1: k,v [B,H,n_ctx,d]; u,tau,death [B,Gu,n_ctx] from
+ * sparsek_mask with the same k (tau, death may come from a longer sequence's first n_ctx entries
+ * only if death was computed on exactly n_ctx entries). */
+int sparsek_decode_load(const sparsek_decode_cfg *cfg, void *state, size_t state_bytes, int32_t n_ctx,
+                        const void *k, const void *v, const float *u, const float *tau,
+                        const int32_t *death, void *stream);
+/* q_new,k_new,v_new [B,H,d]; u_new [B,Gu]; o out [B,H,d].  state is updated in place. */
+int sparsek_decode_step(const sparsek_decode_cfg *cfg, void *state, const void *q_new,
+                        const void *k_new, const void *v_new, const float *u_new, void *o,
+                        void *stream);
+/* copies the per-row status words [B*Gu] to host memory; synchronises the stream.  bit 0: candidate overflow */
+int sparsek_decode_status(const sparsek_decode_cfg *cfg, const void *state, int32_t *host_flags,
+                          void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSEK_H */

@@ -1,0 +1,184 @@
+// C-ABI entry points of libsparsek: argument validation, then the launch wrappers.
+#include "common.hpp"
+
+using namespace spk;
+
+namespace {
+
+int check_common(const sparsek_cfg* c)
+{
+    if (!c) return SPARSEK_ERR_INVALID_ARG;
+    if (c->B < 1 || c->H < 1 || c->n < 1 || c->k < 0 || c->w < 0 || c->k + c->w < 1)
+        return SPARSEK_ERR_INVALID_ARG;
+    if (c->Gu != 1 && c->Gu != c->H) return SPARSEK_ERR_INVALID_ARG;
+    if ((long long)c->B * c->H > 65535) return SPARSEK_ERR_UNSUPPORTED;
+    if ((long long)c->n > (1 << 28)) return SPARSEK_ERR_UNSUPPORTED;
+    return SPARSEK_OK;
+}
+
+int check_attn(const sparsek_cfg* c)
+{
+    int rc = check_common(c);
+    if (rc) return rc;
+    if (c->gate_mode < 0 || c->gate_mode > 2) return SPARSEK_ERR_INVALID_ARG;
+    if (c->dtype != SPARSEK_F32 && c->dtype != SPARSEK_BF16) return SPARSEK_ERR_UNSUPPORTED;
+    if (c->d < 4 || c->d > 128 || (c->d % 4) != 0) return SPARSEK_ERR_UNSUPPORTED;
+    if (!(c->softmax_scale == c->softmax_scale)) return SPARSEK_ERR_INVALID_ARG;
+    return SPARSEK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sparsek_strerror(int code)
+{
+    switch (code) {
+        case SPARSEK_OK: return "ok";
+        case SPARSEK_ERR_INVALID_ARG: return "invalid argument";
+        case SPARSEK_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+        case SPARSEK_ERR_WORKSPACE: return "workspace or state buffer too small";
+        case SPARSEK_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown error";
+    }
+}
+
+size_t sparsek_mask_workspace_bytes(const sparsek_cfg* cfg)
+{
+    if (check_common(cfg)) return 0;
+    return mask_ws_bytes(*cfg);
+}
+
+int sparsek_mask(const sparsek_cfg* cfg, const float* u, float* tau, int32_t* death, void* ws,
+                 size_t ws_bytes, void* stream)
+{
+    int rc = check_common(cfg);
+    if (rc) return rc;
+    if (!u || !tau || !death || !ws) return SPARSEK_ERR_INVALID_ARG;
+    if (ws_bytes < mask_ws_bytes(*cfg)) return SPARSEK_ERR_WORKSPACE;
+    return launch_mask(*cfg, u, tau, death, ws, (hipStream_t)stream);
+}
+
+int sparsek_materialize(const sparsek_cfg* cfg, const float* u, const float* tau, const int32_t* death,
+                        int32_t t_begin, int32_t t_end, int32_t* idx, float* gate, void* stream)
+{
+    int rc = check_common(cfg);
+    if (rc) return rc;
+    if (!u || !tau || !death || !idx) return SPARSEK_ERR_INVALID_ARG;
+    if (t_begin < 0 || t_end < t_begin || t_end > cfg->n) return SPARSEK_ERR_INVALID_ARG;
+    if (t_end - t_begin > 65535 * 16) return SPARSEK_ERR_UNSUPPORTED;
+    return launch_materialize(*cfg, u, tau, death, t_begin, t_end, idx, gate, (hipStream_t)stream);
+}
+
+size_t sparsek_attn_fwd_workspace_bytes(const sparsek_cfg* cfg)
+{
+    if (check_attn(cfg)) return 0;
+    return attn_fwd_ws_bytes(*cfg);
+}
+
+int sparsek_attn_fwd(const sparsek_cfg* cfg, const void* q, const void* k, const void* v, const float* u,
+                     const float* tau, const int32_t* death, void* o, float* lse, void* ws,
+                     size_t ws_bytes, void* stream)
+{
+    int rc = check_attn(cfg);
+    if (rc) return rc;
+    if (!q || !k || !v || !u || !tau || !death || !o || !ws) return SPARSEK_ERR_INVALID_ARG;
+    if (ws_bytes < attn_fwd_ws_bytes(*cfg)) return SPARSEK_ERR_WORKSPACE;
+    return launch_attn_fwd(*cfg, q, k, v, u, tau, death, o, lse, ws, (hipStream_t)stream);
+}
+
+}  // extern "C"
+
+// ---- entry points whose kernels live in mask_bwd.hip and decode.hip ----
+namespace spk {
+size_t decode_state_bytes(const sparsek_decode_cfg& c);
+int launch_decode_init(const sparsek_decode_cfg& c, void* state, hipStream_t st);
+int launch_decode_load(const sparsek_decode_cfg& c, void* state, int n_ctx, const void* k, const void* v,
+                       const float* u, const float* tau, const int32_t* death, hipStream_t st);
+int launch_decode_step(const sparsek_decode_cfg& c, void* state, const void* q, const void* k, const void* v,
+                       const float* u_new, void* o, hipStream_t st);
+int decode_status(const sparsek_decode_cfg& c, const void* state, int32_t* host_flags, hipStream_t st);
+}  // namespace spk
+
+namespace {
+int check_decode(const sparsek_decode_cfg* c)
+{
+    if (!c) return SPARSEK_ERR_INVALID_ARG;
+    if (c->B < 1 || c->H < 1 || c->k < 0 || c->w < 0 || c->k + c->w < 1 || c->cand_cap < 0)
+        return SPARSEK_ERR_INVALID_ARG;
+    if (c->Gu != 1 && c->Gu != c->H) return SPARSEK_ERR_INVALID_ARG;
+    if (c->gate_mode < 0 || c->gate_mode > 2) return SPARSEK_ERR_INVALID_ARG;
+    if (c->dtype != SPARSEK_F32 && c->dtype != SPARSEK_BF16) return SPARSEK_ERR_UNSUPPORTED;
+    if (c->d < 8 || c->d > 128 || (c->d % 8) != 0) return SPARSEK_ERR_UNSUPPORTED;
+    if ((long long)c->B * c->H > (1 << 24)) return SPARSEK_ERR_UNSUPPORTED;
+    if (!(c->softmax_scale == c->softmax_scale)) return SPARSEK_ERR_INVALID_ARG;
+    return SPARSEK_OK;
+}
+}  // namespace
+
+extern "C" {
+
+size_t sparsek_mask_bwd_workspace_bytes(const sparsek_cfg* cfg)
+{
+    if (check_attn(cfg)) return 0;
+    return mask_bwd_ws_bytes(*cfg);
+}
+
+int sparsek_mask_bwd(const sparsek_cfg* cfg, const void* q, const void* k, const void* v, const float* u,
+                     const float* tau, const int32_t* death, const void* o, const float* lse, const void* dO,
+                     float* du, void* ws, size_t ws_bytes, void* stream)
+{
+    int rc = check_attn(cfg);
+    if (rc) return rc;
+    if (!q || !k || !v || !u || !tau || !death || !o || !lse || !dO || !du || !ws)
+        return SPARSEK_ERR_INVALID_ARG;
+    if (ws_bytes < mask_bwd_ws_bytes(*cfg)) return SPARSEK_ERR_WORKSPACE;
+    return launch_mask_bwd(*cfg, q, k, v, u, tau, death, o, lse, dO, du, ws, (hipStream_t)stream);
+}
+
+size_t sparsek_decode_state_bytes(const sparsek_decode_cfg* cfg)
+{
+    if (check_decode(cfg)) return 0;
+    return decode_state_bytes(*cfg);
+}
+
+int sparsek_decode_init(const sparsek_decode_cfg* cfg, void* state, size_t state_bytes, void* stream)
+{
+    int rc = check_decode(cfg);
+    if (rc) return rc;
+    if (!state) return SPARSEK_ERR_INVALID_ARG;
+    if (state_bytes < decode_state_bytes(*cfg)) return SPARSEK_ERR_WORKSPACE;
+    return launch_decode_init(*cfg, state, (hipStream_t)stream);
+}
+
+int sparsek_decode_load(const sparsek_decode_cfg* cfg, void* state, size_t state_bytes, int32_t n_ctx,
+                        const void* k, const void* v, const float* u, const float* tau, const int32_t* death,
+                        void* stream)
+{
+    int rc = check_decode(cfg);
+    if (rc) return rc;
+    if (!state || n_ctx < 0) return SPARSEK_ERR_INVALID_ARG;
+    if (n_ctx > 0 && (!k || !v || !u || !tau || !death)) return SPARSEK_ERR_INVALID_ARG;
+    if (state_bytes < decode_state_bytes(*cfg)) return SPARSEK_ERR_WORKSPACE;
+    if (n_ctx == 0) return launch_decode_init(*cfg, state, (hipStream_t)stream);
+    return launch_decode_load(*cfg, state, n_ctx, k, v, u, tau, death, (hipStream_t)stream);
+}
+
+int sparsek_decode_step(const sparsek_decode_cfg* cfg, void* state, const void* q_new, const void* k_new,
+                        const void* v_new, const float* u_new, void* o, void* stream)
+{
+    int rc = check_decode(cfg);
+    if (rc) return rc;
+    if (!state || !q_new || !k_new || !v_new || !u_new || !o) return SPARSEK_ERR_INVALID_ARG;
+    return launch_decode_step(*cfg, state, q_new, k_new, v_new, u_new, o, (hipStream_t)stream);
+}
+
+int sparsek_decode_status(const sparsek_decode_cfg* cfg, const void* state, int32_t* host_flags, void* stream)
+{
+    int rc = check_decode(cfg);
+    if (rc) return rc;
+    if (!state || !host_flags) return SPARSEK_ERR_INVALID_ARG;
+    return decode_status(*cfg, state, host_flags, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -71,8 +71,8 @@ def make(config, Gu=1, seed=None, with_dO=False, **override):
     """Host-side inputs of one configuration (optionally shrunk through ``override``).
 
     Returns a dict: shape parameters, ``scale`` (softmax scale, 1.0: the recipes already
-    divide q,k by sqrt(d) or 8), storage arrays ``q,k,v[,dO]`` (fp32 or uint16 bf16 bits)
-    and their fp32 values ``q32,k32,v32[,dO32]``, and ``u`` [B,Gu,n] fp32.
+    divide q,k by sqrt(d) or 8), storage arrays ``Q,K,V[,dO]`` (fp32 or uint16 bf16 bits)
+    and their fp32 values ``Q32,K32,V32[,dO32]``, and ``u`` [B,Gu,n] fp32.
     """
     p = dict(CONFIGS[config])
     p.update(override)
@@ -83,7 +83,7 @@ def make(config, Gu=1, seed=None, with_dO=False, **override):
     out = dict(p)
     out.update(Gu=Gu, seed=seed, scale=1.0)
     div = np.float32(p["qk_div"])
-    for name in ("q", "k", "v"):
+    for name in ("Q", "K", "V"):
         x = rng.standard_normal((B, H, n, d), dtype=np.float32) / div
         out[name], out[name + "32"] = _store(x, p["dtype"])
     out["u"] = draw_scores(rng, p["scores"], B, Gu, n, p.get("hidden", 768))
@@ -94,12 +94,12 @@ def make(config, Gu=1, seed=None, with_dO=False, **override):
 
 
 def decode_steps(config, B, H, Gu, d, steps, seed, dtype="bf16", qk_div=None):
-    """Per-step decode inputs: q_new,k_new,v_new [steps,B,H,d] and u_new [steps,B,Gu]."""
+    """Per-step decode inputs: Q,K,V [steps,B,H,d] (+ their fp32 values Q32,K32,V32) and u [steps,B,Gu]."""
     p = CONFIGS[config]
     div = np.float32(qk_div if qk_div is not None else p["qk_div"])
     rng = np.random.default_rng(seed)
     out = {}
-    for name in ("q", "k", "v"):
+    for name in ("Q", "K", "V"):
         x = rng.standard_normal((steps, B, H, d), dtype=np.float32) / div
         out[name], out[name + "32"] = _store(x, dtype)
     out["u"] = rng.standard_normal((steps, B, Gu), dtype=np.float32)

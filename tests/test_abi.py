@@ -1,0 +1,44 @@
+"""The C-ABI library loads without a GPU and exports every symbol the header declares."""
+import ctypes
+import os
+import re
+
+import paper_2406_16747_amd as spk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sparsek.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sparsek_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(spk.lib_path()):
+        from paper_2406_16747_amd import build
+
+        build.build()
+    L = ctypes.CDLL(spk.lib_path())
+    names = declared_symbols()
+    assert len(names) >= 12
+    for name in names:
+        assert hasattr(L, name), name
+
+
+def test_argument_validation_needs_no_gpu():
+    L = spk.lib()
+    cfg = spk.SparsekCfg(B=1, H=2, Gu=1, n=16, d=64, k=4, w=4, dtype=spk.BF16, gate_mode=0, softmax_scale=1.0)
+    null = ctypes.c_void_p(0)
+    assert L.sparsek_mask(ctypes.byref(cfg), null, null, null, null, 0, null) == -1
+    assert L.sparsek_mask_workspace_bytes(ctypes.byref(cfg)) > 0
+    bad = spk.SparsekCfg(B=1, H=2, Gu=3, n=16, d=64, k=4, w=4, dtype=spk.BF16, gate_mode=0, softmax_scale=1.0)
+    assert L.sparsek_mask_workspace_bytes(ctypes.byref(bad)) == 0
+    one = ctypes.c_void_p(256)  # never dereferenced: validation fails first
+    assert L.sparsek_mask(ctypes.byref(bad), one, one, one, one, 1 << 20, null) == -1
+    bad = spk.SparsekCfg(B=1, H=2, Gu=1, n=16, d=64, k=0, w=0, dtype=spk.BF16, gate_mode=0, softmax_scale=1.0)
+    assert L.sparsek_attn_fwd(ctypes.byref(bad), *([one] * 8), one, 1 << 20, null) == -1
+    bad = spk.SparsekCfg(B=1, H=2, Gu=1, n=16, d=96 + 1, k=1, w=0, dtype=spk.BF16, gate_mode=0, softmax_scale=1.0)
+    assert L.sparsek_attn_fwd(ctypes.byref(bad), *([one] * 8), one, 1 << 20, null) == -2
+    assert L.sparsek_attn_fwd(ctypes.byref(cfg), *([one] * 8), one, 8, null) == -3
+    assert b"workspace" in L.sparsek_strerror(-3)

@@ -1,0 +1,89 @@
+"""GPU parity of stage 3 (sparsek_attn_fwd) against the CPU oracle.
+
+Bars: bf16 outputs max abs err <= 1e-2 against the fp64 oracle, plus a self-imposed
+relative bar max|err| <= 2^-7 max|ref| (the 1e-2 bar alone is looser than the signal for
+the 1/sqrt(d)-scaled recipes); fp32 outputs <= 2e-5 relative to max|ref|.
+A second pass with unscaled q,k (peaky softmax) makes wrong gates or indices visible.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2406_16747_amd as spk
+from paper_2406_16747_amd import synth
+from gpu_util import dev, host, require_gpu, say
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(oracle, inp, gate_mode=0, scale=None, heads=None, rows=None, qk_boost=1.0):
+    """Runs the GPU path on the whole input and the oracle on `heads` (list of (b,h)) and
+    query rows `rows` (None = all)."""
+    B, H, n, d, k, w, Gu = (inp[x] for x in ("B", "H", "n", "d", "k", "w", "Gu"))
+    bf16 = inp["dtype"] == "bf16"
+    scale = inp["scale"] if scale is None else scale
+    u = inp["u"]
+    ud = dev(u)
+    tau_g, death_g = spk.sparsek_mask(ud, k)
+    q, kk, v = (dev(inp[x], bf16) for x in ("Q", "K", "V"))
+    q32, k32 = inp["Q32"], inp["K32"]
+    if qk_boost != 1.0:  # exact in bf16 for powers of two
+        q = (q.float() * qk_boost).to(q.dtype)
+        q32 = q32 * np.float32(qk_boost)
+    o_g, lse_g = spk.sparsek_attn_fwd(q, kk, v, ud, tau_g, death_g, k, w, gate_mode, scale)
+    torch.cuda.synchronize()
+    o_g, lse_g = host(o_g), host(lse_g)
+    assert np.isfinite(o_g).all() and np.isfinite(lse_g).all()
+    heads = heads if heads is not None else [(b, h) for b in range(B) for h in range(H)]
+    worst = 0.0
+    for (b, h) in heads:
+        g = 0 if Gu == 1 else h
+        tau_r = oracle.tau_prefixes(u[b, g], k)[0]
+        death_r = oracle.death(u[b, g], k)
+        np.testing.assert_array_equal(host(death_g)[b, g], death_r)
+        spans = [(0, n)] if rows is None else rows
+        for (a, e) in spans:
+            o_r, lse_r = oracle.attn_rows(q32[b, h], k32[b, h], inp["V32"][b, h], u[b, g], tau_r, death_r, k, w,
+                                          gate_mode, scale, a, e)
+            err = np.abs(o_g[b, h, a:e] - o_r).max()
+            ref = np.abs(o_r).max()
+            if bf16:
+                assert err <= 1e-2, (b, h, a, err)
+                assert err <= ref * 2.0 ** -7 + 1e-6, (b, h, a, err, ref)
+            else:
+                assert err <= 2e-5 * max(ref, 1e-3), (b, h, a, err, ref)
+            np.testing.assert_allclose(lse_g[b, h, a:e], lse_r, atol=2e-3 if bf16 else 1e-4, rtol=1e-4)
+            worst = max(worst, err / max(ref, 1e-30))
+    return worst
+
+
+@pytest.mark.parametrize("gate_mode", [0, 1, 2])
+def test_config1_fp32(oracle, gate_mode):
+    require_gpu()
+    say("attn config 1 mode", gate_mode)
+    inp = synth.make(1)
+    run_case(oracle, inp, gate_mode)
+    run_case(oracle, inp, gate_mode, qk_boost=8.0)
+
+
+@pytest.mark.parametrize("n,d,k,w,Gu,dtype", [
+    (1, 64, 4, 4, 1, "bf16"), (7, 64, 2, 3, 1, "bf16"), (300, 64, 16, 0, 1, "bf16"),
+    (333, 128, 0, 40, 1, "bf16"), (700, 128, 50, 130, 2, "bf16"), (515, 64, 600, 5, 1, "bf16"),
+    (450, 32, 20, 33, 2, "fp32"), (129, 128, 1, 1, 1, "fp32"),
+])
+@pytest.mark.parametrize("gate_mode", [0, 1])
+def test_small_shapes(oracle, n, d, k, w, Gu, dtype, gate_mode):
+    require_gpu()
+    say("attn small", n, d, k, w, Gu, dtype, gate_mode)
+    inp = synth.make(1, Gu=Gu, seed=n * 7 + k, B=2, H=2, n=n, d=d, k=k, w=w, dtype=dtype, qk_div=float(np.sqrt(d)))
+    run_case(oracle, inp, gate_mode)
+    run_case(oracle, inp, gate_mode, qk_boost=8.0)
+
+
+def test_config2_shape_reduced_batch(oracle):
+    """Config 2 recipe (scores from a linear scorer on a hidden state) at B=1, 3 heads."""
+    require_gpu()
+    say("attn config 2 (reduced batch)")
+    inp = synth.make(2, B=1, H=3)
+    run_case(oracle, inp, 0)
+    run_case(oracle, inp, 1, qk_boost=8.0, heads=[(0, 1)])
