@@ -167,6 +167,353 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------
+// MFMA kernel (bf16 storage, D = 64 or 128).  One workgroup = 128 queries x 4 waves; each
+// wave owns 32 queries and walks the block's key set in tiles of 64 keys:
+//   S^T (keys x queries) = K_tile . Q^T     v_mfma_f32_32x32x16_bf16, K rows from LDS
+//   online softmax down the key axis: every lane owns one query column, so row maxima and
+//   sums stay inside a lane (one exchange with the lane holding the other half of the keys)
+//   O^T (d x queries)   += V_tile^T . P^T   V is written to LDS transposed so that the key
+//   axis is contiguous for the A operand; P^T feeds the B operand straight from registers.
+// K/V rows are gathered from HBM by position with 16-byte/8-byte coalesced loads into
+// registers one tile ahead of the compute.
+// ---------------------------------------------------------------------------------
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int KT = 64;     // keys per tile
+constexpr int SEG = 2304;  // keys whose metadata is staged in LDS at a time (36 tiles)
+
+template <int D>
+struct MfmaSmem {
+    uint16_t Ks[KT][D + 8];   // K tile, row-major, rows padded by 16 bytes
+    uint16_t Vt[D][KT + 4];   // V tile transposed, rows padded by 8 bytes
+    int32_t jpos[SEG];        // key position
+    int32_t jlast[SEG];       // last query that attends the key: w - 1 + death[j]; -1 = padding
+    float ju[SEG];            // key score
+    int32_t tile_lmin[SEG / KT];
+};
+
+template <int D>
+__device__ __forceinline__ void load_tile(const int32_t* jp, const uint16_t* __restrict__ kh,
+                                          const uint16_t* __restrict__ vh, int tid,
+                                          u32x4 (&kpre)[KT * (D / 8) / 256],
+                                          u32x2 (&vpre)[(KT / 4) * (D / 4) / 256][4])
+{
+    constexpr int KCH = D / 8;
+#pragma unroll
+    for (int x = 0; x < KT * KCH / 256; x++) {
+        const int c = tid + 256 * x;
+        const int r = c / KCH, cc = c % KCH;
+        kpre[x] = *(const u32x4*)(kh + (size_t)jp[r] * D + 8 * cc);
+    }
+#pragma unroll
+    for (int x = 0; x < (KT / 4) * (D / 4) / 256; x++) {
+        const int un = tid + 256 * x;
+        const int dch = un % (D / 4), kg = un / (D / 4);
+#pragma unroll
+        for (int a2 = 0; a2 < 4; a2++)
+            vpre[x][a2] = *(const u32x2*)(vh + (size_t)jp[4 * kg + a2] * D + 4 * dch);
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void store_tile(uint16_t (&Ks)[KT][D + 8], uint16_t (&Vt)[D][KT + 4], int tid,
+                                           const u32x4 (&kpre)[KT * (D / 8) / 256],
+                                           const u32x2 (&vpre)[(KT / 4) * (D / 4) / 256][4])
+{
+    constexpr int KCH = D / 8;
+#pragma unroll
+    for (int x = 0; x < KT * KCH / 256; x++) {
+        const int c = tid + 256 * x;
+        const int r = c / KCH, cc = c % KCH;
+        *(u32x4*)&Ks[r][8 * cc] = kpre[x];
+    }
+#pragma unroll
+    for (int x = 0; x < (KT / 4) * (D / 4) / 256; x++) {
+        const int un = tid + 256 * x;
+        const int dch = un % (D / 4), kg = un / (D / 4);
+        const u32x2 r0 = vpre[x][0], r1 = vpre[x][1], r2 = vpre[x][2], r3 = vpre[x][3];
+        u32x2 t0, t1, t2, t3;  // 4x4 transpose of 16-bit values: t_e = column e of the 4 key rows
+        t0.x = (r0.x & 0xFFFFu) | (r1.x << 16);
+        t0.y = (r2.x & 0xFFFFu) | (r3.x << 16);
+        t1.x = (r0.x >> 16) | (r1.x & 0xFFFF0000u);
+        t1.y = (r2.x >> 16) | (r3.x & 0xFFFF0000u);
+        t2.x = (r0.y & 0xFFFFu) | (r1.y << 16);
+        t2.y = (r2.y & 0xFFFFu) | (r3.y << 16);
+        t3.x = (r0.y >> 16) | (r1.y & 0xFFFF0000u);
+        t3.y = (r2.y >> 16) | (r3.y & 0xFFFF0000u);
+        *(u32x2*)&Vt[4 * dch + 0][4 * kg] = t0;
+        *(u32x2*)&Vt[4 * dch + 1][4 * kg] = t1;
+        *(u32x2*)&Vt[4 * dch + 2][4 * kg] = t2;
+        *(u32x2*)&Vt[4 * dch + 3][4 * kg] = t3;
+    }
+}
+
+template <int D, int MODE>
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ kk, const uint16_t* __restrict__ v,
+    const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
+    const int32_t* __restrict__ lists, const int32_t* __restrict__ counts, uint16_t* __restrict__ o,
+    float* __restrict__ lse, int H, int Gu, int n, int k, int w, float scale, int nb, int BH)
+{
+    __shared__ __align__(16) MfmaSmem<D> sm;
+    constexpr int DS = D / 16;   // MFMA k-steps over the head dim
+    constexpr int DB = D / 32;   // 32-row blocks of O^T
+    constexpr int KLD = KT * (D / 8) / 256;        // 16-byte K chunks per thread per tile
+    constexpr int VUN = (KT / 4) * (D / 4) / 256;  // V 4x4 units per thread per tile
+
+    // ---- block -> (head, query block): heads are dealt to the 8 XCDs so that one head's
+    // blocks share an L2; late (long) blocks go first
+    int bh, blk;
+    {
+        const int id = blockIdx.x;
+        if (BH % 8 == 0) {
+            const int xcd = id & 7, slot = id >> 3;
+            bh = (slot / nb) * 8 + xcd;
+            blk = nb - 1 - (slot % nb);
+        } else {
+            bh = id / nb;
+            blk = nb - 1 - (id % nb);
+        }
+    }
+    const int b = bh / H, h = bh % H;
+    const int row = b * Gu + (Gu == 1 ? 0 : h);
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int half = lane >> 5, col = lane & 31;
+    const int i0 = blk * QB;
+    const uint16_t* qh = q + (size_t)bh * n * D;
+    const uint16_t* kh = kk + (size_t)bh * n * D;
+    const uint16_t* vh = v + (size_t)bh * n * D;
+    const float* ur = u + (size_t)row * n;
+    const float* tr = tau + (size_t)row * n;
+    const int32_t* dr = death + (size_t)row * n;
+    const int32_t* list = lists + ((size_t)row * nb + blk) * (size_t)(k > 0 ? k : 1);
+    const int cnt = counts[(size_t)row * nb + blk];
+    const int c0 = max(0, i0 - w + 1);
+    const int c_end = min(n - 1, i0 + QB - 1);
+    const int nkl = (cnt + KT - 1) / KT * KT;                // list part, padded to whole tiles
+    const int nkc = (c_end - c0 + 1 + KT - 1) / KT * KT;     // contiguous part, padded
+    const int nk_total = nkl + nkc;
+
+    // ---- this wave's queries ----
+    const int qa = i0 + 32 * wv;          // first query of the wave
+    const int qb = min(qa + 31, n - 1);   // last real query of the wave
+    const int qi = qa + col;              // this lane's query
+    const bool wave_live = qa < n;
+    const int qrow = min(qi, n - 1);
+    const float tau_q = (qi < n && qi - w >= 0) ? tr[qi - w] : 0.0f;
+    bf16x8 qreg[DS];
+#pragma unroll
+    for (int s = 0; s < DS; s++)
+        qreg[s] = *(const bf16x8*)(qh + (size_t)qrow * D + 16 * s + 8 * half);
+
+    f32x16 acc_o[DB];
+#pragma unroll
+    for (int x = 0; x < DB; x++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc_o[x][r] = 0.0f;
+    float m_run = -INFINITY, l_run = 0.0f;
+    const float c2 = scale * 1.4426950408889634f;
+
+    u32x4 kpre[KLD];
+    u32x2 vpre[VUN][4];
+
+    for (int seg0 = 0; seg0 < nk_total; seg0 += SEG) {
+        const int seg_n = min(SEG, nk_total - seg0);
+        __syncthreads();  // previous segment fully consumed
+        for (int e = tid; e < seg_n; e += 256) {
+            const int E = seg0 + e;
+            int j = 0;
+            bool real;
+            if (E < nkl) {
+                real = E < cnt;
+                if (real) j = list[E];
+            } else {
+                j = c0 + (E - nkl);
+                real = j <= c_end;
+                if (!real) j = 0;
+            }
+            sm.jpos[e] = j;
+            sm.jlast[e] = real ? (w - 1 + dr[j]) : -1;
+            sm.ju[e] = real ? ur[j] : 0.0f;
+        }
+        __syncthreads();
+        for (int t = wv; t < seg_n / KT; t += 4) {
+            int lm = sm.jlast[t * KT + lane];
+#pragma unroll
+            for (int o2 = 32; o2 > 0; o2 >>= 1) lm = min(lm, __shfl_xor(lm, o2, 64));
+            if (lane == 0) sm.tile_lmin[t] = lm;
+        }
+        // (visibility of tile_lmin is covered by the barriers of the tile loop)
+
+        const int ntiles = seg_n / KT;
+        __syncthreads();
+        load_tile<D>(sm.jpos, kh, vh, tid, kpre, vpre);
+        for (int t = 0; t < ntiles; t++) {
+            __syncthreads();  // tile t-1 fully read
+            store_tile<D>(sm.Ks, sm.Vt, tid, kpre, vpre);
+            __syncthreads();
+            if (t + 1 < ntiles) load_tile<D>(sm.jpos + (t + 1) * KT, kh, vh, tid, kpre, vpre);
+
+            // ---- does this wave see anything of the tile? ----
+            const int base = t * KT;
+            const int E0 = seg0 + base;
+            const bool is_list = E0 < nkl;
+            const int jbase = is_list ? 0 : c0 + (E0 - nkl);  // first position of a contiguous tile
+            const int lmin = sm.tile_lmin[t];
+            bool skip = !wave_live;
+            bool fast = false;  // every pair valid with gate 1
+            bool nomask = false;  // every pair valid (gates still apply)
+            if (is_list) {
+                nomask = lmin >= qb;
+            } else {
+                if (jbase > qb) skip = true;                       // all keys in the future
+                const int jend = jbase + KT - 1;
+                if (jend <= qa && qb - jbase < w && jend <= c_end) fast = true;  // inside every window
+            }
+            if (skip) continue;
+
+            // ---- S^T = K . Q^T ----
+            f32x16 acc_s[2];
+#pragma unroll
+            for (int mb = 0; mb < 2; mb++) {
+#pragma unroll
+                for (int r = 0; r < 16; r++) acc_s[mb][r] = 0.0f;
+#pragma unroll
+                for (int s = 0; s < DS; s++) {
+                    const bf16x8 a = *(const bf16x8*)&sm.Ks[32 * mb + col][16 * s + 8 * half];
+                    acc_s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], acc_s[mb], 0, 0, 0);
+                }
+            }
+
+            // ---- gates, masks, online softmax (log2 domain) ----
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int mb = 0; mb < 2; mb++) {
+#pragma unroll
+                for (int g4 = 0; g4 < 4; g4++) {
+                    const int kb = 32 * mb + 8 * g4 + 4 * half;  // first of 4 consecutive keys
+                    int4 L4 = make_int4(0, 0, 0, 0);
+                    float4 U4 = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (!fast) {
+                        L4 = *(const int4*)&sm.jlast[base + kb];
+                        if (MODE == 0) U4 = *(const float4*)&sm.ju[base + kb];
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
+                        const int r = 4 * g4 + e;
+                        float s2 = acc_s[mb][r] * c2;
+                        if (!fast) {
+                            const int Lj = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
+                            const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
+                            bool valid;
+                            if (is_list) {
+                                valid = nomask || (qi <= Lj);
+                                if (MODE == 0) s2 *= clip01(uj - tau_q);
+                            } else {
+                                const int j = jbase + kb + e;
+                                valid = (j <= qi) && (qi <= Lj);
+                                if (MODE == 0) s2 *= (qi - j < w) ? 1.0f : clip01(uj - tau_q);
+                            }
+                            s2 = valid ? s2 : -INFINITY;
+                        }
+                        acc_s[mb][r] = s2;
+                        tmax = fmaxf(tmax, s2);
+                    }
+                }
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            const float m_new = fmaxf(m_run, tmax);
+            const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+            const float alpha = exp2f(m_run - m_safe);
+            m_run = m_new;
+            float psum = 0.0f;
+            bf16x8 pb[4];
+#pragma unroll
+            for (int mb = 0; mb < 2; mb++) {
+#pragma unroll
+                for (int g4 = 0; g4 < 4; g4++) {
+                    const int kb = 32 * mb + 8 * g4 + 4 * half;
+                    float4 U4 = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (!fast && MODE != 2) U4 = *(const float4*)&sm.ju[base + kb];
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
+                        const int r = 4 * g4 + e;
+                        const float p = exp2f(acc_s[mb][r] - m_safe);
+                        psum += p;
+                        float pvv = p;
+                        if (!fast && MODE != 2) {  // the value gate (recomputed: cheaper than keeping 32 registers)
+                            const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
+                            const float g = clip01(uj - tau_q);
+                            if (is_list) pvv = p * g;
+                            else pvv = (qi - (jbase + kb + e) < w) ? p : p * g;
+                        }
+                        pb[2 * mb + (r >> 3)][r & 7] = (__bf16)pvv;
+                    }
+                }
+            }
+            l_run = l_run * alpha + psum;
+            if (__any(alpha != 1.0f)) {
+#pragma unroll
+                for (int x = 0; x < DB; x++)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) acc_o[x][r] *= alpha;
+            }
+
+            // ---- O^T += V^T . P^T ----
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+#pragma unroll
+                for (int x = 0; x < DB; x++) {
+                    const bf16x4 lo4 = *(const bf16x4*)&sm.Vt[32 * x + col][16 * g + 4 * half];
+                    const bf16x4 hi4 = *(const bf16x4*)&sm.Vt[32 * x + col][16 * g + 8 + 4 * half];
+                    const bf16x8 a = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+                    acc_o[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[g], acc_o[x], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // ---- epilogue: O = O^T / l, lse ----
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    if (qi < n) {
+        const float inv = 1.0f / l_tot;
+        uint16_t* orow = o + ((size_t)bh * n + qi) * D;
+#pragma unroll
+        for (int x = 0; x < DB; x++) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; g4++) {
+                bf16x4 pk;
+#pragma unroll
+                for (int e = 0; e < 4; e++) pk[e] = (__bf16)(acc_o[x][4 * g4 + e] * inv);
+                *(bf16x4*)(orow + 32 * x + 8 * g4 + 4 * half) = pk;
+            }
+        }
+        if (lse && half == 0) lse[(size_t)bh * n + qi] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+    }
+}
+
+template <int D>
+static void launch_mfma(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
+                        const float* tau, const int32_t* death, const int32_t* lists, const int32_t* counts,
+                        void* o, float* lse, int nb, hipStream_t st)
+{
+    const int BH = c.B * c.H;
+    dim3 grid(nb * BH);
+#define SPK_LAUNCH(MODE)                                                                                   \
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q,        \
+                       (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, (uint16_t*)o, \
+                       lse, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH)
+    if (c.gate_mode == 0) SPK_LAUNCH(0);
+    else if (c.gate_mode == 1) SPK_LAUNCH(1);
+    else SPK_LAUNCH(2);
+#undef SPK_LAUNCH
+}
+
 int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                     const float* tau, const int32_t* death, void* o, float* lse, void* ws,
                     hipStream_t st)
@@ -178,6 +525,11 @@ int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const vo
         (int32_t*)((char*)ws + align_up((size_t)rows * nb * (size_t)(c.k > 0 ? c.k : 1) * sizeof(int32_t), 256));
     hipLaunchKernelGGL(block_lists_kernel, dim3(nb, rows), dim3(256), 0, st, death, c.n, c.k, c.w, nb, lists,
                        counts);
+    if (c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128)) {
+        if (c.d == 64) launch_mfma<64>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, st);
+        else launch_mfma<128>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, st);
+        return launch_status();
+    }
     dim3 grid(nb, c.B * c.H);
     if (c.dtype == SPARSEK_F32) {
         hipLaunchKernelGGL(attn_fwd_generic_kernel<float>, grid, dim3(256), 0, st, (const float*)q,
