@@ -354,6 +354,7 @@ int orc_mask_bwd_head(const float *q, const float *K, const float *V, const floa
     double *o = (double *)malloc(sizeof(double) * (size_t)d);
     for (int i = w; i < n && k > 0 && gate_mode != 2; i++) {
         int T = i - w;
+        if (T + 1 <= k) continue; /* prefix with at most k entries: every gate is 1 by definition, S* is empty */
         int nk = build_keys(u, tau, death, i, k, w, keys, gates);
         attend_list(q + (size_t)i * d, K, V, d, keys, gates, nk, gate_mode, scale, o, NULL, p, qk);
         const float *dOi = dO + (size_t)i * d;

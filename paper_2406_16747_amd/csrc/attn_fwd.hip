@@ -17,14 +17,18 @@ constexpr int QB = 128;  // queries per block (shared by the list builder and th
 
 static inline int nblocks(int n) { return (n + QB - 1) / QB; }
 
-size_t attn_fwd_ws_bytes(const sparsek_cfg& c)
+// Workspace of the per-block top-k lists: lists [rows][nb][max(k,1)] int32, then counts [rows][nb].
+size_t block_lists_bytes(const sparsek_cfg& c, size_t* counts_offset)
 {
     size_t rows = (size_t)c.B * c.Gu;
     size_t nb = nblocks(c.n);
     size_t lists = align_up(rows * nb * (size_t)(c.k > 0 ? c.k : 1) * sizeof(int32_t), 256);
     size_t counts = align_up(rows * nb * sizeof(int32_t), 256);
+    if (counts_offset) *counts_offset = lists;
     return lists + counts;
 }
+
+size_t attn_fwd_ws_bytes(const sparsek_cfg& c) { return block_lists_bytes(c, nullptr); }
 
 // ---------------------------------------------------------------------------------
 // Per (row, block): ascending positions of the top-k of prefix T0 = blk*QB - w.
@@ -514,17 +518,24 @@ static void launch_mfma(const sparsek_cfg& c, const void* q, const void* k, cons
 #undef SPK_LAUNCH
 }
 
+void launch_block_lists(const sparsek_cfg& c, const int32_t* death, int32_t* lists, int32_t* counts,
+                        hipStream_t st)
+{
+    const int nb = nblocks(c.n);
+    hipLaunchKernelGGL(block_lists_kernel, dim3(nb, c.B * c.Gu), dim3(256), 0, st, death, c.n, c.k, c.w, nb,
+                       lists, counts);
+}
+
 int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                     const float* tau, const int32_t* death, void* o, float* lse, void* ws,
                     hipStream_t st)
 {
-    const int rows = c.B * c.Gu;
     const int nb = nblocks(c.n);
+    size_t coff = 0;
+    block_lists_bytes(c, &coff);
     int32_t* lists = (int32_t*)ws;
-    int32_t* counts =
-        (int32_t*)((char*)ws + align_up((size_t)rows * nb * (size_t)(c.k > 0 ? c.k : 1) * sizeof(int32_t), 256));
-    hipLaunchKernelGGL(block_lists_kernel, dim3(nb, rows), dim3(256), 0, st, death, c.n, c.k, c.w, nb, lists,
-                       counts);
+    int32_t* counts = (int32_t*)((char*)ws + coff);
+    launch_block_lists(c, death, lists, counts, st);
     if (c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128)) {
         if (c.d == 64) launch_mfma<64>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, st);
         else launch_mfma<128>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, st);

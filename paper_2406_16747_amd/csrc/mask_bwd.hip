@@ -1,11 +1,281 @@
-// SPARSEK mask backward (gradient of sum(dO*O) w.r.t. the scores): placeholder until the
-// fused kernel lands -- reports "unsupported" instead of computing anything.
+// SPARSEK mask backward: du = gradient of L = sum(dO * O) w.r.t. the scores (App. A.3).
+//
+// For prefix T (query i = T + w) the Jacobian-vector product is s * (g - mean_{S*} g) with
+// S*_T = {j <= T : tau_T < u_j < tau_T + 1} and g_j = dL/dm_ij (0 outside the hard top-k).
+// Summed over T:   du_j = C_j - sum_{T : j in S*_T} A_T / |S*_T|
+//   C_j = sum_i g_ij [j in S*_{i-w}]   column sums   } accumulated by the main kernel while it
+//   A_T = sum_j g_{T+w,j} [j in S*_T]  row sums      } recomputes p_ij from q, k, lse (one pass)
+// Because tau_T does not decrease once the prefix holds k entries, "j in S*_T" holds on one
+// contiguous range of T, found by binary search; |S*_T| and the second term then come from
+// difference arrays and prefix sums in an O(n log n) epilogue -- nothing of size n*k is stored.
+//
+//   g_ij = p_ij (dO_i.v_j)                                          value gate (modes 0, 1)
+//        + scale (q_i.k_j) p_ij (m_ij dO_i.v_j - dO_i.o_i)          key gate   (mode 0)
 #include "common.hpp"
+
 namespace spk {
-size_t mask_bwd_ws_bytes(const sparsek_cfg&) { return 256; }
-int launch_mask_bwd(const sparsek_cfg&, const void*, const void*, const void*, const float*, const float*,
-                    const int32_t*, const void*, const float*, const void*, float*, void*, hipStream_t)
+
+constexpr int QB_B = 128;  // must equal the forward's query block (the lists are shared code)
+
+// implemented in attn_fwd.hip
+void launch_block_lists(const sparsek_cfg& c, const int32_t* death, int32_t* lists, int32_t* counts,
+                        hipStream_t st);
+size_t block_lists_bytes(const sparsek_cfg& c, size_t* counts_offset);
+
+struct BwdWs {
+    size_t lists, counts, A, C, diff, G, total;
+};
+static BwdWs bwd_ws(const sparsek_cfg& c)
 {
-    return SPARSEK_ERR_UNSUPPORTED;
+    BwdWs W;
+    size_t coff = 0;
+    size_t lb = block_lists_bytes(c, &coff);
+    const size_t rows = (size_t)c.B * c.Gu;
+    W.lists = 0;
+    W.counts = coff;
+    size_t off = lb;
+    W.A = off; off += align_up(rows * c.n * 4, 256);
+    W.C = off; off += align_up(rows * c.n * 4, 256);
+    W.diff = off; off += align_up(rows * (c.n + 1) * 4, 256);
+    W.G = off; off += align_up(rows * (size_t)(c.n + 1) * 8, 256);
+    W.total = off;
+    return W;
 }
+size_t mask_bwd_ws_bytes(const sparsek_cfg& c) { return bwd_ws(c).total; }
+
+__global__ void zero_kernel(uint32_t* p, size_t nwords)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nwords; i += (size_t)gridDim.x * blockDim.x)
+        p[i] = 0u;
+}
+
+// strict membership in the fractional set, decided in fp64 (both sides exact)
+__device__ __forceinline__ bool strictly_fractional(float uj, float tauT)
+{
+    return (uj > tauT) && ((double)uj < (double)tauT + 1.0);
+}
+
+template <typename T>
+__device__ __forceinline__ float ldv(const T* p);
+template <>
+__device__ __forceinline__ float ldv<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float ldv<uint16_t>(const uint16_t* p) { return bf16_to_f32(*p); }
+
+// ---------------------------------------------------------------------------------
+// Generic main kernel: one wave per query, lanes over the selected keys.
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void mask_bwd_generic_kernel(
+    const T* __restrict__ q, const T* __restrict__ kk, const T* __restrict__ v, const float* __restrict__ u,
+    const float* __restrict__ tau, const int32_t* __restrict__ death, const int32_t* __restrict__ lists,
+    const int32_t* __restrict__ counts, const T* __restrict__ o, const float* __restrict__ lse,
+    const T* __restrict__ dO, float* __restrict__ A, float* __restrict__ C, int H, int Gu, int n, int d, int k,
+    int w, int gate_mode, float scale, int nb)
+{
+    __shared__ float qs[4][128], ds[4][128];
+    const int blk = blockIdx.x, bh = blockIdx.y;
+    const int b = bh / H, h = bh % H;
+    const int row = b * Gu + (Gu == 1 ? 0 : h);
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int i0 = blk * QB_B;
+    const T* qh = q + (size_t)bh * n * d;
+    const T* kh = kk + (size_t)bh * n * d;
+    const T* vh = v + (size_t)bh * n * d;
+    const T* oh = o + (size_t)bh * n * d;
+    const T* dh = dO + (size_t)bh * n * d;
+    const float* ur = u + (size_t)row * n;
+    const float* tr = tau + (size_t)row * n;
+    const int32_t* dr = death + (size_t)row * n;
+    const int32_t* list = lists + ((size_t)row * nb + blk) * (size_t)(k > 0 ? k : 1);
+    const int cnt = counts[(size_t)row * nb + blk];
+    const int c0 = max(0, i0 - w + 1);
+
+    for (int qi = wv; qi < QB_B; qi += 4) {
+        const int i = i0 + qi;
+        if (i >= n) break;
+        const int Tp = i - w;
+        if (Tp < k) continue;  // prefixes with at most k entries have every gate at 1: no gradient
+        float dpart = 0.0f;
+        for (int c = lane; c < d; c += 64) {
+            const float qv = ldv(qh + (size_t)i * d + c), dv = ldv(dh + (size_t)i * d + c);
+            qs[wv][c] = qv;
+            ds[wv][c] = dv;
+            dpart += dv * ldv(oh + (size_t)i * d + c);
+        }
+        const float Di = wave_sum_f32(dpart);
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        const float tauT = tr[Tp];
+        const float lse_i = lse[(size_t)bh * n + i];
+        const int n_cont = max(0, Tp - c0 + 1);  // contiguous keys already outside the window
+        const int total = cnt + n_cont;
+        float rowsum = 0.0f;
+        for (int e0 = 0; e0 < total; e0 += 64) {
+            const int e = e0 + lane;
+            float gf = 0.0f;
+            int j = -1;
+            if (e < total) {
+                j = (e < cnt) ? list[e] : c0 + (e - cnt);
+                const float uj = ur[j];
+                if (dr[j] > Tp && strictly_fractional(uj, tauT)) {
+                    const float m = clip01(uj - tauT);
+                    float qk = 0.0f, dov = 0.0f;
+                    const T* kj = kh + (size_t)j * d;
+                    const T* vj = vh + (size_t)j * d;
+                    for (int c = 0; c < d; c++) {
+                        qk += qs[wv][c] * ldv(kj + c);
+                        dov += ds[wv][c] * ldv(vj + c);
+                    }
+                    const float s = scale * qk * (gate_mode == 0 ? m : 1.0f);
+                    const float p = __expf(s - lse_i);
+                    gf = p * dov;
+                    if (gate_mode == 0) gf += scale * qk * p * (m * dov - Di);
+                }
+            }
+            if (gf != 0.0f) unsafeAtomicAdd(C + (size_t)row * n + j, gf);
+            rowsum += gf;
+        }
+        rowsum = wave_sum_f32(rowsum);
+        if (lane == 0 && rowsum != 0.0f) unsafeAtomicAdd(A + (size_t)row * n + Tp, rowsum);
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Epilogue 1: per key j the range [a_j, b_j] of prefixes T with j in S*_T; difference array
+// of |S*_T|.  tau is non-decreasing for T >= k-1, so both ends come from binary searches.
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ void frac_range(const float* tr, float uj, int j, int n, int k, int& a, int& b)
+{
+    const int lo = max(j, k);  // shorter prefixes have every gate at 1: S* empty
+    a = 1;
+    b = 0;
+    if (lo > n - 1) return;
+    // b = last T in [lo, n-1] with tau_T < u_j
+    int x = lo, y = n;  // first T with !(tau_T < u_j)
+    while (x < y) {
+        int m = (x + y) >> 1;
+        if (tr[m] < uj) x = m + 1;
+        else y = m;
+    }
+    b = x - 1;
+    // a = first T in [lo, n-1] with u_j < tau_T + 1 (fp64 compare)
+    x = lo;
+    y = n;
+    while (x < y) {
+        int m = (x + y) >> 1;
+        if ((double)uj < (double)tr[m] + 1.0) y = m;
+        else x = m + 1;
+    }
+    a = x;
+}
+
+__global__ void mask_bwd_ranges_kernel(const float* __restrict__ u, const float* __restrict__ tau, int n, int k,
+                                       int32_t* __restrict__ diff)
+{
+    const int row = blockIdx.y;
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n) return;
+    int a, b;
+    frac_range(tau + (size_t)row * n, u[(size_t)row * n + j], j, n, k, a, b);
+    if (a <= b) {
+        atomicAdd(diff + (size_t)row * (n + 1) + a, 1);
+        atomicAdd(diff + (size_t)row * (n + 1) + b + 1, -1);
+    }
+}
+
+// Epilogue 2: one workgroup per row: |S*_T| = prefix sum of diff; G_T = sum_{T'<=T} A_T'/|S*_T'| (fp64).
+__global__ __launch_bounds__(1024) void mask_bwd_scan_kernel(const float* __restrict__ A,
+                                                              const int32_t* __restrict__ diff, int n,
+                                                              double* __restrict__ G)
+{
+    __shared__ int cpart[1024];
+    __shared__ double gpart[1024];
+    const int row = blockIdx.x, tid = threadIdx.x;
+    const float* Ar = A + (size_t)row * n;
+    const int32_t* dr = diff + (size_t)row * (n + 1);
+    double* Gr = G + (size_t)row * (n + 1);  // Gr[T+1] = sum_{T'<=T}; Gr[0] = 0
+    const int per = (n + 1023) / 1024;
+    const int b = tid * per, e = min(b + per, n);
+    int c = 0;
+    for (int i = b; i < e; i++) c += dr[i];
+    cpart[tid] = c;
+    __syncthreads();
+    int cnt = 0;
+    for (int i = 0; i < tid; i++) cnt += cpart[i];
+    double g = 0.0;
+    const int cnt0 = cnt;
+    for (int i = b; i < e; i++) {
+        cnt += dr[i];
+        if (cnt > 0) g += (double)Ar[i] / (double)cnt;
+    }
+    gpart[tid] = g;
+    __syncthreads();
+    double run = 0.0;
+    for (int i = 0; i < tid; i++) run += gpart[i];
+    cnt = cnt0;
+    if (tid == 0) Gr[0] = 0.0;
+    for (int i = b; i < e; i++) {
+        cnt += dr[i];
+        if (cnt > 0) run += (double)Ar[i] / (double)cnt;
+        Gr[i + 1] = run;
+    }
+}
+
+// Epilogue 3: du_j = C_j - (G[b_j] - G[a_j - 1]).
+__global__ void mask_bwd_final_kernel(const float* __restrict__ u, const float* __restrict__ tau,
+                                      const float* __restrict__ C, const double* __restrict__ G, int n, int k,
+                                      float* __restrict__ du)
+{
+    const int row = blockIdx.y;
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n) return;
+    int a, b;
+    frac_range(tau + (size_t)row * n, u[(size_t)row * n + j], j, n, k, a, b);
+    double r = (double)C[(size_t)row * n + j];
+    if (a <= b) {
+        const double* Gr = G + (size_t)row * (n + 1);
+        r -= Gr[b + 1] - Gr[a];
+    }
+    du[(size_t)row * n + j] = (float)r;
+}
+
+int launch_mask_bwd(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
+                    const float* tau, const int32_t* death, const void* o, const float* lse, const void* dO,
+                    float* du, void* ws, hipStream_t st)
+{
+    const BwdWs W = bwd_ws(c);
+    char* base = (char*)ws;
+    const int rows = c.B * c.Gu;
+    const int nb = (c.n + QB_B - 1) / QB_B;
+    int32_t* lists = (int32_t*)(base + W.lists);
+    int32_t* counts = (int32_t*)(base + W.counts);
+    float* A = (float*)(base + W.A);
+    float* C = (float*)(base + W.C);
+    int32_t* diff = (int32_t*)(base + W.diff);
+    double* G = (double*)(base + W.G);
+    // A, C, diff are contiguous: clear them with one fill kernel (safe under graph capture)
+    hipLaunchKernelGGL(zero_kernel, dim3(512), dim3(256), 0, st, (uint32_t*)(base + W.A), (W.G - W.A) / 4);
+    if (c.gate_mode != 2 && c.k > 0 && c.n > c.w) {
+        launch_block_lists(c, death, lists, counts, st);
+        dim3 grid(nb, c.B * c.H);
+        if (c.dtype == SPARSEK_F32)
+            hipLaunchKernelGGL(mask_bwd_generic_kernel<float>, grid, dim3(256), 0, st, (const float*)q,
+                               (const float*)k, (const float*)v, u, tau, death, lists, counts, (const float*)o, lse,
+                               (const float*)dO, A, C, c.H, c.Gu, c.n, c.d, c.k, c.w, c.gate_mode, c.softmax_scale,
+                               nb);
+        else
+            hipLaunchKernelGGL(mask_bwd_generic_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)q,
+                               (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts,
+                               (const uint16_t*)o, lse, (const uint16_t*)dO, A, C, c.H, c.Gu, c.n, c.d, c.k, c.w,
+                               c.gate_mode, c.softmax_scale, nb);
+        hipLaunchKernelGGL(mask_bwd_ranges_kernel, dim3((c.n + 255) / 256, rows), dim3(256), 0, st, u, tau, c.n,
+                           c.k, diff);
+    }
+    hipLaunchKernelGGL(mask_bwd_scan_kernel, dim3(rows), dim3(1024), 0, st, A, diff, c.n, G);
+    hipLaunchKernelGGL(mask_bwd_final_kernel, dim3((c.n + 255) / 256, rows), dim3(256), 0, st, u, tau, C, G, c.n,
+                       c.k, du);
+    return launch_status();
+}
+
 }  // namespace spk

@@ -1,0 +1,63 @@
+"""GPU parity of sparsek_mask_bwd (gradient w.r.t. the scores) against the CPU oracle.
+
+The membership of a key in the strictly fractional set S* is decided from tau; so that both
+sides decide it on the same numbers the oracle is fed the GPU's fp32 thresholds (already
+checked against the oracle's own to 1e-5 elsewhere).  Bars: |du - ref| <= 1e-2 max|ref| for
+bf16 tensors (the stored bf16 output O enters dO.O with relative error 2^-9), 2e-4 max|ref|
+for fp32.  The sum of du over a row must vanish (rows of the SPARSEK Jacobian sum to 0).
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2406_16747_amd as spk
+from paper_2406_16747_amd import synth
+from gpu_util import dev, host, require_gpu, say
+
+pytestmark = pytest.mark.gpu
+
+
+def run_bwd(oracle, inp, gate_mode, heads_all=True):
+    B, H, n, d, k, w, Gu = (inp[x] for x in ("B", "H", "n", "d", "k", "w", "Gu"))
+    bf16 = inp["dtype"] == "bf16"
+    u = dev(inp["u"])
+    Q, K, V, dO = (dev(inp[x], bf16) for x in ("Q", "K", "V", "dO"))
+    tau, death = spk.sparsek_mask(u, k)
+    o, lse = spk.sparsek_attn_fwd(Q, K, V, u, tau, death, k, w, gate_mode, 1.0)
+    du = spk.sparsek_mask_bwd(Q, K, V, u, tau, death, o, lse, dO, k, w, gate_mode, 1.0)
+    torch.cuda.synchronize()
+    du = host(du)
+    assert np.isfinite(du).all()
+    tau64 = host(tau).astype(np.float64)
+    ref, _ = oracle.mask_bwd(inp["Q32"], inp["K32"], inp["V32"], inp["u"], tau64, host(death), inp["dO32"], k, w,
+                             gate_mode, 1.0)
+    scale = np.abs(ref).max()
+    err = np.abs(du - ref).max()
+    tol = (1e-2 if bf16 else 2e-4) * scale
+    assert err <= tol + 1e-30, (err, scale)
+    if scale > 0:
+        assert np.abs(du.sum(-1)).max() <= 1e-3 * scale * np.sqrt(n)
+    return err / max(scale, 1e-30), scale
+
+
+@pytest.mark.parametrize("n,d,k,w,Gu,dtype", [
+    (200, 64, 12, 9, 1, "bf16"), (333, 128, 20, 0, 1, "bf16"), (520, 64, 30, 40, 2, "bf16"),
+    (300, 32, 10, 7, 2, "fp32"), (90, 64, 100, 5, 1, "bf16"), (150, 64, 0, 5, 1, "bf16"), (64, 64, 3, 70, 1, "bf16"),
+])
+@pytest.mark.parametrize("gate_mode", [0, 1, 2])
+def test_mask_bwd_small(oracle, n, d, k, w, Gu, dtype, gate_mode):
+    require_gpu()
+    say("mask_bwd", n, d, k, w, Gu, dtype, gate_mode)
+    inp = synth.make(3, Gu=Gu, seed=n + k, with_dO=True, B=2, H=2, n=n, d=d, k=k, w=w, dtype=dtype,
+                     qk_div=float(np.sqrt(d)) / 4)
+    rel, scale = run_bwd(oracle, inp, gate_mode)
+    if gate_mode == 2 or k == 0 or n <= w or k >= n:
+        assert scale == 0.0
+
+
+def test_mask_bwd_config3_recipe_reduced(oracle):
+    """Config 3 recipe (drifting scores, k=w=512 at n=8192 scaled down 4x), one batch, 2 heads."""
+    require_gpu()
+    say("mask_bwd config 3 reduced")
+    inp = synth.make(3, with_dO=True, B=1, H=2, n=2048, k=128, w=128)
+    run_bwd(oracle, inp, 0)
