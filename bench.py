@@ -89,6 +89,57 @@ def cpu_baseline(cfg, q, k, v, u, rows_per_head=16384):
     }
 
 
+def decode_leg(steps=256, warm=8):
+    """Config 5: B=64, H=32, d=128, k=w=1024, context 32768 already consumed, one token per
+    sequence per step, `steps` consecutive steps.  Returns the extra JSON object."""
+    import torch
+
+    import paper_2406_16747_amd as spk
+
+    B, H, Gu, d, k, w, n_ctx = 64, 32, 1, 128, 1024, 1024, 32768
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1005)
+    div = math.sqrt(d)
+    K = torch.empty(B, H, n_ctx, d, device="cuda", dtype=torch.bfloat16)
+    V = torch.empty_like(K)
+    for b in range(B):  # per batch element, to keep the fp32 temporaries small
+        K[b] = (torch.randn(H, n_ctx, d, device="cuda", generator=g) / div).bfloat16()
+        V[b] = (torch.randn(H, n_ctx, d, device="cuda", generator=g) / div).bfloat16()
+    u = torch.randn(B, Gu, n_ctx, device="cuda", generator=g)
+    tau, death = spk.sparsek_mask(u, k)
+    state = spk.DecodeState(B, H, Gu, d, k, w, torch.bfloat16)
+    spk.sparsek_decode_load(state, K, V, u, tau, death)
+    torch.cuda.synchronize()
+    del K, V
+    tot = steps + warm
+    qs, ks, vs = ((torch.randn(tot, B, H, d, device="cuda", generator=g) / div).bfloat16() for _ in range(3))
+    us = torch.randn(tot, B, Gu, device="cuda", generator=g)
+    o = torch.empty(B, H, d, device="cuda", dtype=torch.bfloat16)
+    for s in range(warm):
+        spk.sparsek_decode_step(state, qs[s], ks[s], vs[s], us[s], out=o)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for s in range(warm, tot):
+        spk.sparsek_decode_step(state, qs[s], ks[s], vs[s], us[s], out=o)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_us = (time.perf_counter() - t0) / steps * 1e6
+    dev_us = e0.elapsed_time(e1) / steps * 1e3
+    bytes_step = B * H * (k + w) * d * 2 * 2
+    gbs = bytes_step / (dev_us * 1e-6) / 1e9
+    overflow = bool(spk.sparsek_decode_status(state).any())
+    return {
+        "workload": "config 5: decode, B=64 H=32 d=128 k=w=1024 bf16, context 32768, %d steps, Gu=1" % steps,
+        "us_per_step": wall_us, "device_us_per_step": dev_us, "tokens_per_s": B / (wall_us * 1e-6),
+        "candidate_overflow": overflow,
+        "roofline": {"bound": "hbm", "kernel": "decode_attn_kernel", "achieved": gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "algorithmic_bytes": bytes_step,
+                     "traffic": read_traffic("decode_config5_counters.txt")},
+    }
+
+
 def read_traffic(name):
     """HBM bytes per launch of the dominant kernel, from the committed counter summary."""
     path = os.path.join(ROOT, "profiles", name)
@@ -108,6 +159,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--gate-mode", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -178,6 +230,10 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, u)
+    if not args.no_decode:
+        del q, k, v, ws
+        torch.cuda.empty_cache()
+        out["decode"] = decode_leg()
     print(json.dumps(out))
 
 
