@@ -1,0 +1,150 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times: thresholds / lifetimes of whole score rows against the oracle, attention
+outputs on sampled heads and query spans (the oracle computes any row on its own), decode on
+sampled heads over all 256 steps.  Configs 4 and 5 are drawn on the device (same
+distributions as the host recipe) and the sampled slices are copied back for the oracle.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2406_16747_amd as spk
+from paper_2406_16747_amd import synth
+from gpu_util import dev, host, require_gpu, say
+
+pytestmark = pytest.mark.gpu
+
+
+def check_mask_rows(oracle, u_np, tau_g, death_g, k, rows):
+    for (b, g) in rows:
+        tau_r = oracle.tau_prefixes(u_np[b, g], k)[0]
+        death_r = oracle.death(u_np[b, g], k)
+        np.testing.assert_array_equal(death_g[b, g], death_r)
+        err = np.abs(tau_g[b, g].astype(np.float64) - tau_r) / np.maximum(1.0, np.abs(tau_r))
+        assert err.max() <= 1e-5, (b, g, err.max())
+        yield (b, g), tau_r, death_r
+
+
+def check_attn_spans(oracle, q32, k32, v32, u_row, tau_r, death_r, o_g, lse_g, k, w, mode, spans):
+    for (a, e) in spans:
+        o_r, lse_r = oracle.attn_rows(q32, k32, v32, u_row, tau_r, death_r, k, w, mode, 1.0, a, e)
+        err = np.abs(o_g[a:e] - o_r).max()
+        ref = np.abs(o_r).max()
+        assert err <= 1e-2 and err <= ref * 2.0 ** -7 + 1e-6, (a, err, ref)
+        np.testing.assert_allclose(lse_g[a:e], lse_r, atol=2e-3, rtol=1e-4)
+
+
+def test_config2_full(oracle):
+    require_gpu()
+    say("config 2 full: B=8 H=12 n=4096 d=64 k=w=256")
+    inp = synth.make(2)
+    k, w, n = inp["k"], inp["w"], inp["n"]
+    u = dev(inp["u"])
+    Q, K, V = (dev(inp[x], True) for x in ("Q", "K", "V"))
+    tau, death = spk.sparsek_mask(u, k)
+    o, lse = spk.sparsek_attn_fwd(Q, K, V, u, tau, death, k, w, 0, 1.0)
+    torch.cuda.synchronize()
+    tau_g, death_g, o_g, lse_g = host(tau), host(death), host(o), host(lse)
+    for (b, g), tau_r, death_r in check_mask_rows(oracle, inp["u"], tau_g, death_g, k, [(b, 0) for b in range(8)]):
+        if b in (0, 5):
+            for h in (0, 11) if b == 0 else (7,):
+                check_attn_spans(oracle, inp["Q32"][b, h], inp["K32"][b, h], inp["V32"][b, h], inp["u"][b, 0], tau_r,
+                                 death_r, o_g[b, h], lse_g[b, h], k, w, 0, [(0, n)] if (b, h) == (0, 0) else
+                                 [(0, 300), (2000, 2200), (3900, n)])
+
+
+def test_config3_full_forward_and_du(oracle):
+    require_gpu()
+    say("config 3 full: B=4 H=16 n=8192 d=128 k=w=512, forward + du")
+    inp = synth.make(3, with_dO=True)
+    k, w, n = inp["k"], inp["w"], inp["n"]
+    u = dev(inp["u"])
+    Q, K, V, dO = (dev(inp[x], True) for x in ("Q", "K", "V", "dO"))
+    tau, death = spk.sparsek_mask(u, k)
+    o, lse = spk.sparsek_attn_fwd(Q, K, V, u, tau, death, k, w, 0, 1.0)
+    du = spk.sparsek_mask_bwd(Q, K, V, u, tau, death, o, lse, dO, k, w, 0, 1.0)
+    torch.cuda.synchronize()
+    tau_g, death_g, o_g, lse_g, du_g = host(tau), host(death), host(o), host(lse), host(du)
+    for (b, g), tau_r, death_r in check_mask_rows(oracle, inp["u"], tau_g, death_g, k, [(b, 0) for b in range(4)]):
+        if b == 1:
+            for h in (0, 9):
+                check_attn_spans(oracle, inp["Q32"][b, h], inp["K32"][b, h], inp["V32"][b, h], inp["u"][b, 0], tau_r,
+                                 death_r, o_g[b, h], lse_g[b, h], k, w, 0, [(0, 200), (1000, 1150), (8000, n)])
+    # du of batch element 2 (all 16 heads add into its score row)
+    b = 2
+    say("  oracle du for batch element", b)
+    ref, _ = oracle.mask_bwd(inp["Q32"][b:b + 1], inp["K32"][b:b + 1], inp["V32"][b:b + 1], inp["u"][b:b + 1],
+                             tau_g[b:b + 1].astype(np.float64), death_g[b:b + 1], inp["dO32"][b:b + 1], k, w, 0, 1.0)
+    scale = np.abs(ref).max()
+    err = np.abs(du_g[b] - ref[0]).max()
+    assert scale > 0 and err <= 1e-2 * scale, (err, scale)
+
+
+def device_recipe(B, H, Gu, n, d, seed):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    div = math.sqrt(d)
+    q, k, v = ((torch.randn((B, H, n, d), device="cuda", generator=g) / div).bfloat16() for _ in range(3))
+    u = torch.randn((B, Gu, n), device="cuda", generator=g)
+    return q, k, v, u
+
+
+@pytest.mark.parametrize("Gu", [1, 32])
+def test_config4_full(oracle, Gu):
+    require_gpu()
+    say("config 4 full: B=1 H=32 n=32768 d=128 k=w=1024, Gu =", Gu)
+    B, H, n, d, k, w = 1, 32, 32768, 128, 1024, 1024
+    q, kk, v, u = device_recipe(B, H, Gu, n, d, 1004)
+    tau, death = spk.sparsek_mask(u, k)
+    o, lse = spk.sparsek_attn_fwd(q, kk, v, u, tau, death, k, w, 0, 1.0)
+    torch.cuda.synchronize()
+    u_np, tau_g, death_g = host(u), host(tau), host(death)
+    heads = [3] if Gu == 1 else [0, 31]
+    rows = [(0, 0)] if Gu == 1 else [(0, h) for h in heads]
+    for (b, g), tau_r, death_r in check_mask_rows(oracle, u_np, tau_g, death_g, k, rows):
+        h = heads[0] if Gu == 1 else g
+        check_attn_spans(oracle, host(q[0, h]), host(kk[0, h]), host(v[0, h]), u_np[0, g], tau_r, death_r,
+                         host(o[0, h]), host(lse[0, h]), k, w, 0,
+                         [(0, 130), (1000, 1100), (2040, 2180), (16380, 16520), (32640, n)])
+
+
+def test_config5_full_decode(oracle):
+    require_gpu()
+    say("config 5 full: decode B=64 H=32 d=128 k=w=1024, context 32768, 256 steps")
+    B, H, Gu, d, k, w, n_ctx, steps = 64, 32, 1, 128, 1024, 1024, 32768, 256
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1005)
+    div = math.sqrt(d)
+    K = torch.empty(B, H, n_ctx, d, device="cuda", dtype=torch.bfloat16)
+    V = torch.empty_like(K)
+    for b in range(B):
+        K[b] = (torch.randn(H, n_ctx, d, device="cuda", generator=g) / div).bfloat16()
+        V[b] = (torch.randn(H, n_ctx, d, device="cuda", generator=g) / div).bfloat16()
+    u = torch.randn(B, Gu, n_ctx, device="cuda", generator=g)
+    sample = [(0, 0), (37, 21), (63, 31)]
+    hist = {s: (host(K[s[0], s[1]]), host(V[s[0], s[1]]), host(u[s[0], 0])) for s in sample}
+    tau, death = spk.sparsek_mask(u, k)
+    state = spk.DecodeState(B, H, Gu, d, k, w, torch.bfloat16)
+    spk.sparsek_decode_load(state, K, V, u, tau, death)
+    torch.cuda.synchronize()
+    del K, V
+    qs, ks, vs = ((torch.randn(steps, B, H, d, device="cuda", generator=g) / div).bfloat16() for _ in range(3))
+    us = torch.randn(steps, B, Gu, device="cuda", generator=g)
+    outs = torch.empty(steps, B, H, d, device="cuda", dtype=torch.bfloat16)
+    for s in range(steps):
+        spk.sparsek_decode_step(state, qs[s], ks[s], vs[s], us[s], out=outs[s])
+    torch.cuda.synchronize()
+    assert not spk.sparsek_decode_status(state).any()
+    for (b, h) in sample:
+        say("  oracle decode for head", b, h)
+        Kh, Vh, uh = hist[(b, h)]
+        K_full = np.concatenate([Kh, host(ks[:, b, h])])
+        V_full = np.concatenate([Vh, host(vs[:, b, h])])
+        u_full = np.concatenate([uh, host(us[:, b, 0])])
+        ref = oracle.decode_bydef(host(qs[:, b, h]), K_full, V_full, u_full, n_ctx, k, w, 0, 1.0)
+        got = host(outs[:, b, h])
+        err = np.abs(got - ref).max()
+        scale = np.abs(ref).max()
+        assert err <= 1e-2 and err <= scale * 2.0 ** -7, (b, h, err, scale)
