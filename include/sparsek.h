@@ -53,7 +53,7 @@ typedef struct {
     int32_t B, H, Gu, n, d, k, w;
     int32_t dtype;     /* SPARSEK_F32 or SPARSEK_BF16: storage type of q, k, v, o, dO */
     int32_t gate_mode; /* 0, 1 or 2 */
-    float softmax_scale;
+    float softmax_scale; /* finite and > 0 */
 } sparsek_cfg;
 
 const char *sparsek_strerror(int code);

@@ -23,7 +23,7 @@ int check_attn(const sparsek_cfg* c)
     if (c->gate_mode < 0 || c->gate_mode > 2) return SPARSEK_ERR_INVALID_ARG;
     if (c->dtype != SPARSEK_F32 && c->dtype != SPARSEK_BF16) return SPARSEK_ERR_UNSUPPORTED;
     if (c->d < 4 || c->d > 128 || (c->d % 4) != 0) return SPARSEK_ERR_UNSUPPORTED;
-    if (!(c->softmax_scale == c->softmax_scale)) return SPARSEK_ERR_INVALID_ARG;
+    if (!(c->softmax_scale > 0.0f) || !(c->softmax_scale < INFINITY)) return SPARSEK_ERR_INVALID_ARG;
     return SPARSEK_OK;
 }
 
@@ -111,7 +111,7 @@ int check_decode(const sparsek_decode_cfg* c)
     if (c->dtype != SPARSEK_F32 && c->dtype != SPARSEK_BF16) return SPARSEK_ERR_UNSUPPORTED;
     if (c->d < 8 || c->d > 128 || (c->d % 8) != 0) return SPARSEK_ERR_UNSUPPORTED;
     if ((long long)c->B * c->H > (1 << 24)) return SPARSEK_ERR_UNSUPPORTED;
-    if (!(c->softmax_scale == c->softmax_scale)) return SPARSEK_ERR_INVALID_ARG;
+    if (!(c->softmax_scale > 0.0f) || !(c->softmax_scale < INFINITY)) return SPARSEK_ERR_INVALID_ARG;
     return SPARSEK_OK;
 }
 }  // namespace

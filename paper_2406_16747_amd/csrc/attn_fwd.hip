@@ -257,6 +257,125 @@ __device__ __forceinline__ void store_tile(uint16_t (&Ks)[KT][D + 8], uint16_t (
     }
 }
 
+// Tile kinds, chosen per wave and tile:
+//   FAST       contiguous keys inside every query's window and not in its future: no mask, gate 1
+//   LIST       selected keys that outlive every query of the wave: gates, no mask
+//   LIST_MASK  selected keys, some of which expire inside the wave's query range
+//   CONT       contiguous keys at the causal diagonal or at the window's trailing edge
+enum { TILE_FAST = 0, TILE_LIST = 1, TILE_LIST_MASK = 2, TILE_CONT = 3 };
+
+// One 64-key tile for one wave: S^T = K.Q^T, gates/masks, online softmax, O^T += V^T.P^T.
+// The running maximum m_run is kept in raw logit units (before the softmax scale c2 > 0,
+// which already contains log2 e); p = exp2(s*c2 - m*c2) costs one fma and one v_exp_f32.
+template <int D, int MODE, int KIND>
+__device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int base, int col, int half, int qi, int jbase,
+                                             int w, float tau_q, float c2, const bf16x8 (&qreg)[D / 16],
+                                             f32x16 (&acc_o)[D / 32], float& m_run, float& l_run)
+{
+    constexpr int DS = D / 16, DB = D / 32;
+    f32x16 acc_s[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; mb++) {
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc_s[mb][r] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < DS; s++) {
+            const bf16x8 a = *(const bf16x8*)&sm.Ks[32 * mb + col][16 * s + 8 * half];
+            acc_s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], acc_s[mb], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keep the operand loads of the next block from piling up
+    }
+    constexpr bool GATED = (KIND != TILE_FAST) && (MODE != 2);  // the value gate applies
+    constexpr bool KGATE = (KIND != TILE_FAST) && (MODE == 0);  // the key gate applies
+    // CONT tiles: key number kk = cst + 4*half of the tile sits dq - kk positions behind the query.
+    // Folding the lane-dependent 4*half into dqh leaves compile-time constants in every compare
+    // (otherwise the 32 per-lane key numbers are hoisted into registers and spill).
+    const int dqh = qi - jbase - 4 * half;
+    const int dqw = dqh - w;  // in the window  <=>  cst > dqw
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int mb = 0; mb < 2; mb++) {
+#pragma unroll
+        for (int g4 = 0; g4 < 4; g4++) {
+            const int kb = 32 * mb + 8 * g4 + 4 * half;  // first of 4 consecutive keys
+            int4 L4 = make_int4(0, 0, 0, 0);
+            float4 U4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (KIND == TILE_LIST_MASK || KIND == TILE_CONT) L4 = *(const int4*)&sm.jlast[base + kb];
+            if (KGATE) U4 = *(const float4*)&sm.ju[base + kb];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const int r = 4 * g4 + e;
+                float s2 = acc_s[mb][r];
+                const int Lj = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
+                const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
+                const int cst = 32 * mb + 8 * g4 + e;  // key number within the tile minus 4*half
+                if (KGATE) {
+                    const float g = clip01(uj - tau_q);
+                    if (KIND == TILE_CONT) s2 = (cst > dqw) ? s2 : s2 * g;
+                    else s2 *= g;
+                }
+                if (KIND == TILE_LIST_MASK) s2 = (qi <= Lj) ? s2 : -INFINITY;
+                if (KIND == TILE_CONT) s2 = (cst <= dqh && qi <= Lj) ? s2 : -INFINITY;
+                acc_s[mb][r] = s2;
+                tmax = fmaxf(tmax, s2);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // one group of metadata loads in flight at a time
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float m_new = fmaxf(m_run, tmax);
+    const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * c2);
+    const float mc = m_safe * c2;
+    m_run = m_new;
+    float psum = 0.0f;
+    bf16x8 pb[4];
+#pragma unroll
+    for (int mb = 0; mb < 2; mb++) {
+#pragma unroll
+        for (int g4 = 0; g4 < 4; g4++) {
+            const int kb = 32 * mb + 8 * g4 + 4 * half;
+            float4 U4 = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (GATED) U4 = *(const float4*)&sm.ju[base + kb];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const int r = 4 * g4 + e;
+                const float p = __builtin_amdgcn_exp2f(fmaf(acc_s[mb][r], c2, -mc));
+                psum += p;
+                float pvv = p;
+                if (GATED) {  // value gate, recomputed: cheaper than holding 32 registers
+                    const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
+                    const float g = clip01(uj - tau_q);
+                    if (KIND == TILE_CONT) pvv = (32 * mb + 8 * g4 + e > dqw) ? p : p * g;
+                    else pvv = p * g;
+                }
+                pb[2 * mb + (r >> 3)][r & 7] = (__bf16)pvv;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    l_run = l_run * alpha + psum;
+    __builtin_amdgcn_sched_barrier(0);
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int x = 0; x < DB; x++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc_o[x][r] *= alpha;
+    }
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+#pragma unroll
+        for (int x = 0; x < DB; x++) {
+            const bf16x4 lo4 = *(const bf16x4*)&sm.Vt[32 * x + col][16 * g + 4 * half];
+            const bf16x4 hi4 = *(const bf16x4*)&sm.Vt[32 * x + col][16 * g + 8 + 4 * half];
+            const bf16x8 a = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+            acc_o[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[g], acc_o[x], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 template <int D, int MODE>
 __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ kk, const uint16_t* __restrict__ v,
@@ -363,121 +482,21 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
             __syncthreads();
             if (t + 1 < ntiles) load_tile<D>(sm.jpos + (t + 1) * KT, kh, vh, tid, kpre, vpre);
 
-            // ---- does this wave see anything of the tile? ----
+            // ---- classify the tile for this wave (all conditions are wave-uniform) ----
             const int base = t * KT;
             const int E0 = seg0 + base;
             const bool is_list = E0 < nkl;
             const int jbase = is_list ? 0 : c0 + (E0 - nkl);  // first position of a contiguous tile
-            const int lmin = sm.tile_lmin[t];
-            bool skip = !wave_live;
-            bool fast = false;  // every pair valid with gate 1
-            bool nomask = false;  // every pair valid (gates still apply)
+            if (!wave_live) continue;
             if (is_list) {
-                nomask = lmin >= qb;
+                tile_compute<D, MODE, TILE_LIST_MASK>(sm, base, col, half, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
             } else {
-                if (jbase > qb) skip = true;                       // all keys in the future
+                if (jbase > qb) continue;  // every key of the tile is in the future of every query of the wave
                 const int jend = jbase + KT - 1;
-                if (jend <= qa && qb - jbase < w && jend <= c_end) fast = true;  // inside every window
-            }
-            if (skip) continue;
-
-            // ---- S^T = K . Q^T ----
-            f32x16 acc_s[2];
-#pragma unroll
-            for (int mb = 0; mb < 2; mb++) {
-#pragma unroll
-                for (int r = 0; r < 16; r++) acc_s[mb][r] = 0.0f;
-#pragma unroll
-                for (int s = 0; s < DS; s++) {
-                    const bf16x8 a = *(const bf16x8*)&sm.Ks[32 * mb + col][16 * s + 8 * half];
-                    acc_s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], acc_s[mb], 0, 0, 0);
-                }
-            }
-
-            // ---- gates, masks, online softmax (log2 domain) ----
-            float tmax = -INFINITY;
-#pragma unroll
-            for (int mb = 0; mb < 2; mb++) {
-#pragma unroll
-                for (int g4 = 0; g4 < 4; g4++) {
-                    const int kb = 32 * mb + 8 * g4 + 4 * half;  // first of 4 consecutive keys
-                    int4 L4 = make_int4(0, 0, 0, 0);
-                    float4 U4 = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (!fast) {
-                        L4 = *(const int4*)&sm.jlast[base + kb];
-                        if (MODE == 0) U4 = *(const float4*)&sm.ju[base + kb];
-                    }
-#pragma unroll
-                    for (int e = 0; e < 4; e++) {
-                        const int r = 4 * g4 + e;
-                        float s2 = acc_s[mb][r] * c2;
-                        if (!fast) {
-                            const int Lj = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
-                            const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
-                            bool valid;
-                            if (is_list) {
-                                valid = nomask || (qi <= Lj);
-                                if (MODE == 0) s2 *= clip01(uj - tau_q);
-                            } else {
-                                const int j = jbase + kb + e;
-                                valid = (j <= qi) && (qi <= Lj);
-                                if (MODE == 0) s2 *= (qi - j < w) ? 1.0f : clip01(uj - tau_q);
-                            }
-                            s2 = valid ? s2 : -INFINITY;
-                        }
-                        acc_s[mb][r] = s2;
-                        tmax = fmaxf(tmax, s2);
-                    }
-                }
-            }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-            const float m_new = fmaxf(m_run, tmax);
-            const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
-            const float alpha = exp2f(m_run - m_safe);
-            m_run = m_new;
-            float psum = 0.0f;
-            bf16x8 pb[4];
-#pragma unroll
-            for (int mb = 0; mb < 2; mb++) {
-#pragma unroll
-                for (int g4 = 0; g4 < 4; g4++) {
-                    const int kb = 32 * mb + 8 * g4 + 4 * half;
-                    float4 U4 = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (!fast && MODE != 2) U4 = *(const float4*)&sm.ju[base + kb];
-#pragma unroll
-                    for (int e = 0; e < 4; e++) {
-                        const int r = 4 * g4 + e;
-                        const float p = exp2f(acc_s[mb][r] - m_safe);
-                        psum += p;
-                        float pvv = p;
-                        if (!fast && MODE != 2) {  // the value gate (recomputed: cheaper than keeping 32 registers)
-                            const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
-                            const float g = clip01(uj - tau_q);
-                            if (is_list) pvv = p * g;
-                            else pvv = (qi - (jbase + kb + e) < w) ? p : p * g;
-                        }
-                        pb[2 * mb + (r >> 3)][r & 7] = (__bf16)pvv;
-                    }
-                }
-            }
-            l_run = l_run * alpha + psum;
-            if (__any(alpha != 1.0f)) {
-#pragma unroll
-                for (int x = 0; x < DB; x++)
-#pragma unroll
-                    for (int r = 0; r < 16; r++) acc_o[x][r] *= alpha;
-            }
-
-            // ---- O^T += V^T . P^T ----
-#pragma unroll
-            for (int g = 0; g < 4; g++) {
-#pragma unroll
-                for (int x = 0; x < DB; x++) {
-                    const bf16x4 lo4 = *(const bf16x4*)&sm.Vt[32 * x + col][16 * g + 4 * half];
-                    const bf16x4 hi4 = *(const bf16x4*)&sm.Vt[32 * x + col][16 * g + 8 + 4 * half];
-                    const bf16x8 a = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-                    acc_o[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[g], acc_o[x], 0, 0, 0);
-                }
+                if (jend <= qa && qb - jbase < w && jend <= c_end)
+                    tile_compute<D, MODE, TILE_FAST>(sm, base, col, half, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
+                else
+                    tile_compute<D, MODE, TILE_CONT>(sm, base, col, half, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
             }
         }
     }
@@ -497,7 +516,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
                 *(bf16x4*)(orow + 32 * x + 8 * g4 + 4 * half) = pk;
             }
         }
-        if (lse && half == 0) lse[(size_t)bh * n + qi] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+        if (lse && half == 0) lse[(size_t)bh * n + qi] = (m_run * c2 + log2f(l_tot)) * 0.6931471805599453f;
     }
 }
 

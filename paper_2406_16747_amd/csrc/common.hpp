@@ -32,60 +32,120 @@ inline int launch_status()
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 #ifdef __HIPCC__
-// ---- wave-level reductions (all 64 lanes must be active) ----
+// ---- wave-level reductions (all 64 lanes must be active; every lane gets the result) ----
+// Four DPP steps reduce inside each row of 16 lanes (quad swaps, half-row mirror, row mirror),
+// then the four row totals are read with v_readlane and combined.  No LDS round trips.
+#define SPK_DPP(x, ctrl) __builtin_amdgcn_update_dpp(0, (x), (ctrl), 0xF, 0xF, true)
+#define SPK_QP_SWAP1 0xB1   // quad_perm [1,0,3,2]
+#define SPK_QP_SWAP2 0x4E   // quad_perm [2,3,0,1]
+#define SPK_HALF_MIRROR 0x141
+#define SPK_ROW_MIRROR 0x140
+
+__device__ __forceinline__ float dpp_f32(float x, int which)
+{
+    const int i = __float_as_int(x);
+    int r;
+    switch (which) {
+        case 0: r = SPK_DPP(i, SPK_QP_SWAP1); break;
+        case 1: r = SPK_DPP(i, SPK_QP_SWAP2); break;
+        case 2: r = SPK_DPP(i, SPK_HALF_MIRROR); break;
+        default: r = SPK_DPP(i, SPK_ROW_MIRROR); break;
+    }
+    return __int_as_float(r);
+}
+__device__ __forceinline__ int dpp_i32(int i, int which)
+{
+    switch (which) {
+        case 0: return SPK_DPP(i, SPK_QP_SWAP1);
+        case 1: return SPK_DPP(i, SPK_QP_SWAP2);
+        case 2: return SPK_DPP(i, SPK_HALF_MIRROR);
+        default: return SPK_DPP(i, SPK_ROW_MIRROR);
+    }
+}
+__device__ __forceinline__ unsigned long long dpp_u64(unsigned long long x, int which)
+{
+    const int lo = dpp_i32((int)(unsigned)(x & 0xFFFFFFFFull), which);
+    const int hi = dpp_i32((int)(unsigned)(x >> 32), which);
+    return ((unsigned long long)(unsigned)hi << 32) | (unsigned long long)(unsigned)lo;
+}
+__device__ __forceinline__ double dpp_f64(double x, int which)
+{
+    return __longlong_as_double((long long)dpp_u64((unsigned long long)__double_as_longlong(x), which));
+}
+__device__ __forceinline__ float readlane_f32(float x, int l)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), l));
+}
+__device__ __forceinline__ unsigned long long readlane_u64(unsigned long long x, int l)
+{
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(x & 0xFFFFFFFFull), l);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(x >> 32), l);
+    return ((unsigned long long)hi << 32) | lo;
+}
+
 __device__ __forceinline__ double wave_sum_f64(double x)
 {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
-    return x;
+    for (int s = 0; s < 4; s++) x += dpp_f64(x, s);
+    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+    return __longlong_as_double((long long)readlane_u64(b, 15)) + __longlong_as_double((long long)readlane_u64(b, 31)) +
+           __longlong_as_double((long long)readlane_u64(b, 47)) + __longlong_as_double((long long)readlane_u64(b, 63));
 }
 __device__ __forceinline__ float wave_sum_f32(float x)
 {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
-    return x;
-}
-__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long x)
-{
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
-    return x;
+    for (int s = 0; s < 4; s++) x += dpp_f32(x, s);
+    return (readlane_f32(x, 15) + readlane_f32(x, 31)) + (readlane_f32(x, 47) + readlane_f32(x, 63));
 }
 __device__ __forceinline__ int wave_sum_i32(int x)
 {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
-    return x;
+    for (int s = 0; s < 4; s++) x += dpp_i32(x, s);
+    return __builtin_amdgcn_readlane(x, 15) + __builtin_amdgcn_readlane(x, 31) + __builtin_amdgcn_readlane(x, 47) +
+           __builtin_amdgcn_readlane(x, 63);
+}
+// two 32-bit counts packed into one 64-bit word (each < 2^31): summed as two ints
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long x)
+{
+    const int lo = wave_sum_i32((int)(unsigned)(x & 0xFFFFFFFFull));
+    const int hi = wave_sum_i32((int)(unsigned)(x >> 32));
+    return ((unsigned long long)(unsigned)hi << 32) + (unsigned long long)(unsigned)lo;
 }
 __device__ __forceinline__ float wave_min_f32(float x)
 {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x = fminf(x, __shfl_xor(x, o, 64));
-    return x;
+    for (int s = 0; s < 4; s++) x = fminf(x, dpp_f32(x, s));
+    return fminf(fminf(readlane_f32(x, 15), readlane_f32(x, 31)), fminf(readlane_f32(x, 47), readlane_f32(x, 63)));
 }
 __device__ __forceinline__ float wave_max_f32(float x)
 {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, 64));
-    return x;
+    for (int s = 0; s < 4; s++) x = fmaxf(x, dpp_f32(x, s));
+    return fmaxf(fmaxf(readlane_f32(x, 15), readlane_f32(x, 31)), fmaxf(readlane_f32(x, 47), readlane_f32(x, 63)));
 }
 __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long x)
 {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        unsigned long long y = __shfl_xor(x, o, 64);
+    for (int s = 0; s < 4; s++) {
+        const unsigned long long y = dpp_u64(x, s);
         x = y < x ? y : x;
     }
-    return x;
+    unsigned long long a = readlane_u64(x, 15), b = readlane_u64(x, 31), c = readlane_u64(x, 47), d = readlane_u64(x, 63);
+    a = b < a ? b : a;
+    c = d < c ? d : c;
+    return c < a ? c : a;
 }
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long x)
 {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        unsigned long long y = __shfl_xor(x, o, 64);
+    for (int s = 0; s < 4; s++) {
+        const unsigned long long y = dpp_u64(x, s);
         x = y > x ? y : x;
     }
-    return x;
+    unsigned long long a = readlane_u64(x, 15), b = readlane_u64(x, 31), c = readlane_u64(x, 47), d = readlane_u64(x, 63);
+    a = b > a ? b : a;
+    c = d > c ? d : c;
+    return c > a ? c : a;
 }
 
 // Order-preserving map fp32 -> uint32 (-0.0 is folded onto +0.0 first).

@@ -486,6 +486,26 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(sparsek_decode_cfg c, 
 // ---------------------------------------------------------------------------------
 // init / load
 // ---------------------------------------------------------------------------------
+// Empty slots are skipped through their gate score (-inf) but their rows are still streamed and
+// multiplied by a zero weight, so they must hold finite numbers: clear slots [first, NS) of every head.
+__global__ __launch_bounds__(256) void decode_zero_slots_kernel(sparsek_decode_cfg c, char* st, int from_state)
+{
+    const DecodeLayout L = decode_layout(c);
+    const int bh = blockIdx.x;
+    const int b = bh / c.H, h = bh % c.H;
+    const int row = b * c.Gu + (c.Gu == 1 ? 0 : h);
+    const int first = from_state ? L.NS - *((const int*)(st + L.nfree) + row) : 0;
+    const size_t esz = c.dtype == SPARSEK_BF16 ? 2 : 4;
+    const size_t row_bytes = (size_t)c.d * esz;
+    uint4* kd = (uint4*)(st + L.kslots + ((size_t)bh * L.NS + first) * row_bytes);
+    uint4* vd = (uint4*)(st + L.vslots + ((size_t)bh * L.NS + first) * row_bytes);
+    const size_t nchunk = (size_t)(L.NS - first) * row_bytes / 16;
+    for (size_t x = threadIdx.x + (size_t)blockIdx.y * 256; x < nchunk; x += (size_t)gridDim.y * 256) {
+        kd[x] = make_uint4(0, 0, 0, 0);
+        vd[x] = make_uint4(0, 0, 0, 0);
+    }
+}
+
 __global__ __launch_bounds__(NT_ROW) void decode_init_kernel(sparsek_decode_cfg c, char* st)
 {
     const DecodeLayout L = decode_layout(c);
@@ -611,7 +631,9 @@ __global__ __launch_bounds__(256) void decode_load_kv_kernel(sparsek_decode_cfg 
 // ---------------------------------------------------------------------------------
 int launch_decode_init(const sparsek_decode_cfg& c, void* state, hipStream_t st)
 {
+    if (c.d != 32 && c.d != 64 && c.d != 128) return SPARSEK_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(decode_init_kernel, dim3(c.B * c.Gu), dim3(NT_ROW), 0, st, c, (char*)state);
+    hipLaunchKernelGGL(decode_zero_slots_kernel, dim3(c.B * c.H, 4), dim3(256), 0, st, c, (char*)state, 0);
     return launch_status();
 }
 
@@ -627,6 +649,7 @@ int launch_decode_load(const sparsek_decode_cfg& c, void* state, int n_ctx, cons
     else
         hipLaunchKernelGGL(decode_load_kv_kernel<float>, dim3(c.B * c.H), dim3(256), 0, st, c, (char*)state,
                            n_ctx, (const float*)k, (const float*)v);
+    hipLaunchKernelGGL(decode_zero_slots_kernel, dim3(c.B * c.H, 4), dim3(256), 0, st, c, (char*)state, 1);
     return launch_status();
 }
 

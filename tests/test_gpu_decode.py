@@ -38,6 +38,7 @@ def run_decode(oracle, B, H, Gu, d, k, w, n_ctx, steps, dtype="bf16", gate_mode=
     Q, K, V = (dev(hist[x], bf16) for x in ("Q", "K", "V"))
     u = dev(hist["u"])
     state = spk.DecodeState(B, H, Gu, d, k, w, tdt, gate_mode, 1.0, cand_cap)
+    state.buf.fill_(255)  # NaN patterns everywhere: init/load must not rely on fresh memory
     if n_ctx == 0:
         spk.sparsek_decode_init(state)
     else:
