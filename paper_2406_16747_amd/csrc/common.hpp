@@ -154,6 +154,11 @@ __device__ __forceinline__ uint32_t score_key(float v)
     uint32_t b = __float_as_uint(v + 0.0f);
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
+// Inverse of score_key: the fp32 bit pattern of a key.
+__device__ __forceinline__ uint32_t score_key_inv(uint32_t key)
+{
+    return (key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key;
+}
 // Selection order as one unsigned compare: larger score first, then the older position.
 __device__ __forceinline__ unsigned long long sel_key(float v, int idx)
 {

@@ -18,11 +18,11 @@
 namespace spk {
 
 constexpr int CHUNK = 128;        // prefixes per workgroup of the chunk kernel
-constexpr int NT_CHUNK = 512;     // threads of the chunk kernel (8 waves, 16 prefixes each)
+constexpr int NT_CHUNK = 1024;    // threads of the chunk kernel (16 waves, 8 prefixes each)
 constexpr int NW_CHUNK = NT_CHUNK / 64;
-constexpr int TPW = CHUNK / NW_CHUNK;
 constexpr int SUPER = 2048;       // spacing of the coarse lower bounds
 constexpr int CAP = 8192;         // candidate capacity in LDS (scores + positions: 64 KB)
+constexpr int CAP_PAD = CAP + 8;  // room for the -inf padding that rounds both list regions to multiples of 4
 constexpr int NT_COARSE = 1024;
 constexpr int NPROBE = 15;
 constexpr int NPASS = 3;
@@ -36,69 +36,91 @@ size_t mask_ws_bytes(const sparsek_cfg& c)
 }
 
 // ---------------------------------------------------------------------------------
-// Prefixes with at most k entries: tau_t = min(u[0..t]) - 1.  k == 0: tau_t = max, death = j.
-// One workgroup per row; a three-phase scan over `upto` entries.
+// Coarse kernel, grid (nsuper, rows), 1024 threads.
+//  * every block presets death[] = n on its slice of SUPER positions;
+//  * block s == 0 also writes the thresholds of the prefixes with at most k entries:
+//    tau_t = min(u[0..t]) - 1 (k == 0: tau_t = max(u[0..t]) and death[j] = j) -- a block scan;
+//  * block s >= 1 looks at the prefix of length L = s*SUPER and, if L >= k, narrows a bracket
+//    around the root of f_L(x) = k with NPASS passes of NPROBE probes; lo_out = a point with
+//    f(lo) >= k + 1/4 (so lo <= tau of that prefix despite fp32 partial sums).
+// Scores are read once into registers (COARSE_REG per thread), in segments for very long rows.
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void mask_short_prefix_kernel(const float* __restrict__ u,
-                                                                  float* __restrict__ tau,
-                                                                  int32_t* __restrict__ death, int n,
-                                                                  int k)
+constexpr int COARSE_REG = 32;
+
+__device__ void short_prefix_scan(const float* __restrict__ ur, float* __restrict__ tr, int32_t* __restrict__ dr,
+                                  int n, int k, float* part /* [1024] LDS */)
 {
-    __shared__ float part[1024];
-    const int row = blockIdx.x;
-    const float* ur = u + (size_t)row * n;
-    float* tr = tau + (size_t)row * n;
+    const int tid = threadIdx.x;
     const bool use_max = (k == 0);
     const int upto = use_max ? n : (k < n ? k : n);
     const int per = (upto + 1023) / 1024;
-    const int b = threadIdx.x * per;
-    const int e = min(b + per, upto);
+    const int b = tid * per, e = min(b + per, upto);
     float acc = use_max ? -INFINITY : INFINITY;
     for (int i = b; i < e; i++) acc = use_max ? fmaxf(acc, ur[i]) : fminf(acc, ur[i]);
-    part[threadIdx.x] = acc;
+    part[tid] = acc;
     __syncthreads();
-    float run = use_max ? -INFINITY : INFINITY;
-    for (int i = 0; i < (int)threadIdx.x; i++) run = use_max ? fmaxf(run, part[i]) : fminf(run, part[i]);
+    // inclusive Hillis-Steele scan of the 1024 partial extrema
+    for (int off = 1; off < 1024; off <<= 1) {
+        float other = (tid >= off) ? part[tid - off] : acc;
+        __syncthreads();
+        acc = use_max ? fmaxf(acc, other) : fminf(acc, other);
+        part[tid] = acc;
+        __syncthreads();
+    }
+    float run = (tid == 0) ? (use_max ? -INFINITY : INFINITY) : part[tid - 1];
     for (int i = b; i < e; i++) {
         run = use_max ? fmaxf(run, ur[i]) : fminf(run, ur[i]);
         tr[i] = use_max ? run : run - 1.0f;
     }
-    if (use_max) {
-        int32_t* dr = death + (size_t)row * n;
-        for (int i = threadIdx.x; i < n; i += 1024) dr[i] = i;
-    }
+    if (use_max)
+        for (int i = tid; i < n; i += 1024) dr[i] = i;
 }
 
-// ---------------------------------------------------------------------------------
-// Coarse lower bounds.  Block (s, row) looks at the prefix of length L = s*SUPER and, if
-// L >= k, narrows a bracket around the root of f_L(x) = k with NPASS passes of NPROBE probes;
-// lo_out = a point with f(lo) >= k + 1/4 (so lo <= tau of that prefix despite fp32 partial
-// sums).  It also presets death[] = n on its slice.
-// ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(NT_COARSE) void mask_coarse_kernel(const float* __restrict__ u,
                                                                  float* __restrict__ lo_out,
+                                                                 float* __restrict__ tau,
                                                                  int32_t* __restrict__ death, int n,
                                                                  int k, int nsuper)
 {
     __shared__ double red[NT_COARSE / 64][NPROBE + 1];
     __shared__ float bracket[2];
+    __shared__ float part[1024];
     const int s = blockIdx.x, row = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const float* ur = u + (size_t)row * n;
     int32_t* dr = death + (size_t)row * n;
-    for (int i = s * SUPER + tid; i < min(n, (s + 1) * SUPER); i += NT_COARSE) dr[i] = n;
+    if (k > 0)
+        for (int i = s * SUPER + tid; i < min(n, (s + 1) * SUPER); i += NT_COARSE) dr[i] = n;
     const int L = s * SUPER;
     float* out = lo_out + (size_t)row * nsuper + s;
-    if (L < k || L == 0) {
+    if (s == 0) {
+        short_prefix_scan(ur, tau + (size_t)row * n, dr, n, k, part);
         if (tid == 0) *out = -INFINITY;
         return;
     }
+    if (L < k || k == 0) {
+        if (tid == 0) *out = -INFINITY;
+        return;
+    }
+    const int nseg = (L + NT_COARSE * COARSE_REG - 1) / (NT_COARSE * COARSE_REG);
+    float z[COARSE_REG];
+    auto load_seg = [&](int seg) {
+#pragma unroll
+        for (int r = 0; r < COARSE_REG; r++) {
+            const int i = (seg * COARSE_REG + r) * NT_COARSE + tid;
+            z[r] = (i < L) ? ur[i] : -INFINITY;  // -inf never counts in f; excluded from the min below
+        }
+    };
+    load_seg(0);
     // pass 0: range of the prefix
     float mn = INFINITY, mx = -INFINITY;
-    for (int i = tid; i < L; i += NT_COARSE) {
-        float z = ur[i];
-        mn = fminf(mn, z);
-        mx = fmaxf(mx, z);
+    for (int seg = 0; seg < nseg; seg++) {
+        if (nseg > 1) load_seg(seg);
+#pragma unroll
+        for (int r = 0; r < COARSE_REG; r++) {
+            mx = fmaxf(mx, z[r]);
+            mn = (z[r] > -INFINITY) ? fminf(mn, z[r]) : mn;
+        }
     }
     mn = wave_min_f32(mn);
     mx = wave_max_f32(mx);
@@ -117,10 +139,13 @@ __global__ __launch_bounds__(NT_COARSE) void mask_coarse_kernel(const float* __r
         float acc[NPROBE];
 #pragma unroll
         for (int p = 0; p < NPROBE; p++) acc[p] = 0.0f;
-        for (int i = tid; i < L; i += NT_COARSE) {
-            float z = ur[i];
+        for (int seg = 0; seg < nseg; seg++) {
+            if (nseg > 1) load_seg(seg);
 #pragma unroll
-            for (int p = 0; p < NPROBE; p++) acc[p] += clip01(z - (lo + step * (float)(p + 1)));
+            for (int r = 0; r < COARSE_REG; r++) {
+#pragma unroll
+                for (int p = 0; p < NPROBE; p++) acc[p] += clip01(z[r] - (lo + step * (float)(p + 1)));
+            }
         }
 #pragma unroll
         for (int p = 0; p < NPROBE; p++) {
@@ -148,12 +173,15 @@ __global__ __launch_bounds__(NT_COARSE) void mask_coarse_kernel(const float* __r
 // ---------------------------------------------------------------------------------
 // Candidate lists: compacted in LDS, or (overflow fallback) the raw prefix in global memory.
 // ---------------------------------------------------------------------------------
+// LDS list: [0, mo4) older candidates (positions in idx[]; padding entries have score -inf and
+// position INT_MAX), [mo4, M) the chunk's own scores in order (position t0 + i - mo4; padding
+// beyond the chunk has score -inf).  Both regions are multiples of 4 long and 16-byte aligned.
 struct ListLds {
     const float* v;
     const int* idx;
-    int M;
+    int M, mo4, t0;
     __device__ __forceinline__ float val(int i) const { return v[i]; }
-    __device__ __forceinline__ int pos(int i) const { return idx[i]; }
+    __device__ __forceinline__ int pos(int i) const { return i < mo4 ? idx[i] : t0 + (i - mo4); }
 };
 struct ListGlobal {
     const float* u;
@@ -182,6 +210,49 @@ __device__ __forceinline__ void eval_piece(const List& L, int t, double x, int l
                 else sum += dv;
             }
         }
+    }
+    unsigned long long packed = wave_sum_u64(((unsigned long long)f << 32) | (unsigned long long)s);
+    F = (int)(packed >> 32);
+    S = (int)(packed & 0xFFFFFFFFull);
+    fsum = wave_sum_f64(sum);
+    minF = wave_min_f32(mf);
+}
+
+// Same for the LDS list, four scores per lane and step.  The fp64 thresholds are replaced by
+// their round-down fp32 values: for an fp32 score v, v > x  <=>  v > rd(x).  The four scores of
+// a step are added in fp32, the step totals in fp64.  A sum with a single fractional score stays
+// exact, which the flat case (root exactly on a breakpoint, sup rule) relies on.
+__device__ __forceinline__ void eval_piece(const ListLds& L, int t, double x, int lane, int& F, int& S,
+                                           double& fsum, float& minF)
+{
+    const float xf = __double2float_rd(x), x1f = __double2float_rd(x + 1.0);
+    int f = 0, s = 0;
+    double sum = 0.0;
+    float mf = INFINITY;
+    auto add4 = [&](float4 q) {
+        float part = 0.0f;
+        auto one = [&](float v) {
+            const bool a = v > xf, b = v > x1f;
+            s += a ? 1 : 0;
+            f += b ? 1 : 0;
+            part += (a && !b) ? v : 0.0f;
+            mf = fminf(mf, b ? v : INFINITY);
+        };
+        one(q.x); one(q.y); one(q.z); one(q.w);
+        sum += (double)part;
+    };
+    const float4* v4 = (const float4*)L.v;
+    for (int i = lane; i < L.mo4 / 4; i += 64) add4(v4[i]);
+    const int nc = t - L.t0 + 1;  // chunk scores inside prefix t
+    const float4* c4 = (const float4*)(L.v + L.mo4);
+    for (int i = lane; i < (L.M - L.mo4) / 4; i += 64) {
+        float4 q = c4[i];
+        const int c = 4 * i;
+        q.x = (c < nc) ? q.x : -INFINITY;
+        q.y = (c + 1 < nc) ? q.y : -INFINITY;
+        q.z = (c + 2 < nc) ? q.z : -INFINITY;
+        q.w = (c + 3 < nc) ? q.w : -INFINITY;
+        add4(q);
     }
     unsigned long long packed = wave_sum_u64(((unsigned long long)f << 32) | (unsigned long long)s);
     F = (int)(packed >> 32);
@@ -238,61 +309,74 @@ __device__ double solve_tau(const List& L, int t, int k, double start, int lane,
     return x;
 }
 
-// k-th largest selection key among list entries at positions < tlim (at least k of them
-// exist).  MSB-first radix select, 8 bits a round, one 256-bin LDS histogram per wave.
+// k-th largest selection key among list entries at positions < tlim (at least k of them exist;
+// returns 0 otherwise).  Whole workgroup, MSB-first radix select, 8 bits a round, one 256-bin
+// LDS histogram; every thread returns the same key.
 template <class List>
-__device__ unsigned long long kth_largest(const List& L, int tlim, int k, int lane, unsigned* hist)
+__device__ unsigned long long block_kth_largest(const List& L, int tlim, int k, unsigned* hist, unsigned long long* bc)
 {
+    const int tid = threadIdx.x, lane = tid & 63;
     unsigned long long prefix = 0;  // decided high bits
     int r = k;                      // rank wanted among the entries matching the prefix
     for (int round = 0; round < 8; round++) {
         const int shift = 56 - 8 * round;
-        for (int b = lane; b < 256; b += 64) hist[b] = 0;
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        for (int i = lane; i < L.M; i += 64) {
-            int p = L.pos(i);
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int i = tid; i < L.M; i += NT_CHUNK) {
+            const int p = L.pos(i);
             if (p < tlim) {
-                unsigned long long key = sel_key(L.val(i), p);
-                bool match = (round == 0) || ((key >> (shift + 8)) == (prefix >> (shift + 8)));
+                const unsigned long long key = sel_key(L.val(i), p);
+                const bool match = (round == 0) || ((key >> (shift + 8)) == (prefix >> (shift + 8)));
                 if (match) atomicAdd(&hist[(unsigned)(key >> shift) & 255u], 1u);
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        // lane l owns bins 4l..4l+3; suffix sums from the top bin down
-        unsigned h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2],
-                 h3 = hist[4 * lane + 3];
-        unsigned lsum = h0 + h1 + h2 + h3;
-        unsigned suf = lsum;  // inclusive suffix sum over lanes >= this one
+        __syncthreads();
+        if (tid < 64) {  // wave 0: lane l owns bins 4l..4l+3; suffix sums from the top bin down
+            const unsigned h0 = hist[4 * lane], h1 = hist[4 * lane + 1], h2 = hist[4 * lane + 2], h3 = hist[4 * lane + 3];
+            const unsigned lsum = h0 + h1 + h2 + h3;
+            unsigned suf = lsum;
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            unsigned y = __shfl_down(suf, o, 64);
-            if (lane + o < 64) suf += y;
+            for (int o = 1; o < 64; o <<= 1) {
+                const unsigned y = __shfl_down(suf, o, 64);
+                if (lane + o < 64) suf += y;
+            }
+            const unsigned long long ball = __ballot(suf >= (unsigned)r);
+            unsigned long long res = 0;  // digit | count << 16 | above << 32 ; 0xFFFF... = not enough entries
+            if (ball == 0) res = ~0ull;
+            else {
+                const int ls = 63 - __builtin_clzll(ball);
+                unsigned above = __shfl(suf - lsum, ls, 64);
+                const unsigned b3 = __shfl(h3, ls, 64), b2 = __shfl(h2, ls, 64), b1 = __shfl(h1, ls, 64),
+                               b0 = __shfl(h0, ls, 64);
+                unsigned digit, cnt;
+                if (above + b3 >= (unsigned)r) { digit = 4 * ls + 3; cnt = b3; }
+                else if (above + b3 + b2 >= (unsigned)r) { digit = 4 * ls + 2; above += b3; cnt = b2; }
+                else if (above + b3 + b2 + b1 >= (unsigned)r) { digit = 4 * ls + 1; above += b3 + b2; cnt = b1; }
+                else { digit = 4 * ls; above += b3 + b2 + b1; cnt = b0; }
+                res = (unsigned long long)digit | ((unsigned long long)min(cnt, 0xFFFFu) << 16) | ((unsigned long long)above << 32);
+            }
+            if (lane == 0) *bc = res;
         }
-        unsigned long long ball = __ballot(suf >= (unsigned)r);
-        if (ball == 0) return 0;  // fewer than k entries: caller's precondition broken
-        int ls = 63 - __builtin_clzll(ball);  // highest lane whose suffix reaches r
-        unsigned above = __shfl(suf - lsum, ls, 64);  // entries in bins above that lane
-        unsigned b3 = __shfl(h3, ls, 64), b2 = __shfl(h2, ls, 64), b1 = __shfl(h1, ls, 64),
-                 b0 = __shfl(h0, ls, 64);
-        int digit;
-        unsigned cnt;
-        if (above + b3 >= (unsigned)r) { digit = 4 * ls + 3; cnt = b3; }
-        else if (above + b3 + b2 >= (unsigned)r) { digit = 4 * ls + 2; above += b3; cnt = b2; }
-        else if (above + b3 + b2 + b1 >= (unsigned)r) { digit = 4 * ls + 1; above += b3 + b2; cnt = b1; }
-        else { digit = 4 * ls; above += b3 + b2 + b1; cnt = b0; }
-        r -= (int)above;
-        prefix |= (unsigned long long)digit << shift;
-        if (cnt == 1 && shift > 0) {  // a single entry carries this prefix: fetch it
-            unsigned long long best = 0;
-            for (int i = lane; i < L.M; i += 64) {
-                int p = L.pos(i);
+        __syncthreads();
+        const unsigned long long res = *bc;
+        if (res == ~0ull) return 0;
+        r -= (int)(res >> 32);
+        prefix |= (res & 0xFFull) << shift;
+        if (((res >> 16) & 0xFFFFull) == 1 && shift > 0) {  // a single entry carries this prefix: fetch it
+            __syncthreads();
+            if (tid == 0) *bc = 0;
+            __syncthreads();
+            for (int i = tid; i < L.M; i += NT_CHUNK) {
+                const int p = L.pos(i);
                 if (p < tlim) {
-                    unsigned long long key = sel_key(L.val(i), p);
-                    if ((key >> shift) == (prefix >> shift)) best = key;
+                    const unsigned long long key = sel_key(L.val(i), p);
+                    if ((key >> shift) == (prefix >> shift)) *bc = key;  // exactly one writer
                 }
             }
-            return wave_max_u64(best);
+            __syncthreads();
+            return *bc;
         }
+        __syncthreads();
     }
     return prefix;
 }
@@ -312,6 +396,26 @@ __device__ __forceinline__ unsigned long long succ_key(const List& L, int tlim, 
     }
     return wave_min_u64(best);
 }
+// LDS list: branch-free scan of 64-bit keys, four entries per lane and step.
+__device__ __forceinline__ unsigned long long succ_key(const ListLds& L, int tlim, unsigned long long theta, int lane)
+{
+    unsigned long long best = ~0ull;
+    auto one = [&](float v, int p) {
+        const unsigned long long key = sel_key(v, p);
+        const bool ok = (p < tlim) && (key > theta) && (key < best);
+        best = ok ? key : best;
+    };
+    const float4* v4 = (const float4*)L.v;
+    const int4* i4 = (const int4*)L.idx;
+    for (int i = lane; i < L.mo4 / 4; i += 64) {
+        const float4 q = v4[i];
+        const int4 p = i4[i];
+        one(q.x, p.x); one(q.y, p.y); one(q.z, p.z); one(q.w, p.w);
+    }
+    const int nc = tlim - L.t0;  // chunk scores at positions < tlim
+    for (int c = lane; c < nc; c += 64) one(L.v[L.mo4 + c], L.t0 + c);
+    return wave_min_u64(best);
+}
 
 template <class List>
 __device__ __forceinline__ unsigned long long min_key(const List& L, int tlim, int lane)
@@ -327,30 +431,29 @@ __device__ __forceinline__ unsigned long long min_key(const List& L, int tlim, i
     return wave_min_u64(best);
 }
 
-// One wave, prefixes [ta, tb): writes tau (for t >= k) and theta keys into th[t - t0].
+// One wave, thresholds of prefixes [ta, tb) (those longer than k).
 template <class List>
-__device__ void wave_prefixes(const List& L, const float* __restrict__ ur, float* __restrict__ tr,
-                              int t0, int ta, int tb, int k, float lo, int lane, unsigned* hist,
-                              unsigned long long* th, unsigned long long* th_start, int* status)
+__device__ void wave_tau(const List& L, const float* __restrict__ ur, float* __restrict__ tr, int ta, int tb,
+                         int k, float start0, int lane, int* status)
 {
-    // ---- tau ----
+    const float my_u = (ta + lane < tb) ? ur[ta + lane] : 0.0f;  // tb - ta <= 64
     bool have_prev = false;
     double tau_prev = 0.0;
     for (int t = ta; t < tb; t++) {
-        if (t + 1 <= k) continue;  // written by the short-prefix kernel
-        const double ut = (double)ur[t];
+        if (t + 1 <= k) continue;  // written by the coarse kernel's short-prefix scan
+        const double ut = (double)readlane_f32(my_u, t - ta);
         double tau;
         if (have_prev && !(ut > tau_prev)) {
             tau = tau_prev;  // the new score is below the threshold: nothing changes
         } else {
             double start;
             if (have_prev) start = tau_prev;
-            else if (lo > -INFINITY) start = (double)lo;
-            else {  // no bound yet: min(prefix) - 1 has f = t+1 >= k
-                float mn = INFINITY;
+            else if (start0 > -INFINITY) start = (double)start0;
+            else {  // no bound known: min(prefix) - 1 has f = t+1 >= k
+                float m2 = INFINITY;
                 for (int i = lane; i < L.M; i += 64)
-                    if (L.pos(i) <= t) mn = fminf(mn, L.val(i));
-                start = (double)wave_min_f32(mn) - 1.0;
+                    if (L.pos(i) <= t) m2 = fminf(m2, L.val(i));
+                start = (double)wave_min_f32(m2) - 1.0;
             }
             tau = solve_tau(L, t, k, start, lane, status);
         }
@@ -358,22 +461,29 @@ __device__ void wave_prefixes(const List& L, const float* __restrict__ ur, float
         have_prev = true;
         if (lane == 0) tr[t] = (float)tau;
     }
-    // ---- theta: k-th largest selection key of each prefix (0 while the prefix is shorter than k) ----
-    unsigned long long theta = 0;
-    if (ta >= k) theta = kth_largest(L, ta, k, lane, hist);
-    if (ta == t0 && lane == 0) *th_start = theta;
-    for (int t = ta; t < tb; t++) {
-        const int len = t + 1;
-        if (len == k) {
-            theta = min_key(L, t + 1, lane);
-        } else if (len > k) {
-            unsigned long long e = sel_key(ur[t], t);
-            if (e > theta) {
-                unsigned long long sc = succ_key(L, t, theta, lane);
-                theta = e < sc ? e : sc;
+}
+
+// One wave, the whole chunk: theta_t = k-th largest selection key of prefix t (0 while the
+// prefix is shorter than k), by "newcomer in, smallest out" starting from theta_{t0-1}.
+template <class List>
+__device__ void wave_theta(const List& L, const float* __restrict__ ur, int t0, int t1, int k,
+                           unsigned long long theta, int lane, unsigned long long* th)
+{
+    for (int tb = t0; tb < t1; tb += 64) {
+        const float my_u = (tb + lane < t1) ? ur[tb + lane] : 0.0f;
+        for (int t = tb; t < min(t1, tb + 64); t++) {
+            const int len = t + 1;
+            if (len == k) {
+                theta = min_key(L, t + 1, lane);
+            } else if (len > k) {
+                const unsigned long long e = sel_key(readlane_f32(my_u, t - tb), t);
+                if (e > theta) {
+                    const unsigned long long sc = succ_key(L, t, theta, lane);
+                    theta = e < sc ? e : sc;
+                }
             }
+            if (lane == 0) th[t - t0] = theta;
         }
-        if (lane == 0) th[t - t0] = theta;
     }
 }
 
@@ -400,18 +510,47 @@ __device__ __forceinline__ void write_death(float v, int j, int t0, int t1, int 
     if (a < t1 - t0) dr[j] = t0 + a;
 }
 
+constexpr int NW_TAU = NW_CHUNK - 1;                     // waves solving tau; the last wave walks theta
+constexpr int TPW_TAU = (CHUNK + NW_TAU - 1) / NW_TAU;   // prefixes per tau wave
+constexpr int SLICE_REG = 8;                             // compaction: scores cached per lane and segment
+
+template <class List>
+__device__ void chunk_body(const List& L, const float* __restrict__ ur, float* __restrict__ tr,
+                           int32_t* __restrict__ dr, int t0, int t1, int k, float lo, unsigned* hist,
+                           unsigned long long* bc, unsigned long long* th, int* status)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    // theta at the chunk start, by the whole workgroup
+    unsigned long long th_start = 0;
+    if (t0 >= k) th_start = block_kth_largest(L, t0, k, hist, bc);
+    // tau lies in [z_(k) - 1, z_(k)), and both ends only rise: theta_{t0-1} - 1 bounds every tau of the chunk
+    float start0 = lo;
+    if (t0 >= k) start0 = fmaxf(lo, __uint_as_float(score_key_inv((uint32_t)(th_start >> 32))) - 1.0f);
+    if (wv < NW_TAU) {
+        const int ta = min(t1, t0 + wv * TPW_TAU), tb = min(t1, ta + TPW_TAU);
+        wave_tau(L, ur, tr, ta, tb, k, start0, lane, status);
+    } else {
+        wave_theta(L, ur, t0, t1, k, th_start, lane, th);
+    }
+    __syncthreads();
+    for (int i = tid; i < L.M; i += NT_CHUNK) {
+        const int p = L.pos(i);
+        if (p < t1) write_death(L.val(i), p, t0, t1, k, th, th_start, dr);
+    }
+}
+
 __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __restrict__ u,
                                                                const float* __restrict__ lo_in,
                                                                float* __restrict__ tau,
                                                                int32_t* __restrict__ death, int n, int k,
                                                                int nsuper, int* __restrict__ status)
 {
-    __shared__ float cand_val[CAP];
-    __shared__ int cand_idx[CAP];
+    __shared__ __align__(16) float cand_val[CAP_PAD];
+    __shared__ __align__(16) int cand_idx[CAP_PAD];
     __shared__ unsigned long long th[CHUNK];
-    __shared__ unsigned hist[NW_CHUNK][256];
+    __shared__ unsigned hist[256];
     __shared__ int wcount[NW_CHUNK + 1];
-    __shared__ unsigned long long th_start;
+    __shared__ unsigned long long bc;
 
     const int c = blockIdx.x, row = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -422,15 +561,21 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
     int32_t* dr = death + (size_t)row * n;
     const float lo = lo_in[(size_t)row * nsuper + t0 / SUPER];
 
-    // ---- ordered compaction of {j < t0 : u_j > lo}: each wave owns a contiguous slice ----
+    // ---- ordered compaction of {j < t0 : u_j > lo}: each wave owns a contiguous slice, read in
+    // segments of 64*SLICE_REG scores held in registers (independent loads, one latency) ----
     const int per = ((t0 + NW_CHUNK - 1) / NW_CHUNK + 63) / 64 * 64;
     const int sb = min(t0, wv * per), se = min(t0, sb + per);
-    const int iters = (se - sb + 63) / 64;
+    constexpr int SEGN = 64 * SLICE_REG;
     int cnt = 0;
-    for (int it = 0; it < iters; it++) {
-        const int i = sb + it * 64 + lane;
-        bool p = (i < se) && (ur[i] > lo);
-        cnt += __popcll(__ballot(p));
+    for (int g0 = sb; g0 < se; g0 += SEGN) {
+        float z[SLICE_REG];
+#pragma unroll
+        for (int r = 0; r < SLICE_REG; r++) {
+            const int i = g0 + r * 64 + lane;
+            z[r] = (i < se) ? ur[i] : -INFINITY;
+        }
+#pragma unroll
+        for (int r = 0; r < SLICE_REG; r++) cnt += __popcll(__ballot(z[r] > lo));
     }
     if (lane == 0) wcount[wv] = cnt;
     __syncthreads();
@@ -441,43 +586,46 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
     }
     __syncthreads();
     const int m_old = wcount[NW_CHUNK];
-    const bool fits = (m_old + (t1 - t0) <= CAP);
+    const int mo4 = (m_old + 3) & ~3, cn = t1 - t0, cn4 = (cn + 3) & ~3;
+    const bool fits = (m_old + cn <= CAP);
     if (fits) {
         int off = wcount[wv];
-        for (int it = 0; it < iters; it++) {
-            const int i = sb + it * 64 + lane;
-            float v = (i < se) ? ur[i] : 0.0f;
-            bool p = (i < se) && (v > lo);
-            unsigned long long ball = __ballot(p);
-            if (p) {
-                int o = off + __popcll(ball & ((1ull << lane) - 1ull));
-                cand_val[o] = v;
-                cand_idx[o] = i;
+        for (int g0 = sb; g0 < se; g0 += SEGN) {
+            float z[SLICE_REG];
+#pragma unroll
+            for (int r = 0; r < SLICE_REG; r++) {
+                const int i = g0 + r * 64 + lane;
+                z[r] = (i < se) ? ur[i] : -INFINITY;
             }
-            off += __popcll(ball);
+#pragma unroll
+            for (int r = 0; r < SLICE_REG; r++) {
+                const bool p = z[r] > lo;
+                const unsigned long long ball = __ballot(p);
+                if (p) {
+                    const int o = off + __popcll(ball & ((1ull << lane) - 1ull));
+                    cand_val[o] = z[r];
+                    cand_idx[o] = g0 + r * 64 + lane;
+                }
+                off += __popcll(ball);
+            }
         }
-        for (int i = tid; i < t1 - t0; i += NT_CHUNK) {
-            cand_val[m_old + i] = ur[t0 + i];
-            cand_idx[m_old + i] = t0 + i;
+        for (int i = m_old + tid; i < mo4; i += NT_CHUNK) {  // pad the older region to a multiple of 4
+            cand_val[i] = -INFINITY;
+            cand_idx[i] = 0x7FFFFFFF;
+        }
+        for (int i = tid; i < cn4; i += NT_CHUNK) {
+            cand_val[mo4 + i] = (i < cn) ? ur[t0 + i] : -INFINITY;
+            cand_idx[mo4 + i] = (i < cn) ? t0 + i : 0x7FFFFFFF;
         }
     }
     __syncthreads();
 
-    const int ta = min(t1, t0 + wv * TPW), tb = min(t1, ta + TPW);
     if (fits) {
-        ListLds L{cand_val, cand_idx, m_old + (t1 - t0)};
-        wave_prefixes(L, ur, tr, t0, ta, tb, k, lo, lane, hist[wv], th, &th_start, status);
+        ListLds L{cand_val, cand_idx, mo4 + cn4, mo4, t0};
+        chunk_body(L, ur, tr, dr, t0, t1, k, lo, hist, &bc, th, status);
     } else {
         ListGlobal L{ur, t1};
-        wave_prefixes(L, ur, tr, t0, ta, tb, k, -INFINITY, lane, hist[wv], th, &th_start, status);
-    }
-    __syncthreads();
-    const unsigned long long ths = th_start;
-    if (fits) {
-        const int M = m_old + (t1 - t0);
-        for (int i = tid; i < M; i += NT_CHUNK) write_death(cand_val[i], cand_idx[i], t0, t1, k, th, ths, dr);
-    } else {
-        for (int i = tid; i < t1; i += NT_CHUNK) write_death(ur[i], i, t0, t1, k, th, ths, dr);
+        chunk_body(L, ur, tr, dr, t0, t1, k, -INFINITY, hist, &bc, th, status);
     }
 }
 
@@ -533,10 +681,9 @@ int launch_mask(const sparsek_cfg& c, const float* u, float* tau, int32_t* death
     const int nsuper = (c.n + SUPER - 1) / SUPER;
     float* lo = (float*)ws;
     int* status = (int*)((char*)ws + align_up((size_t)rows * nsuper * sizeof(float), 256));
-    hipLaunchKernelGGL(mask_short_prefix_kernel, dim3(rows), dim3(1024), 0, st, u, tau, death, c.n, c.k);
+    hipLaunchKernelGGL(mask_coarse_kernel, dim3(c.k == 0 ? 1 : nsuper, rows), dim3(NT_COARSE), 0, st, u, lo, tau,
+                       death, c.n, c.k, nsuper);
     if (c.k == 0) return launch_status();
-    hipLaunchKernelGGL(mask_coarse_kernel, dim3(nsuper, rows), dim3(NT_COARSE), 0, st, u, lo, death, c.n,
-                       c.k, nsuper);
     if (c.k < c.n) {
         const int nchunks = (c.n + CHUNK - 1) / CHUNK;
         hipLaunchKernelGGL(mask_chunk_kernel, dim3(nchunks, rows), dim3(NT_CHUNK), 0, st, u, lo, tau, death,
