@@ -177,113 +177,90 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(
 //   S^T (keys x queries) = K_tile . Q^T     v_mfma_f32_32x32x16_bf16, K rows from LDS
 //   online softmax down the key axis: every lane owns one query column, so row maxima and
 //   sums stay inside a lane (one exchange with the lane holding the other half of the keys)
-//   O^T (d x queries)   += V_tile^T . P^T   V is written to LDS transposed so that the key
-//   axis is contiguous for the A operand; P^T feeds the B operand straight from registers.
-// K/V rows are gathered from HBM by position with 16-byte/8-byte coalesced loads into
-// registers one tile ahead of the compute.
+//   O^T (d x queries)   += V_tile^T . P^T   the A operand needs the key axis contiguous per
+//   lane: V stays row-major in LDS and is read with the transposing LDS load
+//   (ds_read_b64_tr_b16); P^T feeds the B operand straight from the accumulator layout.
+// K/V rows are gathered from HBM by position straight into LDS (global_load_lds, 16 bytes per
+// lane, no register staging), double-buffered, one tile ahead of the compute, one barrier per
+// tile.  A wave-load moves 1 KB = RPL whole rows; tile row r goes to group r % NL, slot r / NL,
+// and the groups are padded (16 bytes for K, 64 for V) so that the operand reads of 16
+// consecutive lanes fall on distinct banks.
 // ---------------------------------------------------------------------------------
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void glb_void_t;
 
 constexpr int KT = 64;     // keys per tile
-constexpr int SEG = 2304;  // keys whose metadata is staged in LDS at a time (36 tiles)
+constexpr int SEG = 1088;  // keys whose metadata is staged in LDS at a time (17 tiles)
 
 template <int D>
 struct MfmaSmem {
-    uint16_t Ks[KT][D + 8];   // K tile, row-major, rows padded by 16 bytes
-    uint16_t Vt[D][KT + 4];   // V tile transposed, rows padded by 8 bytes
+    static constexpr int RB = D * 2;        // bytes per K/V row
+    static constexpr int RPL = 1024 / RB;   // rows per wave-load
+    static constexpr int NL = KT / RPL;     // wave-loads (row groups) per tile and tensor
+    static constexpr int GSK = 1024 + 16;   // group stride of the K buffer
+    static constexpr int GSV = 1024 + 64;   // group stride of the V buffer
+    unsigned char kb[2][NL * GSK];
+    unsigned char vb[2][NL * GSV];
     int32_t jpos[SEG];        // key position
     int32_t jlast[SEG];       // last query that attends the key: w - 1 + death[j]; -1 = padding
     float ju[SEG];            // key score
     int32_t tile_lmin[SEG / KT];
 };
 
+// Enqueue the gather of one tile (64 rows of K and of V) into buffer `buf`.
 template <int D>
-__device__ __forceinline__ void load_tile(const int32_t* jp, const uint16_t* __restrict__ kh,
-                                          const uint16_t* __restrict__ vh, int tid,
-                                          u32x4 (&kpre)[KT * (D / 8) / 256],
-                                          u32x2 (&vpre)[(KT / 4) * (D / 4) / 256][4])
+__device__ __forceinline__ void issue_tile_loads(MfmaSmem<D>& sm, int buf, const int32_t* jp,
+                                                 const uint16_t* __restrict__ kh, const uint16_t* __restrict__ vh,
+                                                 int wv, int lane)
 {
-    constexpr int KCH = D / 8;
+    using S = MfmaSmem<D>;
+    constexpr int LPR = S::RB / 16;  // lanes per row
+    const int jrow = lane / LPR, c = lane % LPR;
 #pragma unroll
-    for (int x = 0; x < KT * KCH / 256; x++) {
-        const int c = tid + 256 * x;
-        const int r = c / KCH, cc = c % KCH;
-        kpre[x] = *(const u32x4*)(kh + (size_t)jp[r] * D + 8 * cc);
-    }
-#pragma unroll
-    for (int x = 0; x < (KT / 4) * (D / 4) / 256; x++) {
-        const int un = tid + 256 * x;
-        const int dch = un % (D / 4), kg = un / (D / 4);
-#pragma unroll
-        for (int a2 = 0; a2 < 4; a2++)
-            vpre[x][a2] = *(const u32x2*)(vh + (size_t)jp[4 * kg + a2] * D + 4 * dch);
-    }
-}
-
-template <int D>
-__device__ __forceinline__ void store_tile(uint16_t (&Ks)[KT][D + 8], uint16_t (&Vt)[D][KT + 4], int tid,
-                                           const u32x4 (&kpre)[KT * (D / 8) / 256],
-                                           const u32x2 (&vpre)[(KT / 4) * (D / 4) / 256][4])
-{
-    constexpr int KCH = D / 8;
-#pragma unroll
-    for (int x = 0; x < KT * KCH / 256; x++) {
-        const int c = tid + 256 * x;
-        const int r = c / KCH, cc = c % KCH;
-        *(u32x4*)&Ks[r][8 * cc] = kpre[x];
-    }
-#pragma unroll
-    for (int x = 0; x < (KT / 4) * (D / 4) / 256; x++) {
-        const int un = tid + 256 * x;
-        const int dch = un % (D / 4), kg = un / (D / 4);
-        const u32x2 r0 = vpre[x][0], r1 = vpre[x][1], r2 = vpre[x][2], r3 = vpre[x][3];
-        u32x2 t0, t1, t2, t3;  // 4x4 transpose of 16-bit values: t_e = column e of the 4 key rows
-        t0.x = (r0.x & 0xFFFFu) | (r1.x << 16);
-        t0.y = (r2.x & 0xFFFFu) | (r3.x << 16);
-        t1.x = (r0.x >> 16) | (r1.x & 0xFFFF0000u);
-        t1.y = (r2.x >> 16) | (r3.x & 0xFFFF0000u);
-        t2.x = (r0.y & 0xFFFFu) | (r1.y << 16);
-        t2.y = (r2.y & 0xFFFFu) | (r3.y << 16);
-        t3.x = (r0.y >> 16) | (r1.y & 0xFFFF0000u);
-        t3.y = (r2.y >> 16) | (r3.y & 0xFFFF0000u);
-        *(u32x2*)&Vt[4 * dch + 0][4 * kg] = t0;
-        *(u32x2*)&Vt[4 * dch + 1][4 * kg] = t1;
-        *(u32x2*)&Vt[4 * dch + 2][4 * kg] = t2;
-        *(u32x2*)&Vt[4 * dch + 3][4 * kg] = t3;
+    for (int x = 0; x < S::NL / 4; x++) {
+        const int L = wv * (S::NL / 4) + x;
+        const size_t off = (size_t)jp[L + S::NL * jrow] * D + 8 * c;
+        __builtin_amdgcn_global_load_lds((glb_void_t*)(kh + off), (lds_void_t*)&sm.kb[buf][L * S::GSK], 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_void_t*)(vh + off), (lds_void_t*)&sm.vb[buf][L * S::GSV], 16, 0, 0);
     }
 }
 
 // Tile kinds, chosen per wave and tile:
 //   FAST       contiguous keys inside every query's window and not in its future: no mask, gate 1
-//   LIST       selected keys that outlive every query of the wave: gates, no mask
-//   LIST_MASK  selected keys, some of which expire inside the wave's query range
+//   LIST_MASK  selected keys (gates; a key may expire inside the wave's query range)
 //   CONT       contiguous keys at the causal diagonal or at the window's trailing edge
-enum { TILE_FAST = 0, TILE_LIST = 1, TILE_LIST_MASK = 2, TILE_CONT = 3 };
+enum { TILE_FAST = 0, TILE_LIST_MASK = 2, TILE_CONT = 3 };
 
 // One 64-key tile for one wave: S^T = K.Q^T, gates/masks, online softmax, O^T += V^T.P^T.
 // The running maximum m_run is kept in raw logit units (before the softmax scale c2 > 0,
 // which already contains log2 e); p = exp2(s*c2 - m*c2) costs one fma and one v_exp_f32.
 template <int D, int MODE, int KIND>
-__device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int base, int col, int half, int qi, int jbase,
-                                             int w, float tau_q, float c2, const bf16x8 (&qreg)[D / 16],
-                                             f32x16 (&acc_o)[D / 32], float& m_run, float& l_run)
+__device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int buf, int base, int col, int half, int lane,
+                                             int qi, int jbase, int w, float tau_q, float c2,
+                                             const bf16x8 (&qreg)[D / 16], f32x16 (&acc_o)[D / 32], float& m_run,
+                                             float& l_run)
 {
+    using S = MfmaSmem<D>;
     constexpr int DS = D / 16, DB = D / 32;
+    const unsigned char* kbuf = sm.kb[buf];
+    const unsigned char* vbuf = sm.vb[buf];
     f32x16 acc_s[2];
 #pragma unroll
     for (int mb = 0; mb < 2; mb++) {
 #pragma unroll
         for (int r = 0; r < 16; r++) acc_s[mb][r] = 0.0f;
+        const int row = 32 * mb + col;
+        const unsigned char* kr = kbuf + (row % S::NL) * S::GSK + (row / S::NL) * S::RB + 16 * half;
 #pragma unroll
         for (int s = 0; s < DS; s++) {
-            const bf16x8 a = *(const bf16x8*)&sm.Ks[32 * mb + col][16 * s + 8 * half];
+            const bf16x8 a = *(const bf16x8*)(kr + 32 * s);
             acc_s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], acc_s[mb], 0, 0, 0);
         }
-        __builtin_amdgcn_sched_barrier(0);  // keep the operand loads of the next block from piling up
+        __builtin_amdgcn_sched_barrier(0);  // at most one block of operand loads in flight (register budget)
     }
     constexpr bool GATED = (KIND != TILE_FAST) && (MODE != 2);  // the value gate applies
     constexpr bool KGATE = (KIND != TILE_FAST) && (MODE == 0);  // the key gate applies
@@ -319,7 +296,6 @@ __device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int base, int col,
                 acc_s[mb][r] = s2;
                 tmax = fmaxf(tmax, s2);
             }
-            __builtin_amdgcn_sched_barrier(0);  // one group of metadata loads in flight at a time
         }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -352,7 +328,6 @@ __device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int base, int col,
                 }
                 pb[2 * mb + (r >> 3)][r & 7] = (__bf16)pvv;
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
     }
     l_run = l_run * alpha + psum;
@@ -363,13 +338,23 @@ __device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int base, int col,
 #pragma unroll
             for (int r = 0; r < 16; r++) acc_o[x][r] *= alpha;
     }
+    // A operand of O^T += V^T.P^T through transposing LDS loads.  Within each group of 16 lanes,
+    // lane r points at (row r/4, 4-column block r%4) of a 4-row x 16-column patch of V; the load
+    // hands lane i the 4 rows of column i.  MFMA g uses rows 16g + 4*half + {0..3} (k-slots 0..3)
+    // and 16g + 8 + 4*half + {0..3} (k-slots 4..7), the key order P^T already has.
+    const int r16 = lane & 15, grp2 = (lane >> 4) & 1;
 #pragma unroll
     for (int g = 0; g < 4; g++) {
+        const int row0 = 16 * g + 4 * half + (r16 >> 2);
+        const int row1 = row0 + 8;
+        const unsigned char* v0 = vbuf + (row0 % S::NL) * S::GSV + (row0 / S::NL) * S::RB + (16 * grp2 + 4 * (r16 & 3)) * 2;
+        const unsigned char* v1 = vbuf + (row1 % S::NL) * S::GSV + (row1 / S::NL) * S::RB + (16 * grp2 + 4 * (r16 & 3)) * 2;
 #pragma unroll
         for (int x = 0; x < DB; x++) {
-            const bf16x4 lo4 = *(const bf16x4*)&sm.Vt[32 * x + col][16 * g + 4 * half];
-            const bf16x4 hi4 = *(const bf16x4*)&sm.Vt[32 * x + col][16 * g + 8 + 4 * half];
-            const bf16x8 a = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+            const i16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)(v0 + 64 * x));
+            const i16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)(v1 + 64 * x));
+            const bf16x4 lo = __builtin_bit_cast(bf16x4, lo4), hi = __builtin_bit_cast(bf16x4, hi4);
+            const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             acc_o[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[g], acc_o[x], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -386,8 +371,6 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     __shared__ __align__(16) MfmaSmem<D> sm;
     constexpr int DS = D / 16;   // MFMA k-steps over the head dim
     constexpr int DB = D / 32;   // 32-row blocks of O^T
-    constexpr int KLD = KT * (D / 8) / 256;        // 16-byte K chunks per thread per tile
-    constexpr int VUN = (KT / 4) * (D / 4) / 256;  // V 4x4 units per thread per tile
 
     // ---- block -> (head, query block): heads are dealt to the 8 XCDs so that one head's
     // blocks share an L2; late (long) blocks go first
@@ -442,12 +425,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     float m_run = -INFINITY, l_run = 0.0f;
     const float c2 = scale * 1.4426950408889634f;
 
-    u32x4 kpre[KLD];
-    u32x2 vpre[VUN][4];
-
     for (int seg0 = 0; seg0 < nk_total; seg0 += SEG) {
         const int seg_n = min(SEG, nk_total - seg0);
-        __syncthreads();  // previous segment fully consumed
+        __syncthreads();  // previous segment fully consumed (metadata and both tile buffers)
         for (int e = tid; e < seg_n; e += 256) {
             const int E = seg0 + e;
             int j = 0;
@@ -471,16 +451,14 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
             for (int o2 = 32; o2 > 0; o2 >>= 1) lm = min(lm, __shfl_xor(lm, o2, 64));
             if (lane == 0) sm.tile_lmin[t] = lm;
         }
-        // (visibility of tile_lmin is covered by the barriers of the tile loop)
-
         const int ntiles = seg_n / KT;
-        __syncthreads();
-        load_tile<D>(sm.jpos, kh, vh, tid, kpre, vpre);
+        issue_tile_loads<D>(sm, 0, sm.jpos, kh, vh, wv, lane);
         for (int t = 0; t < ntiles; t++) {
-            __syncthreads();  // tile t-1 fully read
-            store_tile<D>(sm.Ks, sm.Vt, tid, kpre, vpre);
+            // tile t has landed (this wave's part: vmcnt; the other waves' parts: barrier); the
+            // barrier also says that everybody is done with tile t-1, whose buffer is refilled next
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            if (t + 1 < ntiles) load_tile<D>(sm.jpos + (t + 1) * KT, kh, vh, tid, kpre, vpre);
+            if (t + 1 < ntiles) issue_tile_loads<D>(sm, (t + 1) & 1, sm.jpos + (t + 1) * KT, kh, vh, wv, lane);
 
             // ---- classify the tile for this wave (all conditions are wave-uniform) ----
             const int base = t * KT;
@@ -489,14 +467,14 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
             const int jbase = is_list ? 0 : c0 + (E0 - nkl);  // first position of a contiguous tile
             if (!wave_live) continue;
             if (is_list) {
-                tile_compute<D, MODE, TILE_LIST_MASK>(sm, base, col, half, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
+                tile_compute<D, MODE, TILE_LIST_MASK>(sm, t & 1, base, col, half, lane, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
             } else {
                 if (jbase > qb) continue;  // every key of the tile is in the future of every query of the wave
                 const int jend = jbase + KT - 1;
                 if (jend <= qa && qb - jbase < w && jend <= c_end)
-                    tile_compute<D, MODE, TILE_FAST>(sm, base, col, half, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
+                    tile_compute<D, MODE, TILE_FAST>(sm, t & 1, base, col, half, lane, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
                 else
-                    tile_compute<D, MODE, TILE_CONT>(sm, base, col, half, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
+                    tile_compute<D, MODE, TILE_CONT>(sm, t & 1, base, col, half, lane, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
             }
         }
     }
