@@ -231,13 +231,26 @@ __device__ __forceinline__ void issue_tile_loads(MfmaSmem<D>& sm, int buf, const
 
 // Tile kinds, chosen per wave and tile:
 //   FAST       contiguous keys inside every query's window and not in its future: no mask, gate 1
-//   LIST_MASK  selected keys (gates; a key may expire inside the wave's query range)
+//   LIST       selected keys that outlive every query of the wave: gates, no mask
+//   LIST_MASK  selected keys, some of which expire inside the wave's query range
 //   CONT       contiguous keys at the causal diagonal or at the window's trailing edge
-enum { TILE_FAST = 0, TILE_LIST_MASK = 2, TILE_CONT = 3 };
+enum { TILE_FAST = 0, TILE_LIST = 1, TILE_LIST_MASK = 2, TILE_CONT = 3 };
 
-// One 64-key tile for one wave: S^T = K.Q^T, gates/masks, online softmax, O^T += V^T.P^T.
-// The running maximum m_run is kept in raw logit units (before the softmax scale c2 > 0,
-// which already contains log2 e); p = exp2(s*c2 - m*c2) costs one fma and one v_exp_f32.
+template <int D>
+__device__ __forceinline__ void rescale_o(f32x16 (&acc_o)[D / 32], float alpha)
+{
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int x = 0; x < D / 32; x++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc_o[x][r] *= alpha;
+    }
+}
+
+// One 64-key tile for one wave.  The two 32-key halves of S^T are accumulated as two
+// interleaved (independent) MFMA chains, the softmax bookkeeping (max exchange, reference
+// update, rescale) is done once per tile, and the 16 MFMAs of O^T += V^T.P^T run over four
+// independent accumulators.
 template <int D, int MODE, int KIND>
 __device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int buf, int base, int col, int half, int lane,
                                              int qi, int jbase, int w, float tau_q, float c2,
@@ -245,30 +258,33 @@ __device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int buf, int base,
                                              float& l_run)
 {
     using S = MfmaSmem<D>;
-    constexpr int DS = D / 16, DB = D / 32;
-    const unsigned char* kbuf = sm.kb[buf];
-    const unsigned char* vbuf = sm.vb[buf];
-    f32x16 acc_s[2];
-#pragma unroll
-    for (int mb = 0; mb < 2; mb++) {
-#pragma unroll
-        for (int r = 0; r < 16; r++) acc_s[mb][r] = 0.0f;
-        const int row = 32 * mb + col;
-        const unsigned char* kr = kbuf + (row % S::NL) * S::GSK + (row / S::NL) * S::RB + 16 * half;
-#pragma unroll
-        for (int s = 0; s < DS; s++) {
-            const bf16x8 a = *(const bf16x8*)(kr + 32 * s);
-            acc_s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], acc_s[mb], 0, 0, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);  // at most one block of operand loads in flight (register budget)
-    }
     constexpr bool GATED = (KIND != TILE_FAST) && (MODE != 2);  // the value gate applies
     constexpr bool KGATE = (KIND != TILE_FAST) && (MODE == 0);  // the key gate applies
-    // CONT tiles: key number kk = cst + 4*half of the tile sits dq - kk positions behind the query.
-    // Folding the lane-dependent 4*half into dqh leaves compile-time constants in every compare
-    // (otherwise the 32 per-lane key numbers are hoisted into registers and spill).
-    const int dqh = qi - jbase - 4 * half;
-    const int dqw = dqh - w;  // in the window  <=>  cst > dqw
+    constexpr bool MASK = (KIND == TILE_LIST_MASK) || (KIND == TILE_CONT);
+    constexpr float LAZY_LOG2 = 8.0f;
+    const unsigned char* kbuf = sm.kb[buf];
+    const unsigned char* vbuf = sm.vb[buf];
+    const int32_t* jlast = sm.jlast + base;
+    const float* ju = sm.ju + base;
+    const int dqh = qi - jbase - 4 * half;  // CONT: key number cst + 4*half sits dq - kk behind the query
+    const int dqw = dqh - w;                // in the window  <=>  cst > dqw
+    // ---- S^T = K . Q^T ----
+    f32x16 acc_s[2];
+    {
+        const unsigned char* kr0 = kbuf + (col % S::NL) * S::GSK + (col / S::NL) * S::RB + 16 * half;
+        const unsigned char* kr1 = kbuf + ((32 + col) % S::NL) * S::GSK + ((32 + col) / S::NL) * S::RB + 16 * half;
+#pragma unroll
+        for (int r = 0; r < 16; r++) { acc_s[0][r] = 0.0f; acc_s[1][r] = 0.0f; }
+#pragma unroll
+        for (int s = 0; s < D / 16; s++) {
+            const bf16x8 a0 = *(const bf16x8*)(kr0 + 32 * s);
+            const bf16x8 a1 = *(const bf16x8*)(kr1 + 32 * s);
+            acc_s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[s], acc_s[0], 0, 0, 0);
+            acc_s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[s], acc_s[1], 0, 0, 0);
+            if ((s & 3) == 3) __builtin_amdgcn_sched_barrier(0);  // bound the operand loads in flight
+        }
+    }
+    // ---- gates, masks, maximum ----
     float tmax = -INFINITY;
 #pragma unroll
     for (int mb = 0; mb < 2; mb++) {
@@ -277,15 +293,17 @@ __device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int buf, int base,
             const int kb = 32 * mb + 8 * g4 + 4 * half;  // first of 4 consecutive keys
             int4 L4 = make_int4(0, 0, 0, 0);
             float4 U4 = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (KIND == TILE_LIST_MASK || KIND == TILE_CONT) L4 = *(const int4*)&sm.jlast[base + kb];
-            if (KGATE) U4 = *(const float4*)&sm.ju[base + kb];
+            if (MASK) L4 = *(const int4*)&jlast[kb];
+            if (KGATE) U4 = *(const float4*)&ju[kb];
 #pragma unroll
             for (int e = 0; e < 4; e++) {
                 const int r = 4 * g4 + e;
                 float s2 = acc_s[mb][r];
                 const int Lj = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
                 const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
-                const int cst = 32 * mb + 8 * g4 + e;  // key number within the tile minus 4*half
+                // key number within the tile minus the lane-dependent 4*half (folded into dqh, dqw so
+                // that every compare below has a compile-time constant on one side)
+                const int cst = 32 * mb + 8 * g4 + e;
                 if (KGATE) {
                     const float g = clip01(uj - tau_q);
                     if (KIND == TILE_CONT) s2 = (cst > dqw) ? s2 : s2 * g;
@@ -297,14 +315,19 @@ __device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int buf, int base,
                 tmax = fmaxf(tmax, s2);
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const float m_new = fmaxf(m_run, tmax);
+    // Lazy reference point: m_run only moves when the maximum grows by more than 2^LAZY_LOG2 in
+    // probability (softmax is shift-invariant; p stays below 2^LAZY_LOG2, harmless in fp32/bf16).
+    // Otherwise some lane of the wave raises its maximum in nearly every tile and the whole
+    // output accumulator would be rescaled every time.
+    const float m_new = (tmax > m_run + LAZY_LOG2 / c2) ? tmax : m_run;
     const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
     const float alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * c2);
     const float mc = m_safe * c2;
     m_run = m_new;
+    // ---- p = exp2(s*c2 - m*c2): one fma and one v_exp_f32 per logit; value gate; P^T in bf16 ----
     float psum = 0.0f;
     bf16x8 pb[4];
 #pragma unroll
@@ -313,14 +336,14 @@ __device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int buf, int base,
         for (int g4 = 0; g4 < 4; g4++) {
             const int kb = 32 * mb + 8 * g4 + 4 * half;
             float4 U4 = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (GATED) U4 = *(const float4*)&sm.ju[base + kb];
+            if (GATED) U4 = *(const float4*)&ju[kb];
 #pragma unroll
             for (int e = 0; e < 4; e++) {
                 const int r = 4 * g4 + e;
                 const float p = __builtin_amdgcn_exp2f(fmaf(acc_s[mb][r], c2, -mc));
                 psum += p;
                 float pvv = p;
-                if (GATED) {  // value gate, recomputed: cheaper than holding 32 registers
+                if (GATED) {  // recomputed: one v_sub with clamp, cheaper than holding 32 registers
                     const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
                     const float g = clip01(uj - tau_q);
                     if (KIND == TILE_CONT) pvv = (32 * mb + 8 * g4 + e > dqw) ? p : p * g;
@@ -329,19 +352,15 @@ __device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int buf, int base,
                 pb[2 * mb + (r >> 3)][r & 7] = (__bf16)pvv;
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
     }
     l_run = l_run * alpha + psum;
-    __builtin_amdgcn_sched_barrier(0);
-    if (__any(alpha != 1.0f)) {
-#pragma unroll
-        for (int x = 0; x < DB; x++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) acc_o[x][r] *= alpha;
-    }
-    // A operand of O^T += V^T.P^T through transposing LDS loads.  Within each group of 16 lanes,
-    // lane r points at (row r/4, 4-column block r%4) of a 4-row x 16-column patch of V; the load
-    // hands lane i the 4 rows of column i.  MFMA g uses rows 16g + 4*half + {0..3} (k-slots 0..3)
-    // and 16g + 8 + 4*half + {0..3} (k-slots 4..7), the key order P^T already has.
+    rescale_o<D>(acc_o, alpha);
+    // ---- O^T += V^T . P^T ----
+    // The A operand comes through transposing LDS loads: within each group of 16 lanes, lane r
+    // points at (row r/4, 4-column block r%4) of a 4-row x 16-column patch of V and receives the
+    // 4 rows of column r.  MFMA g (16 keys) uses rows 16g + 4*half + {0..3} (k-slots 0..3) and
+    // 16g + 8 + 4*half + {0..3} (k-slots 4..7): the key order P^T already has.
     const int r16 = lane & 15, grp2 = (lane >> 4) & 1;
 #pragma unroll
     for (int g = 0; g < 4; g++) {
@@ -350,14 +369,14 @@ __device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int buf, int base,
         const unsigned char* v0 = vbuf + (row0 % S::NL) * S::GSV + (row0 / S::NL) * S::RB + (16 * grp2 + 4 * (r16 & 3)) * 2;
         const unsigned char* v1 = vbuf + (row1 % S::NL) * S::GSV + (row1 / S::NL) * S::RB + (16 * grp2 + 4 * (r16 & 3)) * 2;
 #pragma unroll
-        for (int x = 0; x < DB; x++) {
+        for (int x = 0; x < D / 32; x++) {
             const i16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)(v0 + 64 * x));
             const i16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)(v1 + 64 * x));
             const bf16x4 lo = __builtin_bit_cast(bf16x4, lo4), hi = __builtin_bit_cast(bf16x4, hi4);
             const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             acc_o[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[g], acc_o[x], 0, 0, 0);
         }
-        __builtin_amdgcn_sched_barrier(0);
+        if (g & 1) __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -467,7 +486,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
             const int jbase = is_list ? 0 : c0 + (E0 - nkl);  // first position of a contiguous tile
             if (!wave_live) continue;
             if (is_list) {
-                tile_compute<D, MODE, TILE_LIST_MASK>(sm, t & 1, base, col, half, lane, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
+                if (sm.tile_lmin[t] >= qb)
+                    tile_compute<D, MODE, TILE_LIST>(sm, t & 1, base, col, half, lane, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
+                else
+                    tile_compute<D, MODE, TILE_LIST_MASK>(sm, t & 1, base, col, half, lane, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
             } else {
                 if (jbase > qb) continue;  // every key of the tile is in the future of every query of the wave
                 const int jend = jbase + KT - 1;
