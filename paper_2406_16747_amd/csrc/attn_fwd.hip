@@ -10,10 +10,10 @@
 // with a per-pair validity/gate test.  That turns the per-query sparse gather into dense
 // (queries x keys) tiles.
 #include "common.hpp"
+#include "attn_tiles.hpp"
 
 namespace spk {
 
-constexpr int QB = 128;  // queries per block (shared by the list builder and the kernels)
 
 static inline int nblocks(int n) { return (n + QB - 1) / QB; }
 
@@ -186,49 +186,6 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(
 // and the groups are padded (16 bytes for K, 64 for V) so that the operand reads of 16
 // consecutive lanes fall on distinct banks.
 // ---------------------------------------------------------------------------------
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef short i16x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void glb_void_t;
-
-constexpr int KT = 64;     // keys per tile
-constexpr int SEG = 1088;  // keys whose metadata is staged in LDS at a time (17 tiles)
-
-template <int D>
-struct MfmaSmem {
-    static constexpr int RB = D * 2;        // bytes per K/V row
-    static constexpr int RPL = 1024 / RB;   // rows per wave-load
-    static constexpr int NL = KT / RPL;     // wave-loads (row groups) per tile and tensor
-    static constexpr int GSK = 1024 + 16;   // group stride of the K buffer
-    static constexpr int GSV = 1024 + 64;   // group stride of the V buffer
-    unsigned char kb[2][NL * GSK];
-    unsigned char vb[2][NL * GSV];
-    int32_t jpos[SEG];        // key position
-    int32_t jlast[SEG];       // last query that attends the key: w - 1 + death[j]; -1 = padding
-    float ju[SEG];            // key score
-    int32_t tile_lmin[SEG / KT];
-};
-
-// Enqueue the gather of one tile (64 rows of K and of V) into buffer `buf`.
-template <int D>
-__device__ __forceinline__ void issue_tile_loads(MfmaSmem<D>& sm, int buf, const int32_t* jp,
-                                                 const uint16_t* __restrict__ kh, const uint16_t* __restrict__ vh,
-                                                 int wv, int lane)
-{
-    using S = MfmaSmem<D>;
-    constexpr int LPR = S::RB / 16;  // lanes per row
-    const int jrow = lane / LPR, c = lane % LPR;
-#pragma unroll
-    for (int x = 0; x < S::NL / 4; x++) {
-        const int L = wv * (S::NL / 4) + x;
-        const size_t off = (size_t)jp[L + S::NL * jrow] * D + 8 * c;
-        __builtin_amdgcn_global_load_lds((glb_void_t*)(kh + off), (lds_void_t*)&sm.kb[buf][L * S::GSK], 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((glb_void_t*)(vh + off), (lds_void_t*)&sm.vb[buf][L * S::GSV], 16, 0, 0);
-    }
-}
-
 // Tile kinds, chosen per wave and tile:
 //   FAST       contiguous keys inside every query's window and not in its future: no mask, gate 1
 //   LIST       selected keys that outlive every query of the wave: gates, no mask
@@ -471,13 +428,13 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
             if (lane == 0) sm.tile_lmin[t] = lm;
         }
         const int ntiles = seg_n / KT;
-        issue_tile_loads<D>(sm, 0, sm.jpos, kh, vh, wv, lane);
+        issue_tile_loads<D, 64>(sm, 0, sm.jpos, kh, vh, wv, lane);
         for (int t = 0; t < ntiles; t++) {
             // tile t has landed (this wave's part: vmcnt; the other waves' parts: barrier); the
             // barrier also says that everybody is done with tile t-1, whose buffer is refilled next
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            if (t + 1 < ntiles) issue_tile_loads<D>(sm, (t + 1) & 1, sm.jpos + (t + 1) * KT, kh, vh, wv, lane);
+            if (t + 1 < ntiles) issue_tile_loads<D, 64>(sm, (t + 1) & 1, sm.jpos + (t + 1) * KT, kh, vh, wv, lane);
 
             // ---- classify the tile for this wave (all conditions are wave-uniform) ----
             const int base = t * KT;

@@ -1,0 +1,54 @@
+// Shared by the attention forward and the mask-backward MFMA kernels: vector types, tile
+// geometry, the LDS staging area and the direct-to-LDS gather of one K/V tile.
+#pragma once
+#include "common.hpp"
+
+namespace spk {
+
+constexpr int QB = 128;  // queries per workgroup block (also the granularity of the per-block top-k lists)
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void glb_void_t;
+
+constexpr int KT = 64;     // keys per tile
+constexpr int SEG = 1088;  // keys whose metadata is staged in LDS at a time (17 tiles)
+
+template <int D, int VPAD = 64>
+struct MfmaSmem {
+    static constexpr int RB = D * 2;        // bytes per K/V row
+    static constexpr int RPL = 1024 / RB;   // rows per wave-load
+    static constexpr int NL = KT / RPL;     // wave-loads (row groups) per tile and tensor
+    static constexpr int GSK = 1024 + 16;   // group stride of the K buffer
+    static constexpr int GSV = 1024 + VPAD; // group stride of the V buffer (64: transposing reads, 16: row reads)
+    unsigned char kb[2][NL * GSK];
+    unsigned char vb[2][NL * GSV];
+    int32_t jpos[SEG];        // key position
+    int32_t jlast[SEG];       // last query that attends the key: w - 1 + death[j]; -1 = padding
+    float ju[SEG];            // key score
+    int32_t tile_lmin[SEG / KT];
+};
+
+// Enqueue the gather of one tile (64 rows of K and of V) into buffer `buf`.
+template <int D, int VPAD>
+__device__ __forceinline__ void issue_tile_loads(MfmaSmem<D, VPAD>& sm, int buf, const int32_t* jp,
+                                                 const uint16_t* __restrict__ kh, const uint16_t* __restrict__ vh,
+                                                 int wv, int lane)
+{
+    using S = MfmaSmem<D, VPAD>;
+    constexpr int LPR = S::RB / 16;  // lanes per row
+    const int jrow = lane / LPR, c = lane % LPR;
+#pragma unroll
+    for (int x = 0; x < S::NL / 4; x++) {
+        const int L = wv * (S::NL / 4) + x;
+        const size_t off = (size_t)jp[L + S::NL * jrow] * D + 8 * c;
+        __builtin_amdgcn_global_load_lds((glb_void_t*)(kh + off), (lds_void_t*)&sm.kb[buf][L * S::GSK], 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_void_t*)(vh + off), (lds_void_t*)&sm.vb[buf][L * S::GSV], 16, 0, 0);
+    }
+}
+
+
+}  // namespace spk

@@ -12,10 +12,11 @@
 //   g_ij = p_ij (dO_i.v_j)                                          value gate (modes 0, 1)
 //        + scale (q_i.k_j) p_ij (m_ij dO_i.v_j - dO_i.o_i)          key gate   (mode 0)
 #include "common.hpp"
+#include "attn_tiles.hpp"
 
 namespace spk {
 
-constexpr int QB_B = 128;  // must equal the forward's query block (the lists are shared code)
+constexpr int QB_B = QB;
 
 // implemented in attn_fwd.hip
 void launch_block_lists(const sparsek_cfg& c, const int32_t* death, int32_t* lists, int32_t* counts,
@@ -142,6 +143,258 @@ __global__ __launch_bounds__(256) void mask_bwd_generic_kernel(
 }
 
 // ---------------------------------------------------------------------------------
+// MFMA main kernel (bf16, D = 64 or 128).  Same blocking as the forward: 128 queries x 4
+// waves, 64-key tiles gathered straight into LDS, but only over keys that can carry a soft
+// gate for some query of the block: the block's top-k list and the contiguous keys that have
+// already left the window (positions <= i0 + 127 - w).  Per tile two contractions over d,
+//   S^T  = K . Q^T    (recomputes the logits)      DV^T = V . dO^T   (dO_i . v_j),
+// then g_ij elementwise; row sums stay in the lane that owns the query, column sums are
+// reduced across the 32 query lanes with a halving butterfly (31 exchanges for 32 keys),
+// combined over the 4 waves in LDS and added to C[] with one atomic per key and tile.
+// ---------------------------------------------------------------------------------
+template <int D, int MODE, bool LIST>
+__device__ __forceinline__ void bwd_tile(MfmaSmem<D, 16>& sm, float* colsum, int buf, int base, int col, int half,
+                                         int lane, int qi, bool qlive, int jbase, int w, float tau_q, float scale,
+                                         float lse2, float Di, const bf16x8 (&qreg)[D / 16],
+                                         const bf16x8 (&dreg)[D / 16], float& rowsum)
+{
+    using S = MfmaSmem<D, 16>;
+    const unsigned char* kbuf = sm.kb[buf];
+    const unsigned char* vbuf = sm.vb[buf];
+    f32x16 acc_s[2], acc_d[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; mb++) {
+        const int row = 32 * mb + col;
+        const int off = (row % S::NL) * S::GSK + (row / S::NL) * S::RB + 16 * half;
+#pragma unroll
+        for (int r = 0; r < 16; r++) { acc_s[mb][r] = 0.0f; acc_d[mb][r] = 0.0f; }
+#pragma unroll
+        for (int s = 0; s < D / 16; s++) {
+            const bf16x8 ka = *(const bf16x8*)(kbuf + off + 32 * s);
+            const bf16x8 va = *(const bf16x8*)(vbuf + off + 32 * s);
+            acc_s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], acc_s[mb], 0, 0, 0);
+            acc_d[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dreg[s], acc_d[mb], 0, 0, 0);
+            if ((s & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    const int dqh = qi - jbase - 4 * half;  // contiguous tiles: key number cst + 4*half sits dq - kk behind the query
+    const int dqw = dqh - w;                // outside the window  <=>  cst <= dqw
+    const float c2 = scale * 1.4426950408889634f;
+    float gv[32];
+#pragma unroll
+    for (int mb = 0; mb < 2; mb++) {
+#pragma unroll
+        for (int g4 = 0; g4 < 4; g4++) {
+            const int kb = 32 * mb + 8 * g4 + 4 * half;
+            const int4 L4 = *(const int4*)&sm.jlast[base + kb];
+            const float4 U4 = *(const float4*)&sm.ju[base + kb];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const int r = 4 * g4 + e;
+                const int Lj = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
+                const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
+                const int cst = 32 * mb + 8 * g4 + e;
+                bool valid = qlive && (qi <= Lj);
+                if (!LIST) valid = valid && (cst <= dqw);
+                // strictly fractional gate: tau < u < tau + 1, the upper test exact in fp64
+                const float m = uj - tau_q;
+                const bool frac = (uj > tau_q) && ((double)uj < (double)tau_q + 1.0);
+                const float mg = clip01(m);
+                const float qk = acc_s[mb][r], dov = acc_d[mb][r];
+                const float p = __builtin_amdgcn_exp2f(fmaf(qk * (MODE == 0 ? mg : 1.0f), c2, -lse2));
+                float g = p * dov;
+                if (MODE == 0) g = fmaf(scale * qk * p, fmaf(mg, dov, -Di), g);
+                g = (valid && frac) ? g : 0.0f;
+                gv[16 * mb + r] = g;
+                rowsum += g;
+            }
+        }
+    }
+    // ---- column sums over the 32 queries of this half-wave: halving butterfly ----
+    // after the step with partner lane^b a lane keeps the values whose index has bit b equal to
+    // its own lane bit; at the end lane c (0..31) holds the total of value index c
+    const int c31 = lane & 31;
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+        const bool up = c31 & 16;
+        const float send = up ? gv[r] : gv[r + 16];
+        const float keep = up ? gv[r + 16] : gv[r];
+        gv[r] = keep + __shfl_xor(send, 16, 64);
+    }
+#pragma unroll
+    for (int r = 0; r < 8; r++) {
+        const bool up = c31 & 8;
+        const float send = up ? gv[r] : gv[r + 8];
+        const float keep = up ? gv[r + 8] : gv[r];
+        gv[r] = keep + __shfl_xor(send, 8, 64);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        const bool up = c31 & 4;
+        const float send = up ? gv[r] : gv[r + 4];
+        const float keep = up ? gv[r + 4] : gv[r];
+        gv[r] = keep + __shfl_xor(send, 4, 64);
+    }
+#pragma unroll
+    for (int r = 0; r < 2; r++) {
+        const bool up = c31 & 2;
+        const float send = up ? gv[r] : gv[r + 2];
+        const float keep = up ? gv[r + 2] : gv[r];
+        gv[r] = keep + dpp_f32(send, 1);  // quad swap [2,3,0,1] = lane ^ 2
+    }
+    {
+        const bool up = c31 & 1;
+        const float send = up ? gv[0] : gv[1];
+        const float keep = up ? gv[1] : gv[0];
+        gv[0] = keep + dpp_f32(send, 0);  // quad swap [1,0,3,2] = lane ^ 1
+    }
+    // value index c31 = 16*mb + r  ->  key number 32*mb + 8*(r/4) + 4*half + r%4
+    const int mbk = c31 >> 4, rk = c31 & 15;
+    const int keyn = 32 * mbk + 8 * (rk >> 2) + 4 * half + (rk & 3);
+    if (gv[0] != 0.0f) atomicAdd(&colsum[keyn], gv[0]);
+}
+
+template <int D, int MODE>
+__global__ __launch_bounds__(256, 2) void mask_bwd_mfma_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ kk, const uint16_t* __restrict__ v,
+    const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
+    const int32_t* __restrict__ lists, const int32_t* __restrict__ counts, const uint16_t* __restrict__ o,
+    const float* __restrict__ lse, const uint16_t* __restrict__ dO, float* __restrict__ A, float* __restrict__ C,
+    int H, int Gu, int n, int k, int w, float scale, int nb, int BH)
+{
+    __shared__ __align__(16) MfmaSmem<D, 16> sm;
+    __shared__ float colsum[KT];
+    constexpr int DS = D / 16;
+    int bh, blk;
+    {
+        const int id = blockIdx.x;
+        if (BH % 8 == 0) {
+            const int xcd = id & 7, slot = id >> 3;
+            bh = (slot / nb) * 8 + xcd;
+            blk = nb - 1 - (slot % nb);
+        } else {
+            bh = id / nb;
+            blk = nb - 1 - (id % nb);
+        }
+    }
+    const int b = bh / H, h = bh % H;
+    const int row = b * Gu + (Gu == 1 ? 0 : h);
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int half = lane >> 5, col = lane & 31;
+    const int i0 = blk * QB;
+    const uint16_t* kh = kk + (size_t)bh * n * D;
+    const uint16_t* vh = v + (size_t)bh * n * D;
+    const float* ur = u + (size_t)row * n;
+    const float* tr = tau + (size_t)row * n;
+    const int32_t* dr = death + (size_t)row * n;
+    const int32_t* list = lists + ((size_t)row * nb + blk) * (size_t)(k > 0 ? k : 1);
+    const int cnt = counts[(size_t)row * nb + blk];
+    const int c0 = max(0, i0 - w + 1);
+    const int c1 = min(n - 1, i0 + QB - 1) - w;  // last contiguous key that is outside some query's window
+    const int nkl = (cnt + KT - 1) / KT * KT;
+    const int nkc = (c1 >= c0) ? (c1 - c0 + 1 + KT - 1) / KT * KT : 0;
+    const int nk_total = nkl + nkc;
+    if (nk_total == 0) return;
+
+    const int qa = i0 + 32 * wv;
+    const int qb = min(qa + 31, n - 1);
+    const int qi = qa + col;
+    const int qrow = min(qi, n - 1);
+    const int Tp = qi - w;
+    const bool qlive = (qi < n) && (Tp >= k);  // prefixes with at most k entries carry no gradient
+    const bool wave_live = (qa < n) && (qb - w >= k);
+    const float tau_q = qlive ? tr[Tp] : 0.0f;
+    const float lse2 = lse[(size_t)bh * n + qrow] * 1.4426950408889634f;
+    bf16x8 qreg[DS], dreg[DS];
+    float dpart = 0.0f;
+#pragma unroll
+    for (int s = 0; s < DS; s++) {
+        const size_t off = ((size_t)bh * n + qrow) * D + 16 * s + 8 * half;
+        qreg[s] = *(const bf16x8*)(q + off);
+        dreg[s] = *(const bf16x8*)(dO + off);
+        const bf16x8 ov = *(const bf16x8*)(o + off);
+#pragma unroll
+        for (int e = 0; e < 8; e++) dpart += (float)dreg[s][e] * (float)ov[e];
+    }
+    const float Di = dpart + __shfl_xor(dpart, 32, 64);
+    float rowsum = 0.0f;
+    if (tid < KT) colsum[tid] = 0.0f;
+
+    for (int seg0 = 0; seg0 < nk_total; seg0 += SEG) {
+        const int seg_n = min(SEG, nk_total - seg0);
+        __syncthreads();
+        for (int e = tid; e < seg_n; e += 256) {
+            const int E = seg0 + e;
+            int j = 0;
+            bool real;
+            if (E < nkl) {
+                real = E < cnt;
+                if (real) j = list[E];
+            } else {
+                j = c0 + (E - nkl);
+                real = j <= c1;
+                if (!real) j = 0;
+            }
+            sm.jpos[e] = j;
+            sm.jlast[e] = real ? (w - 1 + dr[j]) : -1;
+            sm.ju[e] = real ? ur[j] : 0.0f;
+        }
+        __syncthreads();
+        const int ntiles = seg_n / KT;
+        issue_tile_loads<D, 16>(sm, 0, sm.jpos, kh, vh, wv, lane);
+        for (int t = 0; t < ntiles; t++) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();  // tile t landed; everybody is done with tile t-1 and its column sums
+            if (t + 1 < ntiles) issue_tile_loads<D, 16>(sm, (t + 1) & 1, sm.jpos + (t + 1) * KT, kh, vh, wv, lane);
+            if (t > 0 && tid < KT) {  // flush the column sums of tile t-1
+                const float cs = colsum[tid];
+                const int e = (t - 1) * KT + tid;
+                if (cs != 0.0f && sm.jlast[e] >= 0) unsafeAtomicAdd(C + (size_t)row * n + sm.jpos[e], cs);
+                colsum[tid] = 0.0f;
+            }
+            __syncthreads();
+            const int base = t * KT;
+            const int E0 = seg0 + base;
+            const bool is_list = E0 < nkl;
+            const int jbase = is_list ? 0 : c0 + (E0 - nkl);
+            if (!wave_live) continue;
+            if (is_list)
+                bwd_tile<D, MODE, true>(sm, colsum, t & 1, base, col, half, lane, qi, qlive, jbase, w, tau_q, scale, lse2,
+                                        Di, qreg, dreg, rowsum);
+            else if (jbase <= qb - w)
+                bwd_tile<D, MODE, false>(sm, colsum, t & 1, base, col, half, lane, qi, qlive, jbase, w, tau_q, scale,
+                                         lse2, Di, qreg, dreg, rowsum);
+        }
+        __syncthreads();
+        if (tid < KT) {  // column sums of the segment's last tile
+            const float cs = colsum[tid];
+            const int e = (ntiles - 1) * KT + tid;
+            if (cs != 0.0f && sm.jlast[e] >= 0) unsafeAtomicAdd(C + (size_t)row * n + sm.jpos[e], cs);
+            colsum[tid] = 0.0f;
+        }
+    }
+    const float rs = rowsum + __shfl_xor(rowsum, 32, 64);
+    if (qlive && half == 0 && rs != 0.0f) unsafeAtomicAdd(A + (size_t)row * n + Tp, rs);
+}
+
+template <int D>
+static void launch_bwd_mfma(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
+                            const float* tau, const int32_t* death, const int32_t* lists, const int32_t* counts,
+                            const void* o, const float* lse, const void* dO, float* A, float* C, int nb,
+                            hipStream_t st)
+{
+    const int BH = c.B * c.H;
+    dim3 grid(nb * BH);
+#define SPK_LAUNCH_B(MODE)                                                                                    \
+    hipLaunchKernelGGL((mask_bwd_mfma_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q,           \
+                       (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, (const uint16_t*)o, \
+                       lse, (const uint16_t*)dO, A, C, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH)
+    if (c.gate_mode == 0) SPK_LAUNCH_B(0);
+    else SPK_LAUNCH_B(1);
+#undef SPK_LAUNCH_B
+}
+
+// ---------------------------------------------------------------------------------
 // Epilogue 1: per key j the range [a_j, b_j] of prefixes T with j in S*_T; difference array
 // of |S*_T|.  tau is non-decreasing for T >= k-1, so both ends come from binary searches.
 // ---------------------------------------------------------------------------------
@@ -259,7 +512,10 @@ int launch_mask_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
     if (c.gate_mode != 2 && c.k > 0 && c.n > c.w) {
         launch_block_lists(c, death, lists, counts, st);
         dim3 grid(nb, c.B * c.H);
-        if (c.dtype == SPARSEK_F32)
+        if (c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128)) {
+            if (c.d == 64) launch_bwd_mfma<64>(c, q, k, v, u, tau, death, lists, counts, o, lse, dO, A, C, nb, st);
+            else launch_bwd_mfma<128>(c, q, k, v, u, tau, death, lists, counts, o, lse, dO, A, C, nb, st);
+        } else if (c.dtype == SPARSEK_F32)
             hipLaunchKernelGGL(mask_bwd_generic_kernel<float>, grid, dim3(256), 0, st, (const float*)q,
                                (const float*)k, (const float*)v, u, tau, death, lists, counts, (const float*)o, lse,
                                (const float*)dO, A, C, c.H, c.Gu, c.n, c.d, c.k, c.w, c.gate_mode, c.softmax_scale,
