@@ -160,6 +160,8 @@ def main():
     ap.add_argument("--gate-mode", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy (to calibrate FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -171,6 +173,14 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     spk.lib()  # fail loudly if the HIP library is missing
+    if args.copy_calibration:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)  # reads 1 GiB, writes 1 GiB per launch
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": a.numel() * 4, "copy_bytes_written": a.numel() * 4, "launches": 3}))
+        return
 
     cfg = dict(B=1, H=32, Gu=1, n=32768, d=128, k=1024, w=1024)
     q, k, v, u = device_inputs(cfg, seed=1004)
