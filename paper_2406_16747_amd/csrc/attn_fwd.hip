@@ -31,14 +31,17 @@ size_t block_lists_bytes(const sparsek_cfg& c, size_t* counts_offset)
 size_t attn_fwd_ws_bytes(const sparsek_cfg& c) { return block_lists_bytes(c, nullptr); }
 
 // ---------------------------------------------------------------------------------
-// Per (row, block): ascending positions of the top-k of prefix T0 = blk*QB - w.
+// Per (row, block): the positions of the top-k of prefix T0 = blk*QB - w, in two partitions:
+// first the keys that stay selected for every query of the block (death >= T0 + QB, ascending),
+// then, filled from the back, the keys that expire inside the block.  Only the tiles of the
+// second partition need a per-pair validity test.  Each wave owns a quarter of [0, T0]: one
+// counting pass, one barrier, one placement pass.
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void block_lists_kernel(const int32_t* __restrict__ death, int n, int k,
                                                           int w, int nb, int32_t* __restrict__ lists,
                                                           int32_t* __restrict__ counts)
 {
-    __shared__ int wcount[4];
-    __shared__ int base;
+    __shared__ int wstay[4], wgo[4];
     const int blk = blockIdx.x, row = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int T0 = blk * QB - w;
@@ -48,25 +51,47 @@ __global__ __launch_bounds__(256) void block_lists_kernel(const int32_t* __restr
         return;
     }
     const int32_t* dr = death + (size_t)row * n;
-    if (tid == 0) base = 0;
-    __syncthreads();
-    for (int j0 = 0; j0 <= T0; j0 += 256) {
-        int j = j0 + tid;
-        bool p = (j <= T0) && (dr[j] > T0);
-        unsigned long long ball = __ballot(p);
-        if (lane == 0) wcount[wv] = __popcll(ball);
-        __syncthreads();
-        int off = base;
-        for (int i = 0; i < wv; i++) off += wcount[i];
-        if (p) {
-            int o = off + __popcll(ball & ((1ull << lane) - 1ull));
-            if (o < k) lo[o] = j;
+    const int len = T0 + 1;
+    const int per = ((len + 3) / 4 + 255) / 256 * 256;
+    const int j_lo = wv * per, j_hi = min(len, j_lo + per);
+    const int stay_from = T0 + QB;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int ns = 0, ng = 0;
+    for (int j0 = j_lo; j0 < j_hi; j0 += 256) {
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const int j = j0 + 64 * e + lane;
+            const int dj = j < j_hi ? dr[j] : 0;
+            ns += __popcll(__ballot(dj >= stay_from));
+            ng += __popcll(__ballot(dj > T0 && dj < stay_from));
         }
-        __syncthreads();
-        if (tid == 0) base += wcount[0] + wcount[1] + wcount[2] + wcount[3];
-        __syncthreads();
     }
-    if (tid == 0) counts[(size_t)row * nb + blk] = min(base, k);
+    if (lane == 0) { wstay[wv] = ns; wgo[wv] = ng; }
+    __syncthreads();
+    int os = 0, og = 0;
+    for (int i = 0; i < wv; i++) { os += wstay[i]; og += wgo[i]; }
+    // min(k, T0 + 1) for a consistent death array; counted, so that every entry below cnt is written
+    const int cnt = min(k, wstay[0] + wstay[1] + wstay[2] + wstay[3] + wgo[0] + wgo[1] + wgo[2] + wgo[3]);
+    for (int j0 = j_lo; j0 < j_hi; j0 += 256) {
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const int j = j0 + 64 * e + lane;
+            const int dj = j < j_hi ? dr[j] : 0;
+            const bool stay = dj >= stay_from, go = dj > T0 && dj < stay_from;
+            const unsigned long long bs = __ballot(stay), bg = __ballot(go);
+            if (stay) {
+                const int o = os + __popcll(bs & below);
+                if (o < cnt) lo[o] = j;
+            }
+            if (go) {
+                const int o = cnt - 1 - (og + __popcll(bg & below));
+                if (o >= 0) lo[o] = j;
+            }
+            os += __popcll(bs);
+            og += __popcll(bg);
+        }
+    }
+    if (tid == 0) counts[(size_t)row * nb + blk] = cnt;
 }
 
 // ---------------------------------------------------------------------------------
@@ -204,44 +229,19 @@ __device__ __forceinline__ void rescale_o(f32x16 (&acc_o)[D / 32], float alpha)
     }
 }
 
-// One 64-key tile for one wave.  The two 32-key halves of S^T are accumulated as two
-// interleaved (independent) MFMA chains, the softmax bookkeeping (max exchange, reference
-// update, rescale) is done once per tile, and the 16 MFMAs of O^T += V^T.P^T run over four
-// independent accumulators.
-template <int D, int MODE, int KIND>
-__device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int buf, int base, int col, int half, int lane,
-                                             int qi, int jbase, int w, float tau_q, float c2,
-                                             const bf16x8 (&qreg)[D / 16], f32x16 (&acc_o)[D / 32], float& m_run,
-                                             float& l_run)
+// Everything between the two MFMA phases of one tile, specialised by tile kind: gates and masks
+// on the logits, the running maximum with its lazily moved reference point, the exponentials,
+// the value gate, and P^T packed to bf16.  Returns the factor the output accumulator has to be
+// rescaled by (1 for almost every tile).
+template <int MODE, int KIND>
+__device__ __forceinline__ float tile_softmax(f32x16 (&acc_s)[2], bf16x8 (&pb)[4], const int32_t* jlast,
+                                              const float* ju, int half, int qi, int dqh, int dqw, float tau_q,
+                                              float c2, float& m_run, float& l_run)
 {
-    using S = MfmaSmem<D>;
     constexpr bool GATED = (KIND != TILE_FAST) && (MODE != 2);  // the value gate applies
     constexpr bool KGATE = (KIND != TILE_FAST) && (MODE == 0);  // the key gate applies
     constexpr bool MASK = (KIND == TILE_LIST_MASK) || (KIND == TILE_CONT);
     constexpr float LAZY_LOG2 = 8.0f;
-    const unsigned char* kbuf = sm.kb[buf];
-    const unsigned char* vbuf = sm.vb[buf];
-    const int32_t* jlast = sm.jlast + base;
-    const float* ju = sm.ju + base;
-    const int dqh = qi - jbase - 4 * half;  // CONT: key number cst + 4*half sits dq - kk behind the query
-    const int dqw = dqh - w;                // in the window  <=>  cst > dqw
-    // ---- S^T = K . Q^T ----
-    f32x16 acc_s[2];
-    {
-        const unsigned char* kr0 = kbuf + (col % S::NL) * S::GSK + (col / S::NL) * S::RB + 16 * half;
-        const unsigned char* kr1 = kbuf + ((32 + col) % S::NL) * S::GSK + ((32 + col) / S::NL) * S::RB + 16 * half;
-#pragma unroll
-        for (int r = 0; r < 16; r++) { acc_s[0][r] = 0.0f; acc_s[1][r] = 0.0f; }
-#pragma unroll
-        for (int s = 0; s < D / 16; s++) {
-            const bf16x8 a0 = *(const bf16x8*)(kr0 + 32 * s);
-            const bf16x8 a1 = *(const bf16x8*)(kr1 + 32 * s);
-            acc_s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[s], acc_s[0], 0, 0, 0);
-            acc_s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[s], acc_s[1], 0, 0, 0);
-            if ((s & 3) == 3) __builtin_amdgcn_sched_barrier(0);  // bound the operand loads in flight
-        }
-    }
-    // ---- gates, masks, maximum ----
     float tmax = -INFINITY;
 #pragma unroll
     for (int mb = 0; mb < 2; mb++) {
@@ -286,7 +286,6 @@ __device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int buf, int base,
     m_run = m_new;
     // ---- p = exp2(s*c2 - m*c2): one fma and one v_exp_f32 per logit; value gate; P^T in bf16 ----
     float psum = 0.0f;
-    bf16x8 pb[4];
 #pragma unroll
     for (int mb = 0; mb < 2; mb++) {
 #pragma unroll
@@ -312,6 +311,55 @@ __device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int buf, int base,
         __builtin_amdgcn_sched_barrier(0);
     }
     l_run = l_run * alpha + psum;
+    return alpha;
+}
+
+// One 64-key tile for one wave.  The two 32-key halves of S^T are accumulated as two
+// interleaved (independent) MFMA chains, the softmax bookkeeping (max exchange, reference
+// update, rescale) is done once per tile, and the 16 MFMAs of O^T += V^T.P^T run over four
+// independent accumulators.  Only the element-wise gate/mask code depends on the tile kind;
+// the two MFMA phases and everything that touches the output accumulator are common code.
+template <int D, int MODE>
+__device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int kind, int buf, int base, int col, int half,
+                                             int lane, int qi, int jbase, int w, float tau_q, float c2,
+                                             const bf16x8 (&qreg)[D / 16], f32x16 (&acc_o)[D / 32], float& m_run,
+                                             float& l_run)
+{
+    using S = MfmaSmem<D>;
+    const unsigned char* kbuf = sm.kb[buf];
+    const unsigned char* vbuf = sm.vb[buf];
+    const int32_t* jlast = sm.jlast + base;
+    const float* ju = sm.ju + base;
+    const int dqh = qi - jbase - 4 * half;  // CONT: key number cst + 4*half sits dq - kk behind the query
+    const int dqw = dqh - w;                // in the window  <=>  cst > dqw
+    // ---- S^T = K . Q^T ----
+    f32x16 acc_s[2];
+    {
+        const unsigned char* kr0 = kbuf + (col % S::NL) * S::GSK + (col / S::NL) * S::RB + 16 * half;
+        const unsigned char* kr1 = kbuf + ((32 + col) % S::NL) * S::GSK + ((32 + col) / S::NL) * S::RB + 16 * half;
+#pragma unroll
+        for (int r = 0; r < 16; r++) { acc_s[0][r] = 0.0f; acc_s[1][r] = 0.0f; }
+#pragma unroll
+        for (int s = 0; s < D / 16; s++) {
+            const bf16x8 a0 = *(const bf16x8*)(kr0 + 32 * s);
+            const bf16x8 a1 = *(const bf16x8*)(kr1 + 32 * s);
+            acc_s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[s], acc_s[0], 0, 0, 0);
+            acc_s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[s], acc_s[1], 0, 0, 0);
+            if ((s & 3) == 3) __builtin_amdgcn_sched_barrier(0);  // bound the operand loads in flight
+        }
+    }
+    // ---- gates, masks, softmax: the only kind-specific code ----
+    bf16x8 pb[4];
+    float alpha;
+    if (kind == TILE_FAST)
+        alpha = tile_softmax<MODE, TILE_FAST>(acc_s, pb, jlast, ju, half, qi, dqh, dqw, tau_q, c2, m_run, l_run);
+    else if (kind == TILE_LIST)
+        alpha = tile_softmax<MODE, TILE_LIST>(acc_s, pb, jlast, ju, half, qi, dqh, dqw, tau_q, c2, m_run, l_run);
+    else if (kind == TILE_LIST_MASK)
+        alpha = tile_softmax<MODE, TILE_LIST_MASK>(acc_s, pb, jlast, ju, half, qi, dqh, dqw, tau_q, c2, m_run, l_run);
+    else
+        alpha = tile_softmax<MODE, TILE_CONT>(acc_s, pb, jlast, ju, half, qi, dqh, dqw, tau_q, c2, m_run, l_run);
+    __builtin_amdgcn_sched_barrier(0);
     rescale_o<D>(acc_o, alpha);
     // ---- O^T += V^T . P^T ----
     // The A operand comes through transposing LDS loads: within each group of 16 lanes, lane r
@@ -364,7 +412,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     }
     const int b = bh / H, h = bh % H;
     const int row = b * Gu + (Gu == 1 ? 0 : h);
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, col = lane & 31;
     const int i0 = blk * QB;
     const uint16_t* qh = q + (size_t)bh * n * D;
@@ -441,20 +489,18 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
             const int E0 = seg0 + base;
             const bool is_list = E0 < nkl;
             const int jbase = is_list ? 0 : c0 + (E0 - nkl);  // first position of a contiguous tile
-            if (!wave_live) continue;
-            if (is_list) {
-                if (sm.tile_lmin[t] >= qb)
-                    tile_compute<D, MODE, TILE_LIST>(sm, t & 1, base, col, half, lane, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
-                else
-                    tile_compute<D, MODE, TILE_LIST_MASK>(sm, t & 1, base, col, half, lane, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
-            } else {
-                if (jbase > qb) continue;  // every key of the tile is in the future of every query of the wave
-                const int jend = jbase + KT - 1;
-                if (jend <= qa && qb - jbase < w && jend <= c_end)
-                    tile_compute<D, MODE, TILE_FAST>(sm, t & 1, base, col, half, lane, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
-                else
-                    tile_compute<D, MODE, TILE_CONT>(sm, t & 1, base, col, half, lane, qi, jbase, w, tau_q, c2, qreg, acc_o, m_run, l_run);
+            int kind = -1;  // -1: nothing of this tile is visible to the wave
+            if (wave_live) {
+                if (is_list) {
+                    kind = (sm.tile_lmin[t] >= qb) ? TILE_LIST : TILE_LIST_MASK;
+                } else if (jbase <= qb) {  // else every key is in the future of every query of the wave
+                    const int jend = jbase + KT - 1;
+                    kind = (jend <= qa && qb - jbase < w && jend <= c_end) ? TILE_FAST : TILE_CONT;
+                }
             }
+            if (kind >= 0)
+                tile_compute<D, MODE>(sm, kind, t & 1, base, col, half, lane, qi, jbase, w, tau_q, c2, qreg, acc_o,
+                                      m_run, l_run);
         }
     }
 
@@ -512,7 +558,7 @@ int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const vo
     int32_t* lists = (int32_t*)ws;
     int32_t* counts = (int32_t*)((char*)ws + coff);
     launch_block_lists(c, death, lists, counts, st);
-    if (c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128)) {
+    if (c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull) {
         if (c.d == 64) launch_mfma<64>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, st);
         else launch_mfma<128>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, st);
         return launch_status();

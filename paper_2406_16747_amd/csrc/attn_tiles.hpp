@@ -32,7 +32,9 @@ struct MfmaSmem {
     int32_t tile_lmin[SEG / KT];
 };
 
-// Enqueue the gather of one tile (64 rows of K and of V) into buffer `buf`.
+// Enqueue the gather of one tile (64 rows of K and of V) into buffer `buf`.  Row offsets are
+// 32-bit byte offsets from the head's base pointer (the host checks n * RB < 2^32), so every
+// load is a uniform base plus one v_lshl_add_u32.
 template <int D, int VPAD>
 __device__ __forceinline__ void issue_tile_loads(MfmaSmem<D, VPAD>& sm, int buf, const int32_t* jp,
                                                  const uint16_t* __restrict__ kh, const uint16_t* __restrict__ vh,
@@ -44,9 +46,9 @@ __device__ __forceinline__ void issue_tile_loads(MfmaSmem<D, VPAD>& sm, int buf,
 #pragma unroll
     for (int x = 0; x < S::NL / 4; x++) {
         const int L = wv * (S::NL / 4) + x;
-        const size_t off = (size_t)jp[L + S::NL * jrow] * D + 8 * c;
-        __builtin_amdgcn_global_load_lds((glb_void_t*)(kh + off), (lds_void_t*)&sm.kb[buf][L * S::GSK], 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((glb_void_t*)(vh + off), (lds_void_t*)&sm.vb[buf][L * S::GSV], 16, 0, 0);
+        const uint32_t off = (uint32_t)jp[L + S::NL * jrow] * (uint32_t)S::RB + 16u * (uint32_t)c;
+        __builtin_amdgcn_global_load_lds((glb_void_t*)((const unsigned char*)kh + off), (lds_void_t*)&sm.kb[buf][L * S::GSK], 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((glb_void_t*)((const unsigned char*)vh + off), (lds_void_t*)&sm.vb[buf][L * S::GSV], 16, 0, 0);
     }
 }
 

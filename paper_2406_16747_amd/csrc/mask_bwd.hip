@@ -279,7 +279,7 @@ __global__ __launch_bounds__(256, 2) void mask_bwd_mfma_kernel(
     }
     const int b = bh / H, h = bh % H;
     const int row = b * Gu + (Gu == 1 ? 0 : h);
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, col = lane & 31;
     const int i0 = blk * QB;
     const uint16_t* kh = kk + (size_t)bh * n * D;
@@ -512,7 +512,7 @@ int launch_mask_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
     if (c.gate_mode != 2 && c.k > 0 && c.n > c.w) {
         launch_block_lists(c, death, lists, counts, st);
         dim3 grid(nb, c.B * c.H);
-        if (c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128)) {
+        if (c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull) {
             if (c.d == 64) launch_bwd_mfma<64>(c, q, k, v, u, tau, death, lists, counts, o, lse, dO, A, C, nb, st);
             else launch_bwd_mfma<128>(c, q, k, v, u, tau, death, lists, counts, o, lse, dO, A, C, nb, st);
         } else if (c.dtype == SPARSEK_F32)
