@@ -11,19 +11,21 @@
 // (queries x keys) tiles.
 #include "common.hpp"
 #include "attn_tiles.hpp"
+#include <type_traits>
 
 namespace spk {
 
 
 static inline int nblocks(int n) { return (n + QB - 1) / QB; }
 
-// Workspace of the per-block top-k lists: lists [rows][nb][max(k,1)] int32, then counts [rows][nb].
+// Workspace of the per-block top-k lists: lists [rows][nb][max(k,1)] int32, then counts [rows][nb]
+// (list lengths) and stays [rows][nb] (lengths of the first partitions).
 size_t block_lists_bytes(const sparsek_cfg& c, size_t* counts_offset)
 {
     size_t rows = (size_t)c.B * c.Gu;
     size_t nb = nblocks(c.n);
     size_t lists = align_up(rows * nb * (size_t)(c.k > 0 ? c.k : 1) * sizeof(int32_t), 256);
-    size_t counts = align_up(rows * nb * sizeof(int32_t), 256);
+    size_t counts = align_up(2 * rows * nb * sizeof(int32_t), 256);
     if (counts_offset) *counts_offset = lists;
     return lists + counts;
 }
@@ -47,7 +49,10 @@ __global__ __launch_bounds__(256) void block_lists_kernel(const int32_t* __restr
     const int T0 = blk * QB - w;
     int32_t* lo = lists + ((size_t)row * nb + blk) * (size_t)(k > 0 ? k : 1);
     if (T0 < 0 || k == 0) {
-        if (tid == 0) counts[(size_t)row * nb + blk] = 0;
+        if (tid == 0) {
+            counts[(size_t)row * nb + blk] = 0;
+            counts[((size_t)gridDim.y + row) * nb + blk] = 0;
+        }
         return;
     }
     const int32_t* dr = death + (size_t)row * n;
@@ -91,7 +96,10 @@ __global__ __launch_bounds__(256) void block_lists_kernel(const int32_t* __restr
             og += __popcll(bg);
         }
     }
-    if (tid == 0) counts[(size_t)row * nb + blk] = cnt;
+    if (tid == 0) {
+        counts[(size_t)row * nb + blk] = cnt;
+        counts[((size_t)gridDim.y + row) * nb + blk] = min(cnt, wstay[0] + wstay[1] + wstay[2] + wstay[3]);
+    }
 }
 
 // ---------------------------------------------------------------------------------
@@ -210,13 +218,36 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(
 // tile.  A wave-load moves 1 KB = RPL whole rows; tile row r goes to group r % NL, slot r / NL,
 // and the groups are padded (16 bytes for K, 64 for V) so that the operand reads of 16
 // consecutive lanes fall on distinct banks.
+//
+// The kernel is bound by vector-ALU issue (gates, masks, exponentials), not by the matrix
+// cores, so inside a tile the two are interleaved by hand: the tile is split into two halves
+// of 32 keys, and the instruction stream is
+//   S_A | S_B + softmax(A) | O += V_A^T.P_A + softmax(B) | O += V_B^T.P_B
+// with one MFMA followed by a slice of the softmax work, the slices fenced with sched_barrier
+// so that the compiler keeps the order.
 // ---------------------------------------------------------------------------------
-// Tile kinds, chosen per wave and tile:
-//   FAST       contiguous keys inside every query's window and not in its future: no mask, gate 1
-//   LIST       selected keys that outlive every query of the wave: gates, no mask
-//   LIST_MASK  selected keys, some of which expire inside the wave's query range
-//   CONT       contiguous keys at the causal diagonal or at the window's trailing edge
-enum { TILE_FAST = 0, TILE_LIST = 1, TILE_LIST_MASK = 2, TILE_CONT = 3 };
+// Tile kinds.  Along a block's key set they come in runs (per wave), so the tile loop is a
+// sequence of loops, one per kind, and each loop body is straight-line code:
+//   LIST       selected keys that stay selected for every query of the block: gates, no mask
+//   LIST_MASK  selected keys some of which expire inside the block (the tail of the list), and
+//              contiguous keys that are behind every window of the wave: gates, lifetime test
+//   EDGE       contiguous keys at the trailing edge of the wave's windows: gate 1 inside the
+//              window, lifetime test (always true inside the window)
+//   FAST       contiguous keys inside every query's window and not in its future: nothing
+//   DIAG       contiguous keys inside every window, at the causal diagonal: causal test
+//   CONT       everything at once (narrow windows, where EDGE and DIAG overlap)
+//   SKIP       keys in the future of the whole wave: loads and barriers only
+enum { TILE_FAST = 0, TILE_LIST = 1, TILE_LIST_MASK = 2, TILE_CONT = 3, TILE_EDGE = 4, TILE_DIAG = 5, TILE_SKIP = 6 };
+
+template <int MODE, int KIND>
+struct TileTraits {
+    static constexpr bool SEL = KIND == TILE_LIST || KIND == TILE_LIST_MASK || KIND == TILE_CONT || KIND == TILE_EDGE;
+    static constexpr bool GATED = SEL && MODE != 2;   // the value gate applies
+    static constexpr bool KGATE = SEL && MODE == 0;   // the key gate applies
+    static constexpr bool SELECT = KIND == TILE_CONT || KIND == TILE_EDGE;  // window keys mixed in: gate 1
+    static constexpr bool MASKL = KIND == TILE_LIST_MASK || KIND == TILE_CONT || KIND == TILE_EDGE;
+    static constexpr bool MASKC = KIND == TILE_CONT || KIND == TILE_DIAG;
+};
 
 template <int D>
 __device__ __forceinline__ void rescale_o(f32x16 (&acc_o)[D / 32], float alpha)
@@ -229,159 +260,211 @@ __device__ __forceinline__ void rescale_o(f32x16 (&acc_o)[D / 32], float alpha)
     }
 }
 
-// Everything between the two MFMA phases of one tile, specialised by tile kind: gates and masks
-// on the logits, the running maximum with its lazily moved reference point, the exponentials,
-// the value gate, and P^T packed to bf16.  Returns the factor the output accumulator has to be
-// rescaled by (1 for almost every tile).
+// Softmax state of one 32-key half of a tile: this lane holds 16 of its logits (4 groups of 4
+// consecutive keys), their gates and lifetimes.
+struct HalfState {
+    float4 G[4];   // scores, overwritten by the gates
+    int4 L[4];     // last query that attends the key
+    float tmax, mc, alpha, psum;
+    bf16x8 pb[2];  // P^T in operand layout
+};
+
 template <int MODE, int KIND>
-__device__ __forceinline__ float tile_softmax(f32x16 (&acc_s)[2], bf16x8 (&pb)[4], const int32_t* jlast,
-                                              const float* ju, int half, int qi, int dqh, int dqw, float tau_q,
-                                              float c2, float& m_run, float& l_run)
+__device__ __forceinline__ void load_meta(HalfState& h, const int32_t* jlast, const float* ju, int hf, int half)
 {
-    constexpr bool GATED = (KIND != TILE_FAST) && (MODE != 2);  // the value gate applies
-    constexpr bool KGATE = (KIND != TILE_FAST) && (MODE == 0);  // the key gate applies
-    constexpr bool MASK = (KIND == TILE_LIST_MASK) || (KIND == TILE_CONT);
-    constexpr float LAZY_LOG2 = 8.0f;
-    float tmax = -INFINITY;
+    using TT = TileTraits<MODE, KIND>;
 #pragma unroll
-    for (int mb = 0; mb < 2; mb++) {
-#pragma unroll
-        for (int g4 = 0; g4 < 4; g4++) {
-            const int kb = 32 * mb + 8 * g4 + 4 * half;  // first of 4 consecutive keys
-            int4 L4 = make_int4(0, 0, 0, 0);
-            float4 U4 = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (MASK) L4 = *(const int4*)&jlast[kb];
-            if (KGATE) U4 = *(const float4*)&ju[kb];
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-                const int r = 4 * g4 + e;
-                float s2 = acc_s[mb][r];
-                const int Lj = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
-                const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
-                // key number within the tile minus the lane-dependent 4*half (folded into dqh, dqw so
-                // that every compare below has a compile-time constant on one side)
-                const int cst = 32 * mb + 8 * g4 + e;
-                if (KGATE) {
-                    const float g = clip01(uj - tau_q);
-                    if (KIND == TILE_CONT) s2 = (cst > dqw) ? s2 : s2 * g;
-                    else s2 *= g;
-                }
-                if (KIND == TILE_LIST_MASK) s2 = (qi <= Lj) ? s2 : -INFINITY;
-                if (KIND == TILE_CONT) s2 = (cst <= dqh && qi <= Lj) ? s2 : -INFINITY;
-                acc_s[mb][r] = s2;
-                tmax = fmaxf(tmax, s2);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
+    for (int g4 = 0; g4 < 4; g4++) {
+        const int kb = 32 * hf + 8 * g4 + 4 * half;
+        if (TT::GATED) h.G[g4] = *(const float4*)&ju[kb];
+        if (TT::MASKL) h.L[g4] = *(const int4*)&jlast[kb];
     }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    // Lazy reference point: m_run only moves when the maximum grows by more than 2^LAZY_LOG2 in
-    // probability (softmax is shift-invariant; p stays below 2^LAZY_LOG2, harmless in fp32/bf16).
-    // Otherwise some lane of the wave raises its maximum in nearly every tile and the whole
-    // output accumulator would be rescaled every time.
-    const float m_new = (tmax > m_run + LAZY_LOG2 / c2) ? tmax : m_run;
-    const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * c2);
-    const float mc = m_safe * c2;
-    m_run = m_new;
-    // ---- p = exp2(s*c2 - m*c2): one fma and one v_exp_f32 per logit; value gate; P^T in bf16 ----
-    float psum = 0.0f;
-#pragma unroll
-    for (int mb = 0; mb < 2; mb++) {
-#pragma unroll
-        for (int g4 = 0; g4 < 4; g4++) {
-            const int kb = 32 * mb + 8 * g4 + 4 * half;
-            float4 U4 = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (GATED) U4 = *(const float4*)&ju[kb];
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-                const int r = 4 * g4 + e;
-                const float p = __builtin_amdgcn_exp2f(fmaf(acc_s[mb][r], c2, -mc));
-                psum += p;
-                float pvv = p;
-                if (GATED) {  // recomputed: one v_sub with clamp, cheaper than holding 32 registers
-                    const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
-                    const float g = clip01(uj - tau_q);
-                    if (KIND == TILE_CONT) pvv = (32 * mb + 8 * g4 + e > dqw) ? p : p * g;
-                    else pvv = p * g;
-                }
-                pb[2 * mb + (r >> 3)][r & 7] = (__bf16)pvv;
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    l_run = l_run * alpha + psum;
-    return alpha;
+    h.tmax = -INFINITY;
+    h.psum = 0.0f;
 }
 
-// One 64-key tile for one wave.  The two 32-key halves of S^T are accumulated as two
-// interleaved (independent) MFMA chains, the softmax bookkeeping (max exchange, reference
-// update, rescale) is done once per tile, and the 16 MFMAs of O^T += V^T.P^T run over four
-// independent accumulators.  Only the element-wise gate/mask code depends on the tile kind;
-// the two MFMA phases and everything that touches the output accumulator are common code.
-template <int D, int MODE>
-__device__ __forceinline__ void tile_compute(MfmaSmem<D>& sm, int kind, int buf, int base, int col, int half,
-                                             int lane, int qi, int jbase, int w, float tau_q, float c2,
-                                             const bf16x8 (&qreg)[D / 16], f32x16 (&acc_o)[D / 32], float& m_run,
-                                             float& l_run)
+// Slice U of the softmax work of one half.  U = 0..3: gates and masks of key group U and the
+// running maximum; after group 3 the maximum is exchanged with the partner lane and the
+// reference point moves if it has to (lazily: only when the maximum grew by more than 2^8 in
+// probability; softmax is shift-invariant and p stays below 2^8, harmless in fp32/bf16; this
+// keeps the rescale of the output accumulator a rare event).  U = 4..7: exponentials, row sum,
+// value gate and bf16 packing of key group U - 4.
+template <int MODE, int KIND, int U>
+__device__ __forceinline__ void softmax_slice(HalfState& h, f32x16& sv, int hf, int qi, int dqh, int dqw,
+                                              float tau_q, float c2, float& m_run)
+{
+    using TT = TileTraits<MODE, KIND>;
+    constexpr float LAZY_LOG2 = 8.0f;
+    if (U < 4) {
+        constexpr int g4 = U & 3;
+        float gg[4] = {h.G[g4].x, h.G[g4].y, h.G[g4].z, h.G[g4].w};
+        const int ll[4] = {h.L[g4].x, h.L[g4].y, h.L[g4].z, h.L[g4].w};
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const int r = 4 * g4 + e;
+            // key number within the tile minus the lane-dependent 4*half (folded into dqh, dqw so
+            // that every compare below has a compile-time constant on one side)
+            const int cst = 32 * hf + 8 * g4 + e;
+            float s2 = sv[r];
+            if (TT::GATED) {
+                float g = clip01(gg[e] - tau_q);
+                if (TT::SELECT) g = (cst > dqw) ? 1.0f : g;
+                gg[e] = g;
+                if (TT::KGATE) s2 *= g;
+            }
+            if (TT::MASKL && TT::MASKC) s2 = (cst <= dqh && qi <= ll[e]) ? s2 : -INFINITY;
+            else if (TT::MASKL) s2 = (qi <= ll[e]) ? s2 : -INFINITY;
+            else if (TT::MASKC) s2 = (cst <= dqh) ? s2 : -INFINITY;
+            sv[r] = s2;
+            h.tmax = fmaxf(h.tmax, s2);
+        }
+        if (TT::GATED) h.G[g4] = make_float4(gg[0], gg[1], gg[2], gg[3]);
+        if (U == 3) {
+            const unsigned tb = __float_as_uint(h.tmax);
+            const auto sw = __builtin_amdgcn_permlane32_swap(tb, tb, false, false);  // both halves, no LDS
+            const float tq = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            const float m_new = (tq > m_run + LAZY_LOG2 / c2) ? tq : m_run;
+            const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+            h.alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * c2);
+            h.mc = m_safe * c2;
+            m_run = m_new;
+        }
+    } else {
+        constexpr int g4 = U & 3;
+        const float gg[4] = {h.G[g4].x, h.G[g4].y, h.G[g4].z, h.G[g4].w};
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            const int r = 4 * g4 + e;
+            const float p = __builtin_amdgcn_exp2f(fmaf(sv[r], c2, -h.mc));
+            h.psum += p;
+            const float pv = TT::GATED ? p * gg[e] : p;
+            h.pb[r >> 3][r & 7] = (__bf16)pv;
+        }
+    }
+}
+
+template <int MODE, int KIND, int U0, int U1>
+__device__ __forceinline__ void softmax_slices(HalfState& h, f32x16& sv, int hf, int qi, int dqh, int dqw,
+                                               float tau_q, float c2, float& m_run)
+{
+    if constexpr (U0 < U1) {
+        softmax_slice<MODE, KIND, U0>(h, sv, hf, qi, dqh, dqw, tau_q, c2, m_run);
+        softmax_slices<MODE, KIND, U0 + 1, U1>(h, sv, hf, qi, dqh, dqw, tau_q, c2, m_run);
+    }
+}
+
+// Compile-time loop: f(integral_constant<int, I>) for I = 0 .. N-1.
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// One 64-key tile for one wave (see the schedule in the header comment).
+template <int D, int MODE, int KIND>
+__device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, int jbase, int col, int half,
+                                          int lane, int qi, int w, float tau_q, float c2,
+                                          const bf16x8 (&qreg)[D / 16], f32x16 (&acc_o)[D / 32], float& m_run,
+                                          float& l_run)
 {
     using S = MfmaSmem<D>;
+    constexpr int NS = D / 16;      // MFMAs per half of S^T
+    constexpr int DB = D / 32;      // 32-row blocks of O^T
+    constexpr int NP = 2 * DB;      // MFMAs per half of O^T += V^T.P^T
+    constexpr int US = 8 / NS;      // softmax slices per MFMA of S_B
+    constexpr int UP = 8 / NP;      // softmax slices per MFMA of the first PV half
     const unsigned char* kbuf = sm.kb[buf];
     const unsigned char* vbuf = sm.vb[buf];
     const int32_t* jlast = sm.jlast + base;
     const float* ju = sm.ju + base;
-    const int dqh = qi - jbase - 4 * half;  // CONT: key number cst + 4*half sits dq - kk behind the query
+    const int dqh = qi - jbase - 4 * half;  // contiguous tiles: key number cst + 4*half sits dqh - cst behind the query
     const int dqw = dqh - w;                // in the window  <=>  cst > dqw
-    // ---- S^T = K . Q^T ----
-    f32x16 acc_s[2];
-    {
-        const unsigned char* kr0 = kbuf + (col % S::NL) * S::GSK + (col / S::NL) * S::RB + 16 * half;
-        const unsigned char* kr1 = kbuf + ((32 + col) % S::NL) * S::GSK + ((32 + col) / S::NL) * S::RB + 16 * half;
-#pragma unroll
-        for (int r = 0; r < 16; r++) { acc_s[0][r] = 0.0f; acc_s[1][r] = 0.0f; }
-#pragma unroll
-        for (int s = 0; s < D / 16; s++) {
-            const bf16x8 a0 = *(const bf16x8*)(kr0 + 32 * s);
-            const bf16x8 a1 = *(const bf16x8*)(kr1 + 32 * s);
-            acc_s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qreg[s], acc_s[0], 0, 0, 0);
-            acc_s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qreg[s], acc_s[1], 0, 0, 0);
-            if ((s & 3) == 3) __builtin_amdgcn_sched_barrier(0);  // bound the operand loads in flight
-        }
-    }
-    // ---- gates, masks, softmax: the only kind-specific code ----
-    bf16x8 pb[4];
-    float alpha;
-    if (kind == TILE_FAST)
-        alpha = tile_softmax<MODE, TILE_FAST>(acc_s, pb, jlast, ju, half, qi, dqh, dqw, tau_q, c2, m_run, l_run);
-    else if (kind == TILE_LIST)
-        alpha = tile_softmax<MODE, TILE_LIST>(acc_s, pb, jlast, ju, half, qi, dqh, dqw, tau_q, c2, m_run, l_run);
-    else if (kind == TILE_LIST_MASK)
-        alpha = tile_softmax<MODE, TILE_LIST_MASK>(acc_s, pb, jlast, ju, half, qi, dqh, dqw, tau_q, c2, m_run, l_run);
-    else
-        alpha = tile_softmax<MODE, TILE_CONT>(acc_s, pb, jlast, ju, half, qi, dqh, dqw, tau_q, c2, m_run, l_run);
-    __builtin_amdgcn_sched_barrier(0);
-    rescale_o<D>(acc_o, alpha);
-    // ---- O^T += V^T . P^T ----
-    // The A operand comes through transposing LDS loads: within each group of 16 lanes, lane r
-    // points at (row r/4, 4-column block r%4) of a 4-row x 16-column patch of V and receives the
-    // 4 rows of column r.  MFMA g (16 keys) uses rows 16g + 4*half + {0..3} (k-slots 0..3) and
-    // 16g + 8 + 4*half + {0..3} (k-slots 4..7): the key order P^T already has.
+    const unsigned char* krA = kbuf + (col % S::NL) * S::GSK + (col / S::NL) * S::RB + 16 * half;
+    const unsigned char* krB = kbuf + ((32 + col) % S::NL) * S::GSK + ((32 + col) / S::NL) * S::RB + 16 * half;
+    // The A operand of O^T += V^T.P^T comes through transposing LDS loads: within each group of
+    // 16 lanes, lane r points at (row r/4, 4-column block r%4) of a 4-row x 16-column patch of V
+    // and receives the 4 rows of column r.  MFMA g (16 keys) uses rows 16g + 4*half + {0..3}
+    // (k-slots 0..3) and 16g + 8 + 4*half + {0..3} (k-slots 4..7): the key order P^T already has.
     const int r16 = lane & 15, grp2 = (lane >> 4) & 1;
-#pragma unroll
-    for (int g = 0; g < 4; g++) {
+    const int vcol = (16 * grp2 + 4 * (r16 & 3)) * 2;
+    auto v_operand = [&](int g, int x) -> bf16x8 {
         const int row0 = 16 * g + 4 * half + (r16 >> 2);
         const int row1 = row0 + 8;
-        const unsigned char* v0 = vbuf + (row0 % S::NL) * S::GSV + (row0 / S::NL) * S::RB + (16 * grp2 + 4 * (r16 & 3)) * 2;
-        const unsigned char* v1 = vbuf + (row1 % S::NL) * S::GSV + (row1 / S::NL) * S::RB + (16 * grp2 + 4 * (r16 & 3)) * 2;
+        const unsigned char* v0 = vbuf + (row0 % S::NL) * S::GSV + (row0 / S::NL) * S::RB + vcol + 64 * x;
+        const unsigned char* v1 = vbuf + (row1 % S::NL) * S::GSV + (row1 / S::NL) * S::RB + vcol + 64 * x;
+        const i16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)v0);
+        const i16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)v1);
+        const bf16x4 lo = __builtin_bit_cast(bf16x4, lo4), hi = __builtin_bit_cast(bf16x4, hi4);
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+
+    HalfState A, B;
+    f32x16 sA, sB;
 #pragma unroll
-        for (int x = 0; x < D / 32; x++) {
-            const i16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)(v0 + 64 * x));
-            const i16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)(v1 + 64 * x));
-            const bf16x4 lo = __builtin_bit_cast(bf16x4, lo4), hi = __builtin_bit_cast(bf16x4, hi4);
-            const bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            acc_o[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[g], acc_o[x], 0, 0, 0);
-        }
-        if (g & 1) __builtin_amdgcn_sched_barrier(0);
+    for (int r = 0; r < 16; r++) { sA[r] = 0.0f; sB[r] = 0.0f; }
+    load_meta<MODE, KIND>(A, jlast, ju, 0, half);
+    // ---- S_A ----
+#pragma unroll
+    for (int s = 0; s < NS; s++) sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(krA + 32 * s), qreg[s], sA, 0, 0, 0);
+    bf16x8 kop = *(const bf16x8*)krB;
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- S_B with softmax(A) ----
+    static_for<0, NS>([&](auto sc) {
+        constexpr int s = decltype(sc)::value;
+        const bf16x8 cur = kop;
+        if (s + 1 < NS) kop = *(const bf16x8*)(krB + 32 * (s + 1));
+        sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qreg[s], sB, 0, 0, 0);
+        softmax_slices<MODE, KIND, US * s, US * (s + 1)>(A, sA, 0, qi, dqh, dqw, tau_q, c2, m_run);
+        if (US * (s + 1) == 4) load_meta<MODE, KIND>(B, jlast, ju, 1, half);  // A's lifetimes are dead by now
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    // (the empty asm uses keep the compiler from sinking the exponentials below the rescale branch)
+    asm volatile("" ::"v"(A.pb[0]), "v"(A.pb[1]), "v"(A.psum));
+    l_run = l_run * A.alpha + A.psum;
+    rescale_o<D>(acc_o, A.alpha);
+    // ---- O^T += V_A^T . P_A^T with softmax(B) ----
+    bf16x8 vop = v_operand(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<0, NP>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        constexpr int g = i / DB, x = i % DB;
+        const bf16x8 cur = vop;
+        if (i + 1 < NP) vop = v_operand((i + 1) / DB, (i + 1) % DB);
+        acc_o[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, A.pb[g], acc_o[x], 0, 0, 0);
+        softmax_slices<MODE, KIND, UP * i, UP * (i + 1)>(B, sB, 1, qi, dqh, dqw, tau_q, c2, m_run);
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    asm volatile("" ::"v"(B.pb[0]), "v"(B.pb[1]), "v"(B.psum));
+    l_run = l_run * B.alpha + B.psum;
+    rescale_o<D>(acc_o, B.alpha);
+    // ---- O^T += V_B^T . P_B^T ----
+#pragma unroll
+    for (int i = 0; i < NP; i++) {
+        const int g = i / DB, x = i % DB;
+        acc_o[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(2 + g, x), B.pb[g], acc_o[x], 0, 0, 0);
+    }
+}
+
+// The tiles [t, t_end) of the current segment, all of one kind.
+template <int D, int MODE, int KIND>
+__device__ __forceinline__ void run_tiles(MfmaSmem<D>& sm, int& t, int t_end, int ntiles, int jbase0,
+                                          const uint16_t* kh, const uint16_t* vh, int wv, int col, int half,
+                                          int lane, int qi, int w, float tau_q, float c2,
+                                          const bf16x8 (&qreg)[D / 16], f32x16 (&acc_o)[D / 32], float& m_run,
+                                          float& l_run)
+{
+    for (; t < t_end; t++) {
+        // tile t has landed (this wave's part: vmcnt; the other waves' parts: barrier); the
+        // barrier also says that everybody is done with tile t-1, whose buffer is refilled next
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (t + 1 < ntiles) issue_tile_loads<D, 64>(sm, (t + 1) & 1, sm.jpos + (t + 1) * KT, kh, vh, wv, lane);
+        if (KIND != TILE_SKIP)
+            tile_body<D, MODE, KIND>(sm, t & 1, t * KT, jbase0 + t * KT, col, half, lane, qi, w, tau_q, c2, qreg,
+                                     acc_o, m_run, l_run);
     }
 }
 
@@ -390,7 +473,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ kk, const uint16_t* __restrict__ v,
     const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
     const int32_t* __restrict__ lists, const int32_t* __restrict__ counts, uint16_t* __restrict__ o,
-    float* __restrict__ lse, int H, int Gu, int n, int k, int w, float scale, int nb, int BH)
+    float* __restrict__ lse, int H, int Gu, int n, int k, int w, float scale, int nb, int BH, int nrows)
 {
     __shared__ __align__(16) MfmaSmem<D> sm;
     constexpr int DS = D / 16;   // MFMA k-steps over the head dim
@@ -423,6 +506,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     const int32_t* dr = death + (size_t)row * n;
     const int32_t* list = lists + ((size_t)row * nb + blk) * (size_t)(k > 0 ? k : 1);
     const int cnt = counts[(size_t)row * nb + blk];
+    const int nstay = counts[(size_t)nrows * nb + (size_t)row * nb + blk];
     const int c0 = max(0, i0 - w + 1);
     const int c_end = min(n - 1, i0 + QB - 1);
     const int nkl = (cnt + KT - 1) / KT * KT;                // list part, padded to whole tiles
@@ -440,6 +524,29 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
 #pragma unroll
     for (int s = 0; s < DS; s++)
         qreg[s] = *(const bf16x8*)(qh + (size_t)qrow * D + 16 * s + 8 * half);
+
+    // ---- the runs of tile kinds for this wave, as global tile numbers (all wave-uniform) ----
+    //   [0,b0) LIST  [b0,b1) LIST_MASK  [b1,b2) EDGE or CONT  [b2,b3) FAST  [b3,b4) DIAG  [b4,..) SKIP
+    int b0 = 0, b1 = 0, b2 = 0, b3 = 0, b4 = 0;
+    bool narrow = false;
+    if (wave_live) {
+        const int TL = nkl / KT, NC = nkc / KT;
+        b0 = min(nstay / KT, TL);
+        // contiguous tile m covers positions c0 + 64m .. c0 + 64m + 63
+        const int x_sel = qa - w - c0 - (KT - 1);     // m <= x_sel/64: behind every window of the wave
+        const int x_fb = qb - w - c0;                 // m >  x_fb/64:  inside every window of the wave
+        const int x_fe = qa - c0 - (KT - 1);          // m <= x_fe/64:  in nobody's future
+        const int m_sel = x_sel >= 0 ? x_sel / KT + 1 : 0;
+        const int m_fb = x_fb >= 0 ? x_fb / KT + 1 : 0;
+        const int m_fe = x_fe >= 0 ? x_fe / KT + 1 : 0;
+        const int m_skip = (qb - c0) / KT + 1;        // first tile entirely in the wave's future
+        narrow = m_fb >= m_fe;                        // no tile is both inside every window and in the past
+        b1 = TL + min(m_sel, NC);
+        b4 = TL + min(m_skip, NC);
+        b2 = narrow ? b4 : TL + min(m_fb, NC);
+        b3 = narrow ? b4 : TL + min(m_fe, NC);
+        b1 = min(b1, b2);
+    }
 
     f32x16 acc_o[DB];
 #pragma unroll
@@ -469,39 +576,22 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
             sm.ju[e] = real ? ur[j] : 0.0f;
         }
         __syncthreads();
-        for (int t = wv; t < seg_n / KT; t += 4) {
-            int lm = sm.jlast[t * KT + lane];
-#pragma unroll
-            for (int o2 = 32; o2 > 0; o2 >>= 1) lm = min(lm, __shfl_xor(lm, o2, 64));
-            if (lane == 0) sm.tile_lmin[t] = lm;
-        }
         const int ntiles = seg_n / KT;
+        const int T0 = seg0 / KT;                 // global number of the segment's first tile
+        const int jbase0 = c0 + (seg0 - nkl);     // position of local tile 0 if it were contiguous
         issue_tile_loads<D, 64>(sm, 0, sm.jpos, kh, vh, wv, lane);
-        for (int t = 0; t < ntiles; t++) {
-            // tile t has landed (this wave's part: vmcnt; the other waves' parts: barrier); the
-            // barrier also says that everybody is done with tile t-1, whose buffer is refilled next
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (t + 1 < ntiles) issue_tile_loads<D, 64>(sm, (t + 1) & 1, sm.jpos + (t + 1) * KT, kh, vh, wv, lane);
-
-            // ---- classify the tile for this wave (all conditions are wave-uniform) ----
-            const int base = t * KT;
-            const int E0 = seg0 + base;
-            const bool is_list = E0 < nkl;
-            const int jbase = is_list ? 0 : c0 + (E0 - nkl);  // first position of a contiguous tile
-            int kind = -1;  // -1: nothing of this tile is visible to the wave
-            if (wave_live) {
-                if (is_list) {
-                    kind = (sm.tile_lmin[t] >= qb) ? TILE_LIST : TILE_LIST_MASK;
-                } else if (jbase <= qb) {  // else every key is in the future of every query of the wave
-                    const int jend = jbase + KT - 1;
-                    kind = (jend <= qa && qb - jbase < w && jend <= c_end) ? TILE_FAST : TILE_CONT;
-                }
-            }
-            if (kind >= 0)
-                tile_compute<D, MODE>(sm, kind, t & 1, base, col, half, lane, qi, jbase, w, tau_q, c2, qreg, acc_o,
-                                      m_run, l_run);
-        }
+        int t = 0;
+#define SPK_RUN(KIND, bound)                                                                                   \
+    run_tiles<D, MODE, KIND>(sm, t, min(ntiles, (bound) - T0), ntiles, jbase0, kh, vh, wv, col, half, lane, qi, \
+                             w, tau_q, c2, qreg, acc_o, m_run, l_run)
+        SPK_RUN(TILE_LIST, b0);
+        SPK_RUN(TILE_LIST_MASK, b1);
+        if (narrow) SPK_RUN(TILE_CONT, b2);
+        else SPK_RUN(TILE_EDGE, b2);
+        SPK_RUN(TILE_FAST, b3);
+        SPK_RUN(TILE_DIAG, b4);
+        SPK_RUN(TILE_SKIP, T0 + ntiles);
+#undef SPK_RUN
     }
 
     // ---- epilogue: O = O^T / l, lse ----
@@ -533,7 +623,7 @@ static void launch_mfma(const sparsek_cfg& c, const void* q, const void* k, cons
 #define SPK_LAUNCH(MODE)                                                                                   \
     hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q,        \
                        (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, (uint16_t*)o, \
-                       lse, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH)
+                       lse, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH, c.B * c.Gu)
     if (c.gate_mode == 0) SPK_LAUNCH(0);
     else if (c.gate_mode == 1) SPK_LAUNCH(1);
     else SPK_LAUNCH(2);
