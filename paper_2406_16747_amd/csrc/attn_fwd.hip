@@ -363,9 +363,12 @@ __device__ __forceinline__ void static_for(F&& f)
     }
 }
 
-// One 64-key tile for one wave (see the schedule in the header comment).
+// One 64-key tile for one wave (see the schedule in the header comment).  The tile is a
+// sequence of MFMA slots (S_A, S_B, PV_A, PV_B); the LDS operand of slot n is requested DEPTH
+// slots earlier into a small register ring, so that no MFMA waits for a read it has just issued.
 template <int D, int MODE, int KIND>
-__device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, int jbase, int col, int half,
+__device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, int jbase, bool more,
+                                          const uint16_t* kh, const uint16_t* vh, int wv, int col, int half,
                                           int lane, int qi, int w, float tau_q, float c2,
                                           const bf16x8 (&qreg)[D / 16], f32x16 (&acc_o)[D / 32], float& m_run,
                                           float& l_run)
@@ -376,6 +379,10 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
     constexpr int NP = 2 * DB;      // MFMAs per half of O^T += V^T.P^T
     constexpr int US = 8 / NS;      // softmax slices per MFMA of S_B
     constexpr int UP = 8 / NP;      // softmax slices per MFMA of the first PV half
+    constexpr int NSLOT = 2 * NS + 2 * NP;
+    constexpr int DEPTH = 2;
+    constexpr int NX = S::NL / 4;   // gather steps of the next tile, one per S_A slot
+    static_assert(NX <= NS, "one gather step per S_A slot");
     const unsigned char* kbuf = sm.kb[buf];
     const unsigned char* vbuf = sm.vb[buf];
     const int32_t* jlast = sm.jlast + base;
@@ -390,8 +397,9 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
     // (k-slots 0..3) and 16g + 8 + 4*half + {0..3} (k-slots 4..7): the key order P^T already has.
     const int r16 = lane & 15, grp2 = (lane >> 4) & 1;
     const int vcol = (16 * grp2 + 4 * (r16 & 3)) * 2;
+    const int vrow = 4 * half + (r16 >> 2);
     auto v_operand = [&](int g, int x) -> bf16x8 {
-        const int row0 = 16 * g + 4 * half + (r16 >> 2);
+        const int row0 = 16 * g + vrow;
         const int row1 = row0 + 8;
         const unsigned char* v0 = vbuf + (row0 % S::NL) * S::GSV + (row0 / S::NL) * S::RB + vcol + 64 * x;
         const unsigned char* v1 = vbuf + (row1 % S::NL) * S::GSV + (row1 / S::NL) * S::RB + vcol + 64 * x;
@@ -400,25 +408,39 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
         const bf16x4 lo = __builtin_bit_cast(bf16x4, lo4), hi = __builtin_bit_cast(bf16x4, hi4);
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
+    auto operand = [&](int n) -> bf16x8 {  // n is a compile-time constant after unrolling
+        if (n < NS) return *(const bf16x8*)(krA + 32 * n);
+        if (n < 2 * NS) return *(const bf16x8*)(krB + 32 * (n - NS));
+        const int i = n - 2 * NS;
+        return v_operand(i / DB, i % DB);
+    };
 
     HalfState A, B;
     f32x16 sA, sB;
 #pragma unroll
     for (int r = 0; r < 16; r++) { sA[r] = 0.0f; sB[r] = 0.0f; }
-    load_meta<MODE, KIND>(A, jlast, ju, 0, half);
-    // ---- S_A ----
+    bf16x8 ring[DEPTH];
 #pragma unroll
-    for (int s = 0; s < NS; s++) sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(krA + 32 * s), qreg[s], sA, 0, 0, 0);
-    bf16x8 kop = *(const bf16x8*)krB;
+    for (int n = 0; n < DEPTH; n++) ring[n] = operand(n);
+    TileRows<D, 64> rows;
+    if (more) rows = tile_rows<D, 64>(sm.jpos + base + KT, wv, lane);
+    load_meta<MODE, KIND>(A, jlast, ju, 0, half);
     __builtin_amdgcn_sched_barrier(0);
-    // ---- S_B with softmax(A) ----
-    static_for<0, NS>([&](auto sc) {
-        constexpr int s = decltype(sc)::value;
-        const bf16x8 cur = kop;
-        if (s + 1 < NS) kop = *(const bf16x8*)(krB + 32 * (s + 1));
-        sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qreg[s], sB, 0, 0, 0);
-        softmax_slices<MODE, KIND, US * s, US * (s + 1)>(A, sA, 0, qi, dqh, dqw, tau_q, c2, m_run);
-        if (US * (s + 1) == 4) load_meta<MODE, KIND>(B, jlast, ju, 1, half);  // A's lifetimes are dead by now
+    // ---- S_A, then S_B with softmax(A) ----
+    static_for<0, 2 * NS>([&](auto nc) {
+        constexpr int n = decltype(nc)::value;
+        const bf16x8 cur = ring[n % DEPTH];
+        if (n < NS) sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qreg[n], sA, 0, 0, 0);
+        else sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qreg[n - NS], sB, 0, 0, 0);
+        if (n + DEPTH < NSLOT) ring[n % DEPTH] = operand(n + DEPTH);
+        // the gather of the next tile rides on the S_A slots, whose issue is otherwise idle
+        // (every wave is past this tile's barrier, so the other buffer is free)
+        if (n < NX && more) tile_load_step<D, 64>(sm, buf ^ 1, rows, n, kh, vh, wv, lane);
+        if (n >= NS) {
+            constexpr int s = n >= NS ? n - NS : 0;
+            softmax_slices<MODE, KIND, US * s, US * (s + 1)>(A, sA, 0, qi, dqh, dqw, tau_q, c2, m_run);
+            if (US * (s + 1) == 4) load_meta<MODE, KIND>(B, jlast, ju, 1, half);  // A's lifetimes are dead by now
+        }
         __builtin_amdgcn_sched_barrier(0);
     });
     // (the empty asm uses keep the compiler from sinking the exponentials below the rescale branch)
@@ -426,14 +448,12 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
     l_run = l_run * A.alpha + A.psum;
     rescale_o<D>(acc_o, A.alpha);
     // ---- O^T += V_A^T . P_A^T with softmax(B) ----
-    bf16x8 vop = v_operand(0, 0);
-    __builtin_amdgcn_sched_barrier(0);
     static_for<0, NP>([&](auto ic) {
         constexpr int i = decltype(ic)::value;
-        constexpr int g = i / DB, x = i % DB;
-        const bf16x8 cur = vop;
-        if (i + 1 < NP) vop = v_operand((i + 1) / DB, (i + 1) % DB);
-        acc_o[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, A.pb[g], acc_o[x], 0, 0, 0);
+        constexpr int n = 2 * NS + i;
+        const bf16x8 cur = ring[n % DEPTH];
+        acc_o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, A.pb[i / DB], acc_o[i % DB], 0, 0, 0);
+        if (n + DEPTH < NSLOT) ring[n % DEPTH] = operand(n + DEPTH);
         softmax_slices<MODE, KIND, UP * i, UP * (i + 1)>(B, sB, 1, qi, dqh, dqw, tau_q, c2, m_run);
         __builtin_amdgcn_sched_barrier(0);
     });
@@ -441,11 +461,13 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
     l_run = l_run * B.alpha + B.psum;
     rescale_o<D>(acc_o, B.alpha);
     // ---- O^T += V_B^T . P_B^T ----
-#pragma unroll
-    for (int i = 0; i < NP; i++) {
-        const int g = i / DB, x = i % DB;
-        acc_o[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(2 + g, x), B.pb[g], acc_o[x], 0, 0, 0);
-    }
+    static_for<0, NP>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        constexpr int n = 2 * NS + NP + i;
+        const bf16x8 cur = ring[n % DEPTH];
+        acc_o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, B.pb[i / DB], acc_o[i % DB], 0, 0, 0);
+        if (n + DEPTH < NSLOT) ring[n % DEPTH] = operand(n + DEPTH);
+    });
 }
 
 // The tiles [t, t_end) of the current segment, all of one kind.
@@ -461,10 +483,11 @@ __device__ __forceinline__ void run_tiles(MfmaSmem<D>& sm, int& t, int t_end, in
         // barrier also says that everybody is done with tile t-1, whose buffer is refilled next
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (t + 1 < ntiles) issue_tile_loads<D, 64>(sm, (t + 1) & 1, sm.jpos + (t + 1) * KT, kh, vh, wv, lane);
         if (KIND != TILE_SKIP)
-            tile_body<D, MODE, KIND>(sm, t & 1, t * KT, jbase0 + t * KT, col, half, lane, qi, w, tau_q, c2, qreg,
-                                     acc_o, m_run, l_run);
+            tile_body<D, MODE, KIND>(sm, t & 1, t * KT, jbase0 + t * KT, t + 1 < ntiles, kh, vh, wv, col, half, lane,
+                                     qi, w, tau_q, c2, qreg, acc_o, m_run, l_run);
+        else if (t + 1 < ntiles)
+            issue_tile_loads<D, 64>(sm, (t + 1) & 1, sm.jpos + (t + 1) * KT, kh, vh, wv, lane);
     }
 }
 

@@ -32,24 +32,57 @@ struct MfmaSmem {
     int32_t tile_lmin[SEG / KT];
 };
 
-// Enqueue the gather of one tile (64 rows of K and of V) into buffer `buf`.  Row offsets are
-// 32-bit byte offsets from the head's base pointer (the host checks n * RB < 2^32), so every
-// load is a uniform base plus one v_lshl_add_u32.
+// The gather of one tile (64 rows of K and of V) into buffer `buf`, as NL/4 steps per wave:
+// tile_rows() reads this lane's row numbers with one LDS load, tile_load_step(x) enqueues one
+// K and one V wave-load.  Row offsets are 32-bit byte offsets from the head's base pointer
+// (the host checks n * RB < 2^32), so every load is a uniform base plus one v_lshl_add_u32.
+template <int D, int VPAD>
+struct TileRows {
+    int32_t j[MfmaSmem<D, VPAD>::NL / 4];
+};
+
+template <int D, int VPAD>
+__device__ __forceinline__ TileRows<D, VPAD> tile_rows(const int32_t* jp, int wv, int lane)
+{
+    using S = MfmaSmem<D, VPAD>;
+    constexpr int LPR = S::RB / 16;  // lanes per row
+    constexpr int NX = S::NL / 4;
+    const int jrow = lane / LPR;
+    TileRows<D, VPAD> r;
+    const int32_t* src = jp + wv * NX + S::NL * jrow;  // row L + NL * jrow for L = wv * NX + x
+    if constexpr (NX == 4) {
+        const int4 t = *(const int4*)src;
+        r.j[0] = t.x; r.j[1] = t.y; r.j[2] = t.z; r.j[3] = t.w;
+    } else {
+        static_assert(NX == 2, "head dim 64 or 128");
+        const int2 t = *(const int2*)src;
+        r.j[0] = t.x; r.j[1] = t.y;
+    }
+    return r;
+}
+
+template <int D, int VPAD>
+__device__ __forceinline__ void tile_load_step(MfmaSmem<D, VPAD>& sm, int buf, const TileRows<D, VPAD>& rows, int x,
+                                               const uint16_t* __restrict__ kh, const uint16_t* __restrict__ vh,
+                                               int wv, int lane)
+{
+    using S = MfmaSmem<D, VPAD>;
+    constexpr int LPR = S::RB / 16;
+    const int c = lane % LPR;
+    const int L = wv * (S::NL / 4) + x;
+    const uint32_t off = (uint32_t)rows.j[x] * (uint32_t)S::RB + 16u * (uint32_t)c;
+    __builtin_amdgcn_global_load_lds((glb_void_t*)((const unsigned char*)kh + off), (lds_void_t*)&sm.kb[buf][L * S::GSK], 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((glb_void_t*)((const unsigned char*)vh + off), (lds_void_t*)&sm.vb[buf][L * S::GSV], 16, 0, 0);
+}
+
 template <int D, int VPAD>
 __device__ __forceinline__ void issue_tile_loads(MfmaSmem<D, VPAD>& sm, int buf, const int32_t* jp,
                                                  const uint16_t* __restrict__ kh, const uint16_t* __restrict__ vh,
                                                  int wv, int lane)
 {
-    using S = MfmaSmem<D, VPAD>;
-    constexpr int LPR = S::RB / 16;  // lanes per row
-    const int jrow = lane / LPR, c = lane % LPR;
+    const TileRows<D, VPAD> rows = tile_rows<D, VPAD>(jp, wv, lane);
 #pragma unroll
-    for (int x = 0; x < S::NL / 4; x++) {
-        const int L = wv * (S::NL / 4) + x;
-        const uint32_t off = (uint32_t)jp[L + S::NL * jrow] * (uint32_t)S::RB + 16u * (uint32_t)c;
-        __builtin_amdgcn_global_load_lds((glb_void_t*)((const unsigned char*)kh + off), (lds_void_t*)&sm.kb[buf][L * S::GSK], 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((glb_void_t*)((const unsigned char*)vh + off), (lds_void_t*)&sm.vb[buf][L * S::GSV], 16, 0, 0);
-    }
+    for (int x = 0; x < MfmaSmem<D, VPAD>::NL / 4; x++) tile_load_step<D, VPAD>(sm, buf, rows, x, kh, vh, wv, lane);
 }
 
 
