@@ -36,14 +36,17 @@ size_t attn_fwd_ws_bytes(const sparsek_cfg& c) { return block_lists_bytes(c, nul
 // Per (row, block): the positions of the top-k of prefix T0 = blk*QB - w, in two partitions:
 // first the keys that stay selected for every query of the block (death >= T0 + QB, ascending),
 // then, filled from the back, the keys that expire inside the block.  Only the tiles of the
-// second partition need a per-pair validity test.  Each wave owns a quarter of [0, T0]: one
-// counting pass, one barrier, one placement pass.
+// second partition need a per-pair validity test.  Each of the 16 waves owns a slice of
+// [0, T0]: one counting pass, one barrier, one placement pass.
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void block_lists_kernel(const int32_t* __restrict__ death, int n, int k,
-                                                          int w, int nb, int32_t* __restrict__ lists,
-                                                          int32_t* __restrict__ counts)
+constexpr int BL_WAVES = 16;   // waves per workgroup of block_lists_kernel
+constexpr int BL_UNROLL = 8;   // loads in flight per lane
+
+__global__ __launch_bounds__(64 * BL_WAVES) void block_lists_kernel(const int32_t* __restrict__ death, int n, int k,
+                                                                     int w, int nb, int32_t* __restrict__ lists,
+                                                                     int32_t* __restrict__ counts)
 {
-    __shared__ int wstay[4], wgo[4];
+    __shared__ int wstay[BL_WAVES], wgo[BL_WAVES];
     const int blk = blockIdx.x, row = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int T0 = blk * QB - w;
@@ -57,32 +60,46 @@ __global__ __launch_bounds__(256) void block_lists_kernel(const int32_t* __restr
     }
     const int32_t* dr = death + (size_t)row * n;
     const int len = T0 + 1;
-    const int per = ((len + 3) / 4 + 255) / 256 * 256;
+    constexpr int STEP = 64 * BL_UNROLL;
+    const int per = ((len + BL_WAVES - 1) / BL_WAVES + STEP - 1) / STEP * STEP;
     const int j_lo = wv * per, j_hi = min(len, j_lo + per);
     const int stay_from = T0 + QB;
     const unsigned long long below = (1ull << lane) - 1ull;
     int ns = 0, ng = 0;
-    for (int j0 = j_lo; j0 < j_hi; j0 += 256) {
+    for (int j0 = j_lo; j0 < j_hi; j0 += STEP) {
+        int dj[BL_UNROLL];
 #pragma unroll
-        for (int e = 0; e < 4; e++) {
+        for (int e = 0; e < BL_UNROLL; e++) {
             const int j = j0 + 64 * e + lane;
-            const int dj = j < j_hi ? dr[j] : 0;
-            ns += __popcll(__ballot(dj >= stay_from));
-            ng += __popcll(__ballot(dj > T0 && dj < stay_from));
+            dj[e] = j < j_hi ? dr[j] : 0;
+        }
+#pragma unroll
+        for (int e = 0; e < BL_UNROLL; e++) {
+            ns += __popcll(__ballot(dj[e] >= stay_from));
+            ng += __popcll(__ballot(dj[e] > T0 && dj[e] < stay_from));
         }
     }
     if (lane == 0) { wstay[wv] = ns; wgo[wv] = ng; }
     __syncthreads();
-    int os = 0, og = 0;
-    for (int i = 0; i < wv; i++) { os += wstay[i]; og += wgo[i]; }
+    int os = 0, og = 0, tot_s = 0, tot_g = 0;
+    for (int i = 0; i < BL_WAVES; i++) {
+        if (i < wv) { os += wstay[i]; og += wgo[i]; }
+        tot_s += wstay[i];
+        tot_g += wgo[i];
+    }
     // min(k, T0 + 1) for a consistent death array; counted, so that every entry below cnt is written
-    const int cnt = min(k, wstay[0] + wstay[1] + wstay[2] + wstay[3] + wgo[0] + wgo[1] + wgo[2] + wgo[3]);
-    for (int j0 = j_lo; j0 < j_hi; j0 += 256) {
+    const int cnt = min(k, tot_s + tot_g);
+    for (int j0 = j_lo; j0 < j_hi; j0 += STEP) {
+        int dj[BL_UNROLL];
 #pragma unroll
-        for (int e = 0; e < 4; e++) {
+        for (int e = 0; e < BL_UNROLL; e++) {
             const int j = j0 + 64 * e + lane;
-            const int dj = j < j_hi ? dr[j] : 0;
-            const bool stay = dj >= stay_from, go = dj > T0 && dj < stay_from;
+            dj[e] = j < j_hi ? dr[j] : 0;
+        }
+#pragma unroll
+        for (int e = 0; e < BL_UNROLL; e++) {
+            const int j = j0 + 64 * e + lane;
+            const bool stay = dj[e] >= stay_from, go = dj[e] > T0 && dj[e] < stay_from;
             const unsigned long long bs = __ballot(stay), bg = __ballot(go);
             if (stay) {
                 const int o = os + __popcll(bs & below);
@@ -98,7 +115,7 @@ __global__ __launch_bounds__(256) void block_lists_kernel(const int32_t* __restr
     }
     if (tid == 0) {
         counts[(size_t)row * nb + blk] = cnt;
-        counts[((size_t)gridDim.y + row) * nb + blk] = min(cnt, wstay[0] + wstay[1] + wstay[2] + wstay[3]);
+        counts[((size_t)gridDim.y + row) * nb + blk] = min(cnt, tot_s);
     }
 }
 
@@ -657,7 +674,7 @@ void launch_block_lists(const sparsek_cfg& c, const int32_t* death, int32_t* lis
                         hipStream_t st)
 {
     const int nb = nblocks(c.n);
-    hipLaunchKernelGGL(block_lists_kernel, dim3(nb, c.B * c.Gu), dim3(256), 0, st, death, c.n, c.k, c.w, nb,
+    hipLaunchKernelGGL(block_lists_kernel, dim3(nb, c.B * c.Gu), dim3(64 * BL_WAVES), 0, st, death, c.n, c.k, c.w, nb,
                        lists, counts);
 }
 

@@ -6,12 +6,16 @@
 //   * tau_t and the k-th largest score theta_t never decrease once the prefix holds k
 //     entries (Sec. 3.2, irreversibility), so for a chunk starting at t0 only the scores
 //     above a lower bound lo <= tau_{t0-1} can matter; a first kernel finds such a bound
-//     at coarse boundaries, the chunk kernel compacts those candidates into LDS;
+//     at coarse boundaries, the chunk kernel compacts those candidates into LDS, sorts them
+//     once (selection order, bitonic) and takes fp64 prefix sums of the sorted scores;
 //   * inside a chunk every wave owns a few consecutive prefixes.  tau_t is the root of
 //     f_t(x) = sum clip(z - x, 0, 1) = k, found by repeating the closed form of the
 //     solution equation (tau from u*, w* and the fractional sum) until the pair (u*, w*)
 //     reproduces itself -- exact, not an iteration to a tolerance; a bracket guards it.
-//     Sums are fp64.  theta_t follows by "newcomer in, smallest out";
+//     One evaluation of (u*, w*, fractional sum) is two searches in the sorted list plus a
+//     difference of prefix sums for the older scores, and a direct pass over the chunk's own
+//     (at most CHUNK) scores, which enter one by one.  theta_t follows by "newcomer in,
+//     smallest out" with a pointer into the sorted list;
 //   * death[j] is the first t with sel_key(j) < theta_t: a binary search in the chunk.
 #include "common.hpp"
 
@@ -21,8 +25,7 @@ constexpr int CHUNK = 128;        // prefixes per workgroup of the chunk kernel
 constexpr int NT_CHUNK = 1024;    // threads of the chunk kernel (16 waves, 8 prefixes each)
 constexpr int NW_CHUNK = NT_CHUNK / 64;
 constexpr int SUPER = 2048;       // spacing of the coarse lower bounds
-constexpr int CAP = 8192;         // candidate capacity in LDS (scores + positions: 64 KB)
-constexpr int CAP_PAD = CAP + 8;  // room for the -inf padding that rounds both list regions to multiples of 4
+constexpr int CAP = 8192;         // candidate capacity in LDS (64-bit keys: 64 KB, fp64 prefix sums: 64 KB)
 constexpr int NT_COARSE = 1024;
 constexpr int NPROBE = 15;
 constexpr int NPASS = 3;
@@ -173,16 +176,20 @@ __global__ __launch_bounds__(NT_COARSE) void mask_coarse_kernel(const float* __r
 // ---------------------------------------------------------------------------------
 // Candidate lists: compacted in LDS, or (overflow fallback) the raw prefix in global memory.
 // ---------------------------------------------------------------------------------
-// LDS list: [0, mo4) older candidates (positions in idx[]; padding entries have score -inf and
-// position INT_MAX), [mo4, M) the chunk's own scores in order (position t0 + i - mo4; padding
-// beyond the chunk has score -inf).  Both regions are multiples of 4 long and 16-byte aligned.
-struct ListLds {
-    const float* v;
-    const int* idx;
-    int M, mo4, t0;
-    __device__ __forceinline__ float val(int i) const { return v[i]; }
-    __device__ __forceinline__ int pos(int i) const { return i < mo4 ? idx[i] : t0 + (i - mo4); }
+// Sorted list: key[0, m_old) = selection keys (score, then older position) of the older
+// candidates in descending order, pref[i] = sum of the scores of key[0, i) in fp64; the chunk's
+// own scores live in registers, two per lane (entries `lane` and `lane + 64` of the chunk).
+struct ListSorted {
+    const unsigned long long* key;
+    const double* pref;
+    int m_old, t0;
+    float nv0, nv1;  // this lane's chunk scores (-inf beyond the chunk)
 };
+__device__ __forceinline__ float key_score(unsigned long long key)
+{
+    return __uint_as_float(score_key_inv((uint32_t)(key >> 32)));
+}
+__device__ __forceinline__ int key_pos(unsigned long long key) { return (int)(0xFFFFFFFFu - (uint32_t)key); }
 struct ListGlobal {
     const float* u;
     int M;
@@ -218,46 +225,53 @@ __device__ __forceinline__ void eval_piece(const List& L, int t, double x, int l
     minF = wave_min_f32(mf);
 }
 
-// Same for the LDS list, four scores per lane and step.  The fp64 thresholds are replaced by
-// their round-down fp32 values: for an fp32 score v, v > x  <=>  v > rd(x).  The four scores of
-// a step are added in fp32, the step totals in fp64.  A sum with a single fractional score stays
-// exact, which the flat case (root exactly on a breakpoint, sup rule) relies on.
-__device__ __forceinline__ void eval_piece(const ListLds& L, int t, double x, int lane, int& F, int& S,
+// Same for the sorted list.  The fp64 thresholds are replaced by their round-down fp32 values:
+// for an fp32 score v, v > x  <=>  v > rd(x).  The counts over the older scores are the results
+// of two searches (32 probes a round; lanes 0..31 search x, lanes 32..63 search x + 1), their
+// fractional sum is a difference of prefix sums, or a direct sum when at most 64 scores are
+// fractional: a sum with a single fractional score has to stay exact, which the flat case
+// (root exactly on a breakpoint, sup rule) relies on.
+__device__ __forceinline__ void eval_piece(const ListSorted& L, int t, double x, int lane, int& F, int& S,
                                            double& fsum, float& minF)
 {
     const float xf = __double2float_rd(x), x1f = __double2float_rd(x + 1.0);
-    int f = 0, s = 0;
-    double sum = 0.0;
-    float mf = INFINITY;
-    auto add4 = [&](float4 q) {
-        float part = 0.0f;
-        auto one = [&](float v) {
-            const bool a = v > xf, b = v > x1f;
-            s += a ? 1 : 0;
-            f += b ? 1 : 0;
-            part += (a && !b) ? v : 0.0f;
-            mf = fminf(mf, b ? v : INFINITY);
-        };
-        one(q.x); one(q.y); one(q.z); one(q.w);
-        sum += (double)part;
-    };
-    const float4* v4 = (const float4*)L.v;
-    for (int i = lane; i < L.mo4 / 4; i += 64) add4(v4[i]);
-    const int nc = t - L.t0 + 1;  // chunk scores inside prefix t
-    const float4* c4 = (const float4*)(L.v + L.mo4);
-    for (int i = lane; i < (L.M - L.mo4) / 4; i += 64) {
-        float4 q = c4[i];
-        const int c = 4 * i;
-        q.x = (c < nc) ? q.x : -INFINITY;
-        q.y = (c + 1 < nc) ? q.y : -INFINITY;
-        q.z = (c + 2 < nc) ? q.z : -INFINITY;
-        q.w = (c + 3 < nc) ? q.w : -INFINITY;
-        add4(q);
+    const int hf = lane >> 5, l32 = lane & 31;
+    const float thr = hf ? x1f : xf;
+    int lo = 0, hi = L.m_old;  // the count lies in [lo, hi]: key[<lo] are above thr, key[>=hi] are not
+    while (__any(lo < hi)) {
+        const int stride = (hi - lo + 31) >> 5;
+        const int p = lo + l32 * stride;
+        const bool above = (p < hi) && (key_score(L.key[p]) > thr);
+        const unsigned long long ball = __ballot(above);
+        const int c = __popc(hf ? (unsigned)(ball >> 32) : (unsigned)ball);
+        if (lo < hi) {
+            if (c == 0) hi = lo;
+            else {
+                hi = min(hi, lo + c * stride);
+                lo = lo + (c - 1) * stride + 1;
+            }
+        }
     }
-    unsigned long long packed = wave_sum_u64(((unsigned long long)f << 32) | (unsigned long long)s);
-    F = (int)(packed >> 32);
-    S = (int)(packed & 0xFFFFFFFFull);
-    fsum = wave_sum_f64(sum);
+    const int b = __builtin_amdgcn_readlane(lo, 0);   // older scores above x
+    const int a = __builtin_amdgcn_readlane(lo, 32);  // older scores above x + 1
+    // the chunk's own scores inside prefix t
+    const int nc = t - L.t0 + 1;
+    const float v0 = (lane < nc) ? L.nv0 : -INFINITY, v1 = (lane + 64 < nc) ? L.nv1 : -INFINITY;
+    const bool a0 = v0 > xf, b0 = v0 > x1f, a1 = v1 > xf, b1 = v1 > x1f;
+    const int f = (b0 ? 1 : 0) + (b1 ? 1 : 0), sc = (a0 ? 1 : 0) + (a1 ? 1 : 0);
+    double part = (double)((a0 && !b0) ? v0 : 0.0f) + (double)((a1 && !b1) ? v1 : 0.0f);
+    float mf = fminf(b0 ? v0 : INFINITY, b1 ? v1 : INFINITY);
+    double base = 0.0;
+    if (b - a <= 64) {
+        if (lane < b - a) part += (double)key_score(L.key[a + lane]);
+    } else {
+        base = L.pref[b] - L.pref[a];
+    }
+    if (a > 0) mf = fminf(mf, key_score(L.key[a - 1]));
+    const unsigned long long packed = wave_sum_u64(((unsigned long long)f << 32) | (unsigned long long)sc);
+    F = a + (int)(packed >> 32);
+    S = b + (int)(packed & 0xFFFFFFFFull);
+    fsum = base + wave_sum_f64(part);
     minF = wave_min_f32(mf);
 }
 
@@ -396,27 +410,6 @@ __device__ __forceinline__ unsigned long long succ_key(const List& L, int tlim, 
     }
     return wave_min_u64(best);
 }
-// LDS list: branch-free scan of 64-bit keys, four entries per lane and step.
-__device__ __forceinline__ unsigned long long succ_key(const ListLds& L, int tlim, unsigned long long theta, int lane)
-{
-    unsigned long long best = ~0ull;
-    auto one = [&](float v, int p) {
-        const unsigned long long key = sel_key(v, p);
-        const bool ok = (p < tlim) && (key > theta) && (key < best);
-        best = ok ? key : best;
-    };
-    const float4* v4 = (const float4*)L.v;
-    const int4* i4 = (const int4*)L.idx;
-    for (int i = lane; i < L.mo4 / 4; i += 64) {
-        const float4 q = v4[i];
-        const int4 p = i4[i];
-        one(q.x, p.x); one(q.y, p.y); one(q.z, p.z); one(q.w, p.w);
-    }
-    const int nc = tlim - L.t0;  // chunk scores at positions < tlim
-    for (int c = lane; c < nc; c += 64) one(L.v[L.mo4 + c], L.t0 + c);
-    return wave_min_u64(best);
-}
-
 template <class List>
 __device__ __forceinline__ unsigned long long min_key(const List& L, int tlim, int lane)
 {
@@ -429,6 +422,23 @@ __device__ __forceinline__ unsigned long long min_key(const List& L, int tlim, i
         }
     }
     return wave_min_u64(best);
+}
+
+// Smallest score of prefix t.
+template <class List>
+__device__ __forceinline__ float prefix_min(const List& L, int t, int lane)
+{
+    float m2 = INFINITY;
+    for (int i = lane; i < L.M; i += 64)
+        if (L.pos(i) <= t) m2 = fminf(m2, L.val(i));
+    return wave_min_f32(m2);
+}
+__device__ __forceinline__ float prefix_min(const ListSorted& L, int t, int lane)
+{
+    const int nc = t - L.t0 + 1;
+    float m2 = fminf((lane < nc) ? L.nv0 : INFINITY, (lane + 64 < nc) ? L.nv1 : INFINITY);
+    if (L.m_old > 0) m2 = fminf(m2, key_score(L.key[L.m_old - 1]));
+    return wave_min_f32(m2);
 }
 
 // One wave, thresholds of prefixes [ta, tb) (those longer than k).
@@ -450,10 +460,7 @@ __device__ void wave_tau(const List& L, const float* __restrict__ ur, float* __r
             if (have_prev) start = tau_prev;
             else if (start0 > -INFINITY) start = (double)start0;
             else {  // no bound known: min(prefix) - 1 has f = t+1 >= k
-                float m2 = INFINITY;
-                for (int i = lane; i < L.M; i += 64)
-                    if (L.pos(i) <= t) m2 = fminf(m2, L.val(i));
-                start = (double)wave_min_f32(m2) - 1.0;
+                start = (double)prefix_min(L, t, lane) - 1.0;
             }
             tau = solve_tau(L, t, k, start, lane, status);
         }
@@ -487,12 +494,48 @@ __device__ void wave_theta(const List& L, const float* __restrict__ ur, int t0, 
     }
 }
 
+// The same walk on the sorted list: `na` older keys lie above theta, so the next older key above
+// theta is key[na - 1]; the chunk's own keys are compared in registers.
+__device__ void wave_theta(const ListSorted& L, const float* __restrict__ ur, int t0, int t1, int k,
+                           unsigned long long theta, int lane, unsigned long long* th)
+{
+    const unsigned long long k0 = sel_key(L.nv0, t0 + lane), k1 = sel_key(L.nv1, t0 + lane + 64);
+    int na = (t0 >= k) ? k - 1 : 0;  // theta = key[k - 1] at the start of a chunk beyond k
+    for (int t = t0; t < t1; t++) {
+        const int len = t + 1, c = t - t0;  // chunk entries 0..c-1 are inside prefix t-1, entry c is the newcomer
+        if (len == k) {
+            // every entry of the prefix is selected: theta is the smallest key
+            unsigned long long m = ~0ull;
+            if (lane <= c) m = k0;
+            if (lane + 64 <= c) m = k1 < m ? k1 : m;
+            m = wave_min_u64(m);
+            if (L.m_old > 0) m = L.key[L.m_old - 1] < m ? L.key[L.m_old - 1] : m;
+            theta = m;
+            na = L.m_old;
+            // older keys above theta: all but the one that equals it, if that one is the minimum
+            if (L.m_old > 0 && L.key[L.m_old - 1] == theta) na = L.m_old - 1;
+        } else if (len > k) {
+            const unsigned long long e = (c < 64) ? readlane_u64(k0, c) : readlane_u64(k1, c - 64);
+            if (e > theta) {
+                unsigned long long sc = ~0ull;
+                if (lane < c && k0 > theta) sc = k0;
+                if (lane + 64 < c && k1 > theta && k1 < sc) sc = k1;
+                sc = wave_min_u64(sc);
+                const unsigned long long so = (na > 0) ? L.key[na - 1] : ~0ull;
+                unsigned long long nt = e < sc ? e : sc;
+                if (so < nt) { nt = so; na--; }
+                theta = nt;
+            }
+        }
+        if (lane == 0) th[t - t0] = theta;
+    }
+}
+
 // death of one list entry given the chunk's theta sequence (non-decreasing).
-__device__ __forceinline__ void write_death(float v, int j, int t0, int t1, int k,
+__device__ __forceinline__ void write_death(unsigned long long key, int j, int t0, int t1, int k,
                                             const unsigned long long* th, unsigned long long th_start,
                                             int32_t* __restrict__ dr)
 {
-    const unsigned long long key = sel_key(v, j);
     int first;
     if (j < t0) {
         if (t0 >= k && key < th_start) return;  // already out before this chunk
@@ -535,8 +578,89 @@ __device__ void chunk_body(const List& L, const float* __restrict__ ur, float* _
     __syncthreads();
     for (int i = tid; i < L.M; i += NT_CHUNK) {
         const int p = L.pos(i);
-        if (p < t1) write_death(L.val(i), p, t0, t1, k, th, th_start, dr);
+        if (p < t1) write_death(sel_key(L.val(i), p), p, t0, t1, k, th, th_start, dr);
     }
+}
+
+// The same for the sorted list: theta at the chunk start is the k-th sorted key.
+__device__ void chunk_body_sorted(const ListSorted& L, const float* __restrict__ ur, float* __restrict__ tr,
+                                  int32_t* __restrict__ dr, int t0, int t1, int k, float lo,
+                                  unsigned long long* th, int* status)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const unsigned long long th_start = (t0 >= k) ? L.key[k - 1] : 0ull;
+    // tau lies in [z_(k) - 1, z_(k)), and both ends only rise: theta_{t0-1} - 1 bounds every tau of the chunk
+    float start0 = lo;
+    if (t0 >= k) start0 = fmaxf(lo, key_score(th_start) - 1.0f);
+    if (wv < NW_TAU) {
+        const int ta = min(t1, t0 + wv * TPW_TAU), tb = min(t1, ta + TPW_TAU);
+        wave_tau(L, ur, tr, ta, tb, k, start0, lane, status);
+    } else {
+        wave_theta(L, ur, t0, t1, k, th_start, lane, th);
+    }
+    __syncthreads();
+    for (int i = tid; i < L.m_old; i += NT_CHUNK) {
+        const unsigned long long key = L.key[i];
+        write_death(key, key_pos(key), t0, t1, k, th, th_start, dr);
+    }
+    if (tid < t1 - t0) write_death(sel_key(ur[t0 + tid], t0 + tid), t0 + tid, t0, t1, k, th, th_start, dr);
+}
+
+// Bitonic sort of key[0, N) in descending order, N a power of two >= 2048 (one or more pairs per
+// thread).  Each wave owns a contiguous run of N/32 compare-exchange pairs, so passes whose
+// stride fits into the wave's N/16 elements need no workgroup barrier: a wave's LDS accesses are
+// performed in program order.
+__device__ void bitonic_sort_desc(unsigned long long* key, int N)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int P = N / (2 * NW_CHUNK);  // pairs per wave
+    for (int k2 = 2; k2 <= N; k2 <<= 1) {
+        for (int j = k2 >> 1; j > 0; j >>= 1) {
+            if (j > P) __syncthreads();
+            for (int m = lane; m < P; m += 64) {
+                const int i = wv * P + m;
+                const int a = 2 * i - (i & (j - 1)), b = a + j;
+                const unsigned long long x = key[a], y = key[b];
+                const bool desc = (a & k2) == 0;
+                if ((x < y) == desc) {
+                    key[a] = y;
+                    key[b] = x;
+                }
+            }
+            if (j > P) __syncthreads();
+        }
+    }
+    __syncthreads();
+}
+
+// pref[i] = sum of the scores of key[0, i), i = 0..N, in fp64 (N a multiple of NT_CHUNK).
+__device__ void sorted_prefix_sums(const unsigned long long* key, double* pref, int N, int m_old, double* wtot)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int per = N / NT_CHUNK;
+    double run = 0.0;
+    for (int r = 0; r < per; r++) {
+        const int i = tid * per + r;
+        run += (i < m_old) ? (double)key_score(key[i]) : 0.0;
+    }
+    // inclusive scan of the thread totals across the wave, then across the waves
+    double inc = run;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const double y = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += y;
+    }
+    if (lane == 63) wtot[wv] = inc;
+    __syncthreads();
+    double before = inc - run;
+    for (int i = 0; i < wv; i++) before += wtot[i];
+    for (int r = 0; r < per; r++) {
+        const int i = tid * per + r;
+        pref[i] = before;
+        before += (i < m_old) ? (double)key_score(key[i]) : 0.0;
+    }
+    if (tid == NT_CHUNK - 1) pref[N] = before;
+    __syncthreads();
 }
 
 __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __restrict__ u,
@@ -545,10 +669,11 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
                                                                int32_t* __restrict__ death, int n, int k,
                                                                int nsuper, int* __restrict__ status)
 {
-    __shared__ __align__(16) float cand_val[CAP_PAD];
-    __shared__ __align__(16) int cand_idx[CAP_PAD];
+    __shared__ __align__(16) unsigned long long skey[CAP];
+    __shared__ __align__(16) double pref[CAP + 1];
     __shared__ unsigned long long th[CHUNK];
     __shared__ unsigned hist[256];
+    __shared__ double wtot[NW_CHUNK];
     __shared__ int wcount[NW_CHUNK + 1];
     __shared__ unsigned long long bc;
 
@@ -561,8 +686,8 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
     int32_t* dr = death + (size_t)row * n;
     const float lo = lo_in[(size_t)row * nsuper + t0 / SUPER];
 
-    // ---- ordered compaction of {j < t0 : u_j > lo}: each wave owns a contiguous slice, read in
-    // segments of 64*SLICE_REG scores held in registers (independent loads, one latency) ----
+    // ---- compaction of {j < t0 : u_j > lo} as selection keys: each wave owns a contiguous slice,
+    // read in segments of 64*SLICE_REG scores held in registers (independent loads, one latency) ----
     const int per = ((t0 + NW_CHUNK - 1) / NW_CHUNK + 63) / 64 * 64;
     const int sb = min(t0, wv * per), se = min(t0, sb + per);
     constexpr int SEGN = 64 * SLICE_REG;
@@ -586,9 +711,12 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
     }
     __syncthreads();
     const int m_old = wcount[NW_CHUNK];
-    const int mo4 = (m_old + 3) & ~3, cn = t1 - t0, cn4 = (cn + 3) & ~3;
-    const bool fits = (m_old + cn <= CAP);
+    // the list must hold the whole top-k of every prefix of the chunk (it does when lo is a lower
+    // bound of tau; checked, not assumed)
+    const bool fits = (m_old <= CAP) && (t0 < k || m_old >= k);
     if (fits) {
+        int npad = 2 * NT_CHUNK;
+        while (npad < m_old) npad <<= 1;
         int off = wcount[wv];
         for (int g0 = sb; g0 < se; g0 += SEGN) {
             float z[SLICE_REG];
@@ -601,28 +729,20 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
             for (int r = 0; r < SLICE_REG; r++) {
                 const bool p = z[r] > lo;
                 const unsigned long long ball = __ballot(p);
-                if (p) {
-                    const int o = off + __popcll(ball & ((1ull << lane) - 1ull));
-                    cand_val[o] = z[r];
-                    cand_idx[o] = g0 + r * 64 + lane;
-                }
+                if (p) skey[off + __popcll(ball & ((1ull << lane) - 1ull))] = sel_key(z[r], g0 + r * 64 + lane);
                 off += __popcll(ball);
             }
         }
-        for (int i = m_old + tid; i < mo4; i += NT_CHUNK) {  // pad the older region to a multiple of 4
-            cand_val[i] = -INFINITY;
-            cand_idx[i] = 0x7FFFFFFF;
+        for (int i = m_old + tid; i < npad; i += NT_CHUNK) skey[i] = 0ull;  // below every real key
+        __syncthreads();
+        if (m_old > 0) {
+            bitonic_sort_desc(skey, npad);
+            sorted_prefix_sums(skey, pref, npad, m_old, wtot);
         }
-        for (int i = tid; i < cn4; i += NT_CHUNK) {
-            cand_val[mo4 + i] = (i < cn) ? ur[t0 + i] : -INFINITY;
-            cand_idx[mo4 + i] = (i < cn) ? t0 + i : 0x7FFFFFFF;
-        }
-    }
-    __syncthreads();
-
-    if (fits) {
-        ListLds L{cand_val, cand_idx, mo4 + cn4, mo4, t0};
-        chunk_body(L, ur, tr, dr, t0, t1, k, lo, hist, &bc, th, status);
+        const int cn = t1 - t0;
+        ListSorted L{skey, pref, m_old, t0, (lane < cn) ? ur[t0 + lane] : -INFINITY,
+                     (lane + 64 < cn) ? ur[t0 + lane + 64] : -INFINITY};
+        chunk_body_sorted(L, ur, tr, dr, t0, t1, k, lo, th, status);
     } else {
         ListGlobal L{ur, t1};
         chunk_body(L, ur, tr, dr, t0, t1, k, -INFINITY, hist, &bc, th, status);
