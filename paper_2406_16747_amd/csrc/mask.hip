@@ -225,14 +225,21 @@ __device__ __forceinline__ void eval_piece(const List& L, int t, double x, int l
     minF = wave_min_f32(mf);
 }
 
-// Same for the sorted list.  The fp64 thresholds are replaced by their round-down fp32 values:
-// for an fp32 score v, v > x  <=>  v > rd(x).  The counts over the older scores are the results
-// of two searches (32 probes a round; lanes 0..31 search x, lanes 32..63 search x + 1), their
-// fractional sum is a difference of prefix sums, or a direct sum when at most 64 scores are
-// fractional: a sum with a single fractional score has to stay exact, which the flat case
-// (root exactly on a breakpoint, sup rule) relies on.
-__device__ __forceinline__ void eval_piece(const ListSorted& L, int t, double x, int lane, int& F, int& S,
-                                           double& fsum, float& minF)
+// The linear piece of f_t that contains x (right-limit counts), for the sorted list.
+struct Piece {
+    int F, S, a;      // a = older scores above x + 1
+    double fsum;
+    double next_old;  // smallest breakpoint of the older scores above x (+inf if none)
+    double prev_old;  // largest breakpoint of the older scores at or below x (-inf if none)
+};
+
+// The fp64 thresholds are replaced by their round-down fp32 values: for an fp32 score v,
+// v > x  <=>  v > rd(x).  The counts over the older scores are the results of two searches
+// (32 probes a round; lanes 0..31 search x, lanes 32..63 search x + 1), their fractional sum is a
+// difference of prefix sums, or a direct sum when at most 64 scores are fractional: a sum with a
+// single fractional score has to stay exact, which the flat case (root exactly on a breakpoint,
+// sup rule) relies on.  The chunk's own scores are added from registers.
+__device__ __forceinline__ Piece eval_sorted(const ListSorted& L, int t, double x, int lane)
 {
     const float xf = __double2float_rd(x), x1f = __double2float_rd(x + 1.0);
     const int hf = lane >> 5, l32 = lane & 31;
@@ -254,31 +261,62 @@ __device__ __forceinline__ void eval_piece(const ListSorted& L, int t, double x,
     }
     const int b = __builtin_amdgcn_readlane(lo, 0);   // older scores above x
     const int a = __builtin_amdgcn_readlane(lo, 32);  // older scores above x + 1
+    Piece P;
+    P.a = a;
+    // neighbouring breakpoints of the older scores (uniform addresses: broadcast reads)
+    P.next_old = INFINITY;
+    P.prev_old = -INFINITY;
+    if (b > 0) P.next_old = (double)key_score(L.key[b - 1]);
+    if (a > 0) P.next_old = fmin(P.next_old, (double)key_score(L.key[a - 1]) - 1.0);
+    if (b < L.m_old) P.prev_old = (double)key_score(L.key[b]);
+    if (a < L.m_old) P.prev_old = fmax(P.prev_old, (double)key_score(L.key[a]) - 1.0);
     // the chunk's own scores inside prefix t
     const int nc = t - L.t0 + 1;
     const float v0 = (lane < nc) ? L.nv0 : -INFINITY, v1 = (lane + 64 < nc) ? L.nv1 : -INFINITY;
     const bool a0 = v0 > xf, b0 = v0 > x1f, a1 = v1 > xf, b1 = v1 > x1f;
     const int f = (b0 ? 1 : 0) + (b1 ? 1 : 0), sc = (a0 ? 1 : 0) + (a1 ? 1 : 0);
     double part = (double)((a0 && !b0) ? v0 : 0.0f) + (double)((a1 && !b1) ? v1 : 0.0f);
-    float mf = fminf(b0 ? v0 : INFINITY, b1 ? v1 : INFINITY);
     double base = 0.0;
     if (b - a <= 64) {
         if (lane < b - a) part += (double)key_score(L.key[a + lane]);
     } else {
         base = L.pref[b] - L.pref[a];
     }
-    if (a > 0) mf = fminf(mf, key_score(L.key[a - 1]));
     const unsigned long long packed = wave_sum_u64(((unsigned long long)f << 32) | (unsigned long long)sc);
-    F = a + (int)(packed >> 32);
-    S = b + (int)(packed & 0xFFFFFFFFull);
-    fsum = base + wave_sum_f64(part);
-    minF = wave_min_f32(mf);
+    P.F = a + (int)(packed >> 32);
+    P.S = b + (int)(packed & 0xFFFFFFFFull);
+    P.fsum = base + wave_sum_f64(part);
+    return P;
+}
+
+// Smallest score above x + 1 in prefix t (the flat case needs it).
+__device__ __forceinline__ float min_saturated(const ListSorted& L, int t, double x, int a, int lane)
+{
+    const float x1f = __double2float_rd(x + 1.0);
+    const int nc = t - L.t0 + 1;
+    const float v0 = (lane < nc) ? L.nv0 : -INFINITY, v1 = (lane + 64 < nc) ? L.nv1 : -INFINITY;
+    float mf = fminf(v0 > x1f ? v0 : INFINITY, v1 > x1f ? v1 : INFINITY);
+    if (a > 0) mf = fminf(mf, key_score(L.key[a - 1]));
+    return wave_min_f32(mf);
+}
+
+// True if none of the chunk's own scores inside prefix t has a breakpoint (z or z - 1) in (lo, hi].
+__device__ __forceinline__ bool own_piece_clear(const ListSorted& L, int t, double lo, double hi, int lane)
+{
+    const int nc = t - L.t0 + 1;
+    const double v0 = (double)L.nv0, v1 = (double)L.nv1;
+    const bool h0 = (lane < nc) && ((v0 > lo && v0 <= hi) || (v0 - 1.0 > lo && v0 - 1.0 <= hi));
+    const bool h1 = (lane + 64 < nc) && ((v1 > lo && v1 <= hi) || (v1 - 1.0 > lo && v1 - 1.0 <= hi));
+    return __ballot(h0 || h1) == 0ull;
 }
 
 // tau of prefix t (t+1 > k >= 1) starting from a point `start` with f_t(start) >= k.
 // Repeats tau <- (fsum + F - k)/(S - F) (solution equation of Sec. 3.3 with u* = F, w* = S)
 // until (F, S) at the new point equal those it was computed from; then that point is the
-// exact root of its linear piece.  Overshoots fall back to bisection of the bracket.
+// exact root of its linear piece.  The step is the root of the linear piece through the current
+// point, taken from whichever side of the root the point lies on (f_t is neither convex nor
+// concave, so a one-sided iteration would creep); a bracket [lo_b, hi_b) of the root is kept and
+// a step that leaves it is replaced by its midpoint.
 template <class List>
 __device__ double solve_tau(const List& L, int t, int k, double start, int lane, int* status)
 {
@@ -290,34 +328,34 @@ __device__ double solve_tau(const List& L, int t, int k, double start, int lane,
         float minF;
         eval_piece(L, t, x, lane, F, S, fsum, minF);
         if (F == pF && S == pS) return x;
+        pF = pS = -1;
         const double f = (double)F + fsum - (double)(S - F) * x;
-        if (f < (double)k) {  // overshoot: x is right of the root
-            hi_b = x;
-            pF = pS = -1;
-            double mid = 0.5 * (lo_b + hi_b);
+        double xn;
+        bool have = false;
+        if (f < (double)k) {
+            hi_b = x;  // x is right of the root
+            if (S > F) { xn = (fsum + (double)F - (double)k) / (double)(S - F); have = true; }
+        } else {
+            lo_b = x;
+            if (S == F) {  // flat to the right of x, f == F there
+                if (F == k) return (double)minF - 1.0;  // sup of the level set f == k
+                xn = (double)minF - 1.0;                 // F > k: the next breakpoint, still left of the root
+                if (xn < hi_b) { x = xn; continue; }
+            } else {
+                xn = (fsum + (double)F - (double)k) / (double)(S - F);
+                if (!(xn > x)) return x;  // f(x) == k up to rounding
+                have = true;
+            }
+        }
+        if (have && xn > lo_b && xn < hi_b) {
+            pF = F;
+            pS = S;
+            x = xn;
+        } else {
+            const double mid = 0.5 * (lo_b + hi_b);
             if (!(mid > lo_b && mid < hi_b)) return lo_b;
             x = mid;
-            continue;
         }
-        lo_b = x;
-        if (S == F) {  // flat to the right of x, f == F there
-            if (F == k) return (double)minF - 1.0;  // sup of the level set f == k
-            x = (double)minF - 1.0;                  // F > k: next breakpoint
-            pF = pS = -1;
-            continue;
-        }
-        const double xn = (fsum + (double)F - (double)k) / (double)(S - F);
-        if (!(xn > x)) return x;  // f(x) == k up to rounding
-        if (xn >= hi_b) {
-            pF = pS = -1;
-            double mid = 0.5 * (lo_b + hi_b);
-            if (!(mid > lo_b && mid < hi_b)) return lo_b;
-            x = mid;
-            continue;
-        }
-        pF = F;
-        pS = S;
-        x = xn;
     }
     if (lane == 0) atomicOr(status, 1);
     return x;
@@ -470,6 +508,85 @@ __device__ void wave_tau(const List& L, const float* __restrict__ ur, float* __r
     }
 }
 
+// The same for the sorted list, with the linear piece carried from prefix to prefix: a new score
+// above the threshold changes the counts of the current piece by one, the root of that piece is
+// the closed form, and it is final if no breakpoint lies between the old and the new threshold
+// (the sorted neighbours and one ballot over the chunk's own scores tell).  Only otherwise the
+// piece is evaluated again (eval_sorted), with the two-sided iteration of solve_tau.
+__device__ void wave_tau(const ListSorted& L, const float* __restrict__ ur, float* __restrict__ tr, int ta,
+                         int tb, int k, float start0, int lane, int* status)
+{
+    const float my_u = (ta + lane < tb) ? ur[ta + lane] : 0.0f;  // tb - ta <= 64
+    bool started = false;  // x = tau of the previous prefix
+    bool have = false;     // and P describes the piece of that prefix's f at x
+    double x = 0.0;
+    Piece P;
+    for (int t = ta; t < tb; t++) {
+        if (t + 1 <= k) continue;  // written by the coarse kernel's short-prefix scan
+        const float utf = readlane_f32(my_u, t - ta);
+        const double ut = (double)utf;
+        if (started && !(ut > x)) {  // the new score is below the threshold: nothing changes
+            if (lane == 0) tr[t] = (float)x;
+            continue;
+        }
+        if (have) {
+            if (ut > x + 1.0) { P.F++; P.S++; }
+            else { P.S++; P.fsum += ut; }
+        } else {
+            if (!started) {
+                if (start0 > -INFINITY) x = (double)start0;
+                else x = (double)prefix_min(L, t, lane) - 1.0;  // no bound known: f = t+1 >= k there
+            }
+            P = eval_sorted(L, t, x, lane);  // tau only rises: f_t(x) >= k at the previous tau too
+            have = true;
+        }
+        started = true;
+        // two-sided iteration on f_t from the piece P at x
+        double lo_b = x, hi_b = INFINITY;
+        int it = 0;
+        for (; it < MAX_ITERS; it++) {
+            const double f = (double)P.F + P.fsum - (double)(P.S - P.F) * x;
+            double xn = 0.0;
+            bool step = false;
+            if (f < (double)k) {
+                hi_b = x;
+                if (P.S > P.F) {
+                    xn = (P.fsum + (double)P.F - (double)k) / (double)(P.S - P.F);
+                    // still inside the piece (it starts at the largest breakpoint <= x): exact root
+                    if (xn < x && xn >= P.prev_old && own_piece_clear(L, t, xn, x, lane)) { x = xn; break; }
+                    step = xn > lo_b && xn < hi_b;
+                }
+            } else {
+                lo_b = x;
+                if (P.S == P.F) {  // flat to the right of x, f == F there
+                    const double nb = (double)min_saturated(L, t, x, P.a, lane) - 1.0;  // next breakpoint
+                    if (P.F == k) {  // sup of the level set f == k; the piece changes there
+                        x = nb;
+                        have = false;
+                        break;
+                    }
+                    xn = nb;  // F > k: still left of the root
+                    step = xn < hi_b;
+                } else {
+                    xn = (P.fsum + (double)P.F - (double)k) / (double)(P.S - P.F);
+                    if (!(xn > x)) break;  // f(x) == k up to rounding
+                    if (xn < P.next_old && own_piece_clear(L, t, x, xn, lane)) { x = xn; break; }
+                    step = xn < hi_b;
+                }
+            }
+            if (!step) {
+                const double mid = 0.5 * (lo_b + hi_b);
+                if (!(mid > lo_b && mid < hi_b)) { x = lo_b; have = false; break; }
+                xn = mid;
+            }
+            x = xn;
+            P = eval_sorted(L, t, x, lane);
+        }
+        if (it == MAX_ITERS && lane == 0) atomicOr(status, 1);
+        if (lane == 0) tr[t] = (float)x;
+    }
+}
+
 // One wave, the whole chunk: theta_t = k-th largest selection key of prefix t (0 while the
 // prefix is shorter than k), by "newcomer in, smallest out" starting from theta_{t0-1}.
 template <class List>
@@ -495,12 +612,69 @@ __device__ void wave_theta(const List& L, const float* __restrict__ ur, int t0, 
 }
 
 // The same walk on the sorted list: `na` older keys lie above theta, so the next older key above
-// theta is key[na - 1]; the chunk's own keys are compared in registers.
+// theta is key[na - 1]; the chunk's own keys are compared in registers.  This walk is the one
+// sequential dependency of a chunk, so it is kept short: in a chunk whose prefixes all hold more
+// than k entries only the newcomers above the starting theta are visited (the others can never
+// enter the top-k: theta only rises), the next two older keys are held in registers, and the
+// steps in between are filled in afterwards with a prefix maximum.
 __device__ void wave_theta(const ListSorted& L, const float* __restrict__ ur, int t0, int t1, int k,
                            unsigned long long theta, int lane, unsigned long long* th)
 {
     const unsigned long long k0 = sel_key(L.nv0, t0 + lane), k1 = sel_key(L.nv1, t0 + lane + 64);
-    int na = (t0 >= k) ? k - 1 : 0;  // theta = key[k - 1] at the start of a chunk beyond k
+    if (t0 >= k) {
+        __builtin_amdgcn_s_setprio(3);  // the other waves of the workgroup wait for this one
+        const unsigned long long th_start = theta;
+        int na = k - 1;  // theta = key[k - 1]
+        unsigned long long so0 = na > 0 ? L.key[na - 1] : ~0ull, so1 = na > 1 ? L.key[na - 2] : ~0ull;
+        th[lane] = 0ull;
+        th[lane + 64] = 0ull;
+        const int cn = t1 - t0;
+        unsigned long long m[2] = {__ballot(lane < cn && k0 > th_start), __ballot(lane + 64 < cn && k1 > th_start)};
+        for (int h = 0; h < 2; h++) {
+            unsigned long long todo = m[h];
+            while (todo) {
+                const int cl = __builtin_ctzll(todo);
+                todo &= todo - 1;
+                const int c = 64 * h + cl;  // chunk entries 0..c-1 are inside the prefix, entry c is the newcomer
+                const unsigned long long e = h ? readlane_u64(k1, cl) : readlane_u64(k0, cl);
+                if (e > theta) {
+                    unsigned long long sc = ~0ull;
+                    if (lane < c && k0 > theta) sc = k0;
+                    if (lane + 64 < c && k1 > theta && k1 < sc) sc = k1;
+                    sc = wave_min_u64(sc);
+                    unsigned long long nt = e < sc ? e : sc;
+                    if (so0 < nt) {
+                        nt = so0;
+                        na--;
+                        so0 = so1;
+                        so1 = na > 1 ? L.key[na - 2] : ~0ull;
+                    }
+                    theta = nt;
+                    if (lane == 0) th[c] = theta;
+                }
+            }
+        }
+        // th[i] = max(th_start, th[0..i]): inclusive prefix maximum over the 128 entries
+        unsigned long long a = th[lane], b = th[lane + 64];
+        a = a > th_start ? a : th_start;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const unsigned long long y = __shfl_up(a, o, 64);
+            if (lane >= o && y > a) a = y;
+        }
+        const unsigned long long top = readlane_u64(a, 63);
+        b = b > top ? b : top;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const unsigned long long y = __shfl_up(b, o, 64);
+            if (lane >= o && y > b) b = y;
+        }
+        th[lane] = a;
+        th[lane + 64] = b;
+        __builtin_amdgcn_s_setprio(0);
+        return;
+    }
+    int na = 0;
     for (int t = t0; t < t1; t++) {
         const int len = t + 1, c = t - t0;  // chunk entries 0..c-1 are inside prefix t-1, entry c is the newcomer
         if (len == k) {
