@@ -807,6 +807,77 @@ __device__ void bitonic_sort_desc(unsigned long long* key, int N)
     __syncthreads();
 }
 
+// Sort key[0, m) in descending order by distribution: NB value buckets between the smallest and
+// the largest score (one counting pass, one scan, one scatter into `tmp`), then every element
+// finds its rank inside its bucket by reading the bucket (a handful of elements for spread-out
+// scores) and goes to its final place in key[].  Returns false, with key[] untouched, when some
+// bucket holds more than BUCKET_MAX elements (many equal or clustered scores): the caller then
+// sorts by comparison.  The result depends on the keys only, not on the order of the atomics.
+constexpr int NB = 2048;
+constexpr int BUCKET_MAX = 96;
+
+__device__ bool bucket_sort_desc(unsigned long long* key, unsigned long long* tmp, int m, float vmin, float vmax,
+                                 int* bcount /* [NB] */, int* boff /* [NB + 1] */, int* flag, int* wsum /* [NW_CHUNK] */)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const float scale = (float)NB / (vmax - vmin);
+    auto bucket = [&](unsigned long long kk) {
+        const float v = key_score(kk);
+        int b = (int)((v - vmin) * scale);
+        b = max(0, min(NB - 1, b));
+        return NB - 1 - b;  // larger scores first
+    };
+    for (int i = tid; i < NB; i += NT_CHUNK) bcount[i] = 0;
+    if (tid == 0) *flag = 0;
+    __syncthreads();
+    for (int i = tid; i < m; i += NT_CHUNK) atomicAdd(&bcount[bucket(key[i])], 1);
+    __syncthreads();
+    // exclusive scan of the NB counts (NB / NT_CHUNK consecutive buckets per thread)
+    constexpr int BPT = NB / NT_CHUNK;
+    int c[BPT], tot = 0, big = 0;
+#pragma unroll
+    for (int r = 0; r < BPT; r++) {
+        c[r] = bcount[tid * BPT + r];
+        tot += c[r];
+        big |= c[r] > BUCKET_MAX ? 1 : 0;
+    }
+    int inc = tot;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int y = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += y;
+    }
+    if (lane == 63) wsum[wv] = inc;
+    if (big) *flag = 1;
+    __syncthreads();
+    if (*flag) return false;
+    int before = inc - tot;
+    for (int i = 0; i < wv; i++) before += wsum[i];
+#pragma unroll
+    for (int r = 0; r < BPT; r++) {
+        boff[tid * BPT + r] = before;
+        bcount[tid * BPT + r] = before;  // scatter cursor
+        before += c[r];
+    }
+    if (tid == NT_CHUNK - 1) boff[NB] = before;
+    __syncthreads();
+    for (int i = tid; i < m; i += NT_CHUNK) {
+        const unsigned long long kk = key[i];
+        tmp[atomicAdd(&bcount[bucket(kk)], 1)] = kk;
+    }
+    __syncthreads();
+    for (int i = tid; i < m; i += NT_CHUNK) {
+        const unsigned long long kk = tmp[i];
+        const int b = bucket(kk);
+        const int b0 = boff[b], b1 = boff[b + 1];
+        int rank = 0;
+        for (int j = b0; j < b1; j++) rank += tmp[j] > kk ? 1 : 0;
+        key[b0 + rank] = kk;
+    }
+    __syncthreads();
+    return true;
+}
+
 // pref[i] = sum of the scores of key[0, i), i = 0..N, in fp64 (N a multiple of NT_CHUNK).
 __device__ void sorted_prefix_sums(const unsigned long long* key, double* pref, int N, int m_old, double* wtot)
 {
@@ -849,6 +920,8 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
     __shared__ unsigned hist[256];
     __shared__ double wtot[NW_CHUNK];
     __shared__ int wcount[NW_CHUNK + 1];
+    __shared__ float wmin[NW_CHUNK], wmax[NW_CHUNK];
+    __shared__ int bcount[NB], boff[NB + 1], bflag, wsum[NW_CHUNK];
     __shared__ unsigned long long bc;
 
     const int c = blockIdx.x, row = blockIdx.y;
@@ -866,6 +939,7 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
     const int sb = min(t0, wv * per), se = min(t0, sb + per);
     constexpr int SEGN = 64 * SLICE_REG;
     int cnt = 0;
+    float cmin = INFINITY, cmax = -INFINITY;  // range of the candidates
     for (int g0 = sb; g0 < se; g0 += SEGN) {
         float z[SLICE_REG];
 #pragma unroll
@@ -874,9 +948,16 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
             z[r] = (i < se) ? ur[i] : -INFINITY;
         }
 #pragma unroll
-        for (int r = 0; r < SLICE_REG; r++) cnt += __popcll(__ballot(z[r] > lo));
+        for (int r = 0; r < SLICE_REG; r++) {
+            const bool p = z[r] > lo;
+            cnt += __popcll(__ballot(p));
+            cmin = p ? fminf(cmin, z[r]) : cmin;
+            cmax = p ? fmaxf(cmax, z[r]) : cmax;
+        }
     }
-    if (lane == 0) wcount[wv] = cnt;
+    cmin = wave_min_f32(cmin);
+    cmax = wave_max_f32(cmax);
+    if (lane == 0) { wcount[wv] = cnt; wmin[wv] = cmin; wmax[wv] = cmax; }
     __syncthreads();
     if (tid == 0) {
         int run = 0;
@@ -910,7 +991,11 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
         for (int i = m_old + tid; i < npad; i += NT_CHUNK) skey[i] = 0ull;  // below every real key
         __syncthreads();
         if (m_old > 0) {
-            bitonic_sort_desc(skey, npad);
+            float vmin = INFINITY, vmax = -INFINITY;
+            for (int i = 0; i < NW_CHUNK; i++) { vmin = fminf(vmin, wmin[i]); vmax = fmaxf(vmax, wmax[i]); }
+            // pref[] is free until the prefix sums are taken: scratch of the distribution sort
+            if (!bucket_sort_desc(skey, (unsigned long long*)pref, m_old, vmin, vmax, bcount, boff, &bflag, wsum))
+                bitonic_sort_desc(skey, npad);
             sorted_prefix_sums(skey, pref, npad, m_old, wtot);
         }
         const int cn = t1 - t0;
