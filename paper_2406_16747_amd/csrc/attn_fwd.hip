@@ -281,7 +281,6 @@ __device__ __forceinline__ void rescale_o(f32x16 (&acc_o)[D / 32], float alpha)
 // consecutive keys), their gates and lifetimes.
 struct HalfState {
     float4 G[4];   // scores, overwritten by the gates
-    int4 L[4];     // last query that attends the key
     float tmax, mc, alpha, psum;
     bf16x8 pb[2];  // P^T in operand layout
 };
@@ -294,7 +293,6 @@ __device__ __forceinline__ void load_meta(HalfState& h, const int32_t* jlast, co
     for (int g4 = 0; g4 < 4; g4++) {
         const int kb = 32 * hf + 8 * g4 + 4 * half;
         if (TT::GATED) h.G[g4] = *(const float4*)&ju[kb];
-        if (TT::MASKL) h.L[g4] = *(const int4*)&jlast[kb];
     }
     h.tmax = -INFINITY;
     h.psum = 0.0f;
@@ -307,15 +305,19 @@ __device__ __forceinline__ void load_meta(HalfState& h, const int32_t* jlast, co
 // keeps the rescale of the output accumulator a rare event).  U = 4..7: exponentials, row sum,
 // value gate and bf16 packing of key group U - 4.
 template <int MODE, int KIND, int U>
-__device__ __forceinline__ void softmax_slice(HalfState& h, f32x16& sv, int hf, int qi, int dqh, int dqw,
-                                              float tau_q, float c2, float& m_run)
+__device__ __forceinline__ void softmax_slice(HalfState& h, f32x16& sv, const int32_t* jlast, int half, int hf,
+                                              int qi, int dqh, int dqw, float tau_q, float c2, float& m_run)
 {
     using TT = TileTraits<MODE, KIND>;
     constexpr float LAZY_LOG2 = 8.0f;
     if (U < 4) {
         constexpr int g4 = U & 3;
         float gg[4] = {h.G[g4].x, h.G[g4].y, h.G[g4].z, h.G[g4].w};
-        const int ll[4] = {h.L[g4].x, h.L[g4].y, h.L[g4].z, h.L[g4].w};
+        // lifetimes are read where they are used (only the few masked tile kinds need them):
+        // holding them across the tile costs more registers than the kernel has
+        int4 L4 = make_int4(0, 0, 0, 0);
+        if (TT::MASKL) L4 = *(const int4*)&jlast[32 * hf + 8 * g4 + 4 * half];
+        const int ll[4] = {L4.x, L4.y, L4.z, L4.w};
 #pragma unroll
         for (int e = 0; e < 4; e++) {
             const int r = 4 * g4 + e;
@@ -361,12 +363,12 @@ __device__ __forceinline__ void softmax_slice(HalfState& h, f32x16& sv, int hf, 
 }
 
 template <int MODE, int KIND, int U0, int U1>
-__device__ __forceinline__ void softmax_slices(HalfState& h, f32x16& sv, int hf, int qi, int dqh, int dqw,
-                                               float tau_q, float c2, float& m_run)
+__device__ __forceinline__ void softmax_slices(HalfState& h, f32x16& sv, const int32_t* jlast, int half, int hf,
+                                               int qi, int dqh, int dqw, float tau_q, float c2, float& m_run)
 {
     if constexpr (U0 < U1) {
-        softmax_slice<MODE, KIND, U0>(h, sv, hf, qi, dqh, dqw, tau_q, c2, m_run);
-        softmax_slices<MODE, KIND, U0 + 1, U1>(h, sv, hf, qi, dqh, dqw, tau_q, c2, m_run);
+        softmax_slice<MODE, KIND, U0>(h, sv, jlast, half, hf, qi, dqh, dqw, tau_q, c2, m_run);
+        softmax_slices<MODE, KIND, U0 + 1, U1>(h, sv, jlast, half, hf, qi, dqh, dqw, tau_q, c2, m_run);
     }
 }
 
@@ -455,8 +457,8 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
         if (n < NX && more) tile_load_step<D, 64>(sm, buf ^ 1, rows, n, kh, vh, wv, lane);
         if (n >= NS) {
             constexpr int s = n >= NS ? n - NS : 0;
-            softmax_slices<MODE, KIND, US * s, US * (s + 1)>(A, sA, 0, qi, dqh, dqw, tau_q, c2, m_run);
-            if (US * (s + 1) == 4) load_meta<MODE, KIND>(B, jlast, ju, 1, half);  // A's lifetimes are dead by now
+            softmax_slices<MODE, KIND, US * s, US * (s + 1)>(A, sA, jlast, half, 0, qi, dqh, dqw, tau_q, c2, m_run);
+            if (US * (s + 1) == 4) load_meta<MODE, KIND>(B, jlast, ju, 1, half);
         }
         __builtin_amdgcn_sched_barrier(0);
     });
@@ -471,7 +473,7 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
         const bf16x8 cur = ring[n % DEPTH];
         acc_o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, A.pb[i / DB], acc_o[i % DB], 0, 0, 0);
         if (n + DEPTH < NSLOT) ring[n % DEPTH] = operand(n + DEPTH);
-        softmax_slices<MODE, KIND, UP * i, UP * (i + 1)>(B, sB, 1, qi, dqh, dqw, tau_q, c2, m_run);
+        softmax_slices<MODE, KIND, UP * i, UP * (i + 1)>(B, sB, jlast, half, 1, qi, dqh, dqw, tau_q, c2, m_run);
         __builtin_amdgcn_sched_barrier(0);
     });
     asm volatile("" ::"v"(B.pb[0]), "v"(B.pb[1]), "v"(B.psum));
