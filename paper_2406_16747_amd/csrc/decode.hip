@@ -238,12 +238,38 @@ __global__ __launch_bounds__(NT_ROW) void decode_update_kernel(sparsek_decode_cf
     const int k = c.k, w = c.w;
     const int t = *R.pos;
     int nsel = *R.nsel, ncand = *R.ncand;
+    const int nfree0 = *R.nfree;
     const double tau_old = *R.tau_d;
     const float unew = u_new[row];
+    // The new token's K/V rows of this score row's heads do not depend on the state: fetch the
+    // first batch (16-byte vectors, 4 per thread and tensor) now, store it once the slot is known.
+    const int b_ = row / c.Gu, g_ = row % c.Gu;
+    const int h0 = (c.Gu == 1) ? 0 : g_, nh = (c.Gu == 1) ? c.H : 1;
+    const int vpr = c.d * (int)sizeof(T) / 16;  // vectors per row
+    const int nvec = nh * vpr;
+    const uint4* ksrc = (const uint4*)(k_new + ((size_t)b_ * c.H + h0) * c.d);
+    const uint4* vsrc = (const uint4*)(v_new + ((size_t)b_ * c.H + h0) * c.d);
+    constexpr int VB = 4;
+    uint4 kpre[VB], vpre[VB];
+#pragma unroll
+    for (int r = 0; r < VB; r++) {
+        const int v = r * NT_ROW + tid;
+        if (v < nvec) { kpre[r] = ksrc[v]; vpre[r] = vsrc[v]; }
+    }
     __syncthreads();
 
     const bool leave = (w == 0) || (t >= w);
     int new_slot = -1;
+    // Free-slot stack: at most one slot is pushed and at most one is popped per step, so the
+    // step works on a local copy (count, the slot pushed in this step, the old top fetched
+    // ahead) and writes the stack back once.
+    int nfree = nfree0, pushed = -1;
+    const int old_top = nfree0 > 0 ? R.free_stack[nfree0 - 1] : -1;
+    auto pop_slot = [&]() -> int {
+        if (pushed >= 0) { const int r = pushed; pushed = -1; return r; }
+        nfree--;
+        return old_top;
+    };
     if (leave) {
         const int p = (w > 0) ? t - w : t;          // position joining the prefix (= prefix index T)
         const float z = (w > 0) ? R.win_u[p % w] : unew;
@@ -316,14 +342,13 @@ __global__ __launch_bounds__(NT_ROW) void decode_update_kernel(sparsek_decode_cf
         }
         // ---- (d) slots ----
         if (tid == 0) {
-            int nfree = *R.nfree;
             if (selected) {
                 int slot = zslot;
                 if (evict) {
                     R.slot_u[ev_slot] = -INFINITY;
-                    R.free_stack[nfree++] = ev_slot;
+                    pushed = ev_slot;
                 }
-                if (w == 0) slot = R.free_stack[--nfree];
+                if (w == 0) slot = pop_slot();
                 R.sel_u[e] = z;
                 R.sel_pos[e] = p;
                 R.sel_slot[e] = slot;
@@ -332,27 +357,25 @@ __global__ __launch_bounds__(NT_ROW) void decode_update_kernel(sparsek_decode_cf
                 if (w == 0) new_slot = slot;
             } else if (w > 0) {
                 R.slot_u[zslot] = -INFINITY;
-                R.free_stack[nfree++] = zslot;
+                pushed = zslot;
             }
-            *R.nfree = nfree;
             *R.nsel = nsel;
             *R.ncand = ncand;
             *R.tau_d = tau_new;
             *R.tau_f = (float)tau_new;
         }
-        __syncthreads();
     }
     // ---- (2) append the new token to the window ----
     if (tid == 0) {
         if (w > 0) {
-            int nfree = *R.nfree;
-            const int slot = R.free_stack[--nfree];
-            *R.nfree = nfree;
+            const int slot = pop_slot();
             R.win_u[t % w] = unew;
             R.win_slot[t % w] = slot;
             R.slot_u[slot] = INFINITY;
             new_slot = slot;
         }
+        if (pushed >= 0) R.free_stack[nfree++] = pushed;
+        *R.nfree = nfree;
         *R.new_slot = new_slot;
         *R.pos = t + 1;
         sh_i[2] = new_slot;
@@ -362,12 +385,18 @@ __global__ __launch_bounds__(NT_ROW) void decode_update_kernel(sparsek_decode_cf
     if (new_slot >= 0) {
         T* ks = (T*)(st + L.kslots);
         T* vs = (T*)(st + L.vslots);
-        const int b = row / c.Gu, g = row % c.Gu;
-        const int h0 = (c.Gu == 1) ? 0 : g, h1 = (c.Gu == 1) ? c.H : g + 1;
-        for (int h = h0; h < h1; h++) {
-            const size_t bh = (size_t)b * c.H + h;
-            copy_row(ks + (bh * L.NS + new_slot) * c.d, k_new + bh * c.d, c.d, tid, NT_ROW);
-            copy_row(vs + (bh * L.NS + new_slot) * c.d, v_new + bh * c.d, c.d, tid, NT_ROW);
+        auto dst = [&](T* slots, int v) -> uint4* {  // vector v of the rows -> its place in slot new_slot
+            const size_t bh = (size_t)b_ * c.H + h0 + v / vpr;
+            return (uint4*)(slots + (bh * L.NS + new_slot) * c.d) + v % vpr;
+        };
+#pragma unroll
+        for (int r = 0; r < VB; r++) {
+            const int v = r * NT_ROW + tid;
+            if (v < nvec) { *dst(ks, v) = kpre[r]; *dst(vs, v) = vpre[r]; }
+        }
+        for (int v = VB * NT_ROW + tid; v < nvec; v += NT_ROW) {  // more heads than one batch holds
+            *dst(ks, v) = ksrc[v];
+            *dst(vs, v) = vsrc[v];
         }
     }
 }
