@@ -154,8 +154,8 @@ __global__ __launch_bounds__(256) void mask_bwd_generic_kernel(
 // ---------------------------------------------------------------------------------
 template <int D, int MODE, bool LIST>
 __device__ __forceinline__ void bwd_tile(MfmaSmem<D, 16>& sm, float* colsum, int buf, int base, int col, int half,
-                                         int lane, int qi, bool qlive, int jbase, int w, float tau_q, float scale,
-                                         float lse2, float Di, const bf16x8 (&qreg)[D / 16],
+                                         int lane, int qi, bool qlive, int jbase, int w, float tau_q, float tau1_up,
+                                         float scale, float lse2, float Di, const bf16x8 (&qreg)[D / 16],
                                          const bf16x8 (&dreg)[D / 16], float& rowsum)
 {
     using S = MfmaSmem<D, 16>;
@@ -196,15 +196,16 @@ __device__ __forceinline__ void bwd_tile(MfmaSmem<D, 16>& sm, float* colsum, int
                 const int cst = 32 * mb + 8 * g4 + e;
                 bool valid = qlive && (qi <= Lj);
                 if (!LIST) valid = valid && (cst <= dqw);
-                // strictly fractional gate: tau < u < tau + 1, the upper test exact in fp64
+                // strictly fractional gate: tau < u < tau + 1.  tau1_up is tau + 1 rounded up to fp32:
+                // for an fp32 score, u < tau + 1 (exactly)  <=>  u < tau1_up
                 const float m = uj - tau_q;
-                const bool frac = (uj > tau_q) && ((double)uj < (double)tau_q + 1.0);
+                const bool frac = (uj > tau_q) && (uj < tau1_up);
                 const float mg = clip01(m);
                 const float qk = acc_s[mb][r], dov = acc_d[mb][r];
                 const float p = __builtin_amdgcn_exp2f(fmaf(qk * (MODE == 0 ? mg : 1.0f), c2, -lse2));
-                float g = p * dov;
-                if (MODE == 0) g = fmaf(scale * qk * p, fmaf(mg, dov, -Di), g);
-                g = (valid && frac) ? g : 0.0f;
+                float g = dov;
+                if (MODE == 0) g = fmaf(scale * qk, fmaf(mg, dov, -Di), dov);
+                g = (valid && frac) ? g * p : 0.0f;
                 gv[16 * mb + r] = g;
                 rowsum += g;
             }
@@ -263,7 +264,7 @@ __global__ __launch_bounds__(256, 2) void mask_bwd_mfma_kernel(
     int H, int Gu, int n, int k, int w, float scale, int nb, int BH)
 {
     __shared__ __align__(16) MfmaSmem<D, 16> sm;
-    __shared__ float colsum[KT];
+    __shared__ float colsum[2][KT];  // per tile parity: tile t adds into [t & 1] while [(t-1) & 1] is flushed
     constexpr int DS = D / 16;
     int bh, blk;
     {
@@ -304,6 +305,7 @@ __global__ __launch_bounds__(256, 2) void mask_bwd_mfma_kernel(
     const bool qlive = (qi < n) && (Tp >= k);  // prefixes with at most k entries carry no gradient
     const bool wave_live = (qa < n) && (qb - w >= k);
     const float tau_q = qlive ? tr[Tp] : 0.0f;
+    const float tau1_up = __double2float_ru((double)tau_q + 1.0);
     const float lse2 = lse[(size_t)bh * n + qrow] * 1.4426950408889634f;
     bf16x8 qreg[DS], dreg[DS];
     float dpart = 0.0f;
@@ -318,7 +320,7 @@ __global__ __launch_bounds__(256, 2) void mask_bwd_mfma_kernel(
     }
     const float Di = dpart + __shfl_xor(dpart, 32, 64);
     float rowsum = 0.0f;
-    if (tid < KT) colsum[tid] = 0.0f;
+    if (tid < 2 * KT) colsum[tid / KT][tid % KT] = 0.0f;
 
     for (int seg0 = 0; seg0 < nk_total; seg0 += SEG) {
         const int seg_n = min(SEG, nk_total - seg0);
@@ -346,31 +348,30 @@ __global__ __launch_bounds__(256, 2) void mask_bwd_mfma_kernel(
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();  // tile t landed; everybody is done with tile t-1 and its column sums
             if (t + 1 < ntiles) issue_tile_loads<D, 16>(sm, (t + 1) & 1, sm.jpos + (t + 1) * KT, kh, vh, wv, lane);
-            if (t > 0 && tid < KT) {  // flush the column sums of tile t-1
-                const float cs = colsum[tid];
+            if (t > 0 && tid < KT) {  // flush the column sums of tile t-1 (nobody adds to that buffer before the next barrier)
+                const float cs = colsum[(t - 1) & 1][tid];
                 const int e = (t - 1) * KT + tid;
                 if (cs != 0.0f && sm.jlast[e] >= 0) unsafeAtomicAdd(C + (size_t)row * n + sm.jpos[e], cs);
-                colsum[tid] = 0.0f;
+                colsum[(t - 1) & 1][tid] = 0.0f;
             }
-            __syncthreads();
             const int base = t * KT;
             const int E0 = seg0 + base;
             const bool is_list = E0 < nkl;
             const int jbase = is_list ? 0 : c0 + (E0 - nkl);
             if (!wave_live) continue;
             if (is_list)
-                bwd_tile<D, MODE, true>(sm, colsum, t & 1, base, col, half, lane, qi, qlive, jbase, w, tau_q, scale, lse2,
-                                        Di, qreg, dreg, rowsum);
+                bwd_tile<D, MODE, true>(sm, colsum[t & 1], t & 1, base, col, half, lane, qi, qlive, jbase, w, tau_q, tau1_up, scale,
+                                        lse2, Di, qreg, dreg, rowsum);
             else if (jbase <= qb - w)
-                bwd_tile<D, MODE, false>(sm, colsum, t & 1, base, col, half, lane, qi, qlive, jbase, w, tau_q, scale,
-                                         lse2, Di, qreg, dreg, rowsum);
+                bwd_tile<D, MODE, false>(sm, colsum[t & 1], t & 1, base, col, half, lane, qi, qlive, jbase, w, tau_q, tau1_up,
+                                         scale, lse2, Di, qreg, dreg, rowsum);
         }
         __syncthreads();
         if (tid < KT) {  // column sums of the segment's last tile
-            const float cs = colsum[tid];
+            const float cs = colsum[(ntiles - 1) & 1][tid];
             const int e = (ntiles - 1) * KT + tid;
             if (cs != 0.0f && sm.jlast[e] >= 0) unsafeAtomicAdd(C + (size_t)row * n + sm.jpos[e], cs);
-            colsum[tid] = 0.0f;
+            colsum[(ntiles - 1) & 1][tid] = 0.0f;
         }
     }
     const float rs = rowsum + __shfl_xor(rowsum, 32, 64);
