@@ -149,7 +149,8 @@ __global__ __launch_bounds__(256) void mask_bwd_generic_kernel(
 // already left the window (positions <= i0 + 127 - w).  Per tile two contractions over d,
 //   S^T  = K . Q^T    (recomputes the logits)      DV^T = V . dO^T   (dO_i . v_j),
 // then g_ij elementwise; row sums stay in the lane that owns the query, column sums are
-// reduced across the 32 query lanes with a halving butterfly (31 exchanges for 32 keys),
+// reduced across the 32 query lanes with a halving butterfly (31 exchanges for 32 keys, all
+// of them lane permutes in the vector ALU: permlane16_swap, DPP row rotate / mirror / quad),
 // combined over the 4 waves in LDS and added to C[] with one atomic per key and tile.
 // ---------------------------------------------------------------------------------
 template <int D, int MODE, bool LIST>
@@ -217,24 +218,26 @@ __device__ __forceinline__ void bwd_tile(MfmaSmem<D, 16>& sm, float* colsum, int
     const int c31 = lane & 31;
 #pragma unroll
     for (int r = 0; r < 16; r++) {
-        const bool up = c31 & 16;
-        const float send = up ? gv[r] : gv[r + 16];
-        const float keep = up ? gv[r + 16] : gv[r];
-        gv[r] = keep + __shfl_xor(send, 16, 64);
+        // lane ^ 16: v_permlane16_swap hands the even row the odd row's first operand and the odd
+        // row the even row's second operand, which is exactly "send one, keep the other"
+        const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(gv[r]), __float_as_uint(gv[r + 16]), false, false);
+        gv[r] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
     }
 #pragma unroll
     for (int r = 0; r < 8; r++) {
         const bool up = c31 & 8;
         const float send = up ? gv[r] : gv[r + 8];
         const float keep = up ? gv[r + 8] : gv[r];
-        gv[r] = keep + __shfl_xor(send, 8, 64);
+        gv[r] = keep + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(send), 0x128, 0xF, 0xF, true));  // row_ror:8 = lane ^ 8
     }
 #pragma unroll
     for (int r = 0; r < 4; r++) {
         const bool up = c31 & 4;
         const float send = up ? gv[r] : gv[r + 4];
         const float keep = up ? gv[r + 4] : gv[r];
-        gv[r] = keep + __shfl_xor(send, 4, 64);
+        int x = __builtin_amdgcn_update_dpp(0, __float_as_int(send), 0x141, 0xF, 0xF, true);  // half-row mirror: lane ^ 7
+        x = __builtin_amdgcn_update_dpp(0, x, 0x1B, 0xF, 0xF, true);                          // quad reverse: lane ^ 3
+        gv[r] = keep + __int_as_float(x);
     }
 #pragma unroll
     for (int r = 0; r < 2; r++) {
