@@ -441,35 +441,48 @@ __global__ void mask_bwd_ranges_kernel(const float* __restrict__ u, const float*
     }
 }
 
+// Exclusive prefix sum of one value per thread over the 1024 threads of a workgroup.
+template <typename T>
+__device__ __forceinline__ T block_exclusive_scan_1024(T x, T* wtot /* [16] LDS */)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    T inc = x;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const T y = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += y;
+    }
+    __syncthreads();  // wtot may still be read from a previous call
+    if (lane == 63) wtot[wv] = inc;
+    __syncthreads();
+    T before = inc - x;
+    for (int i = 0; i < wv; i++) before += wtot[i];
+    return before;
+}
+
 // Epilogue 2: one workgroup per row: |S*_T| = prefix sum of diff; G_T = sum_{T'<=T} A_T'/|S*_T'| (fp64).
 __global__ __launch_bounds__(1024) void mask_bwd_scan_kernel(const float* __restrict__ A,
                                                               const int32_t* __restrict__ diff, int n,
                                                               double* __restrict__ G)
 {
-    __shared__ int cpart[1024];
-    __shared__ double gpart[1024];
+    __shared__ int cw[16];
+    __shared__ double gw[16];
     const int row = blockIdx.x, tid = threadIdx.x;
     const float* Ar = A + (size_t)row * n;
     const int32_t* dr = diff + (size_t)row * (n + 1);
     double* Gr = G + (size_t)row * (n + 1);  // Gr[T+1] = sum_{T'<=T}; Gr[0] = 0
     const int per = (n + 1023) / 1024;
-    const int b = tid * per, e = min(b + per, n);
+    const int b = min(tid * per, n), e = min(b + per, n);
     int c = 0;
     for (int i = b; i < e; i++) c += dr[i];
-    cpart[tid] = c;
-    __syncthreads();
-    int cnt = 0;
-    for (int i = 0; i < tid; i++) cnt += cpart[i];
+    const int cnt0 = block_exclusive_scan_1024<int>(c, cw);
+    int cnt = cnt0;
     double g = 0.0;
-    const int cnt0 = cnt;
     for (int i = b; i < e; i++) {
         cnt += dr[i];
         if (cnt > 0) g += (double)Ar[i] / (double)cnt;
     }
-    gpart[tid] = g;
-    __syncthreads();
-    double run = 0.0;
-    for (int i = 0; i < tid; i++) run += gpart[i];
+    double run = block_exclusive_scan_1024<double>(g, gw);
     cnt = cnt0;
     if (tid == 0) Gr[0] = 0.0;
     for (int i = b; i < e; i++) {

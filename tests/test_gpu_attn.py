@@ -70,6 +70,10 @@ def test_config1_fp32(oracle, gate_mode):
     (1, 64, 4, 4, 1, "bf16"), (7, 64, 2, 3, 1, "bf16"), (300, 64, 16, 0, 1, "bf16"),
     (333, 128, 0, 40, 1, "bf16"), (700, 128, 50, 130, 2, "bf16"), (515, 64, 600, 5, 1, "bf16"),
     (450, 32, 20, 33, 2, "fp32"), (129, 128, 1, 1, 1, "fp32"),
+    # windows just wider than a query block (edge and diagonal tile runs meet), a top-k list that
+    # spans two metadata segments, and a long expiring tail of the list
+    (1000, 128, 70, 150, 1, "bf16"), (900, 64, 100, 192, 1, "bf16"), (2600, 128, 1500, 256, 1, "bf16"),
+    (1500, 64, 300, 64, 1, "bf16"),
 ])
 @pytest.mark.parametrize("gate_mode", [0, 1])
 def test_small_shapes(oracle, n, d, k, w, Gu, dtype, gate_mode):
