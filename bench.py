@@ -6,7 +6,7 @@ sparsek_mask (thresholds + lifetimes) followed by sparsek_attn_fwd, at the
 Llama-7B-shaped long-context configuration (B=1, H=32, n=32768, d=128, k=w=1024, bf16).
 Inputs are resident in HBM before the timed region.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-bwd] [--no-decode]
 """
 import argparse
 import json
@@ -140,6 +140,53 @@ def decode_leg(steps=256, warm=8):
     }
 
 
+def mask_bwd_leg(iters=20, warm=3):
+    """Config 3: B=4, H=16, n=8192, d=128, k=w=512, bf16: forward, then the SPARSEK mask backward
+    (du of L = sum(dO * O)).  Returns the extra JSON object."""
+    import torch
+
+    import paper_2406_16747_amd as spk
+
+    B, H, Gu, n, d, k, w = 4, 16, 1, 8192, 128, 512, 512
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1003)
+    div = math.sqrt(d)
+    q, kk, v = ((torch.randn(B, H, n, d, device="cuda", generator=g) / div).bfloat16() for _ in range(3))
+    dO = torch.randn(B, H, n, d, device="cuda", generator=g).bfloat16()
+    pos = torch.arange(n, device="cuda", dtype=torch.float32)
+    u = torch.randn(B, Gu, n, device="cuda", generator=g) + 0.5 * torch.sin(pos / 256.0)
+    tau, death = spk.sparsek_mask(u, k)
+    o, lse = spk.sparsek_attn_fwd(q, kk, v, u, tau, death, k, w, 0, 1.0)
+
+    def timed(fn):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    fwd_ms = timed(lambda: spk.sparsek_attn_fwd(q, kk, v, u, tau, death, k, w, 0, 1.0))
+    bwd_ms = timed(lambda: spk.sparsek_mask_bwd(q, kk, v, u, tau, death, o, lse, dO, k, w, 0, 1.0))
+    # pairs outside the window are the only ones with a soft gate: two contractions (Q.K^T and dO.V^T) over them
+    sel_pairs = attended_pairs(n, k, w) - (n * w - w * (w - 1) // 2)
+    flops = 4.0 * d * sel_pairs * B * H
+    fwd_flops = 4.0 * d * attended_pairs(n, k, w) * B * H
+    ach = flops / (bwd_ms * 1e-3) / 1e12
+    return {
+        "workload": "config 3: B=4 H=16 n=8192 d=128 k=w=512 bf16, Gu=1, gate_mode=0",
+        "attn_fwd_ms": fwd_ms, "attn_fwd_tflops": fwd_flops / (fwd_ms * 1e-3) / 1e12,
+        "mask_bwd_ms": bwd_ms,
+        "roofline": {"bound": "mfma", "kernel": "mask_bwd_mfma_kernel<128> + epilogue", "achieved": ach,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                     "algorithmic_flops": flops, "traffic": None},
+    }
+
+
 def read_traffic(name):
     """HBM bytes per launch of the dominant kernel, from the committed counter summary."""
     path = os.path.join(ROOT, "profiles", name)
@@ -160,6 +207,7 @@ def main():
     ap.add_argument("--gate-mode", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-bwd", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (to calibrate FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -240,9 +288,25 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, u)
-    if not args.no_decode:
-        del q, k, v, ws
+    # the same attention launch with the gate applied to the values only, and not at all
+    gm = {}
+    for mode in (0, 1, 2):
+        tau, death = spk.sparsek_mask(u, cfg["k"])
+        spk.sparsek_attn_fwd(q, k, v, u, tau, death, cfg["k"], cfg["w"], mode, 1.0, return_lse=True, ws=ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            spk.sparsek_attn_fwd(q, k, v, u, tau, death, cfg["k"], cfg["w"], mode, 1.0, return_lse=True, ws=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        gm[str(mode)] = e0.elapsed_time(e1) / 5
+    out["attn_ms_by_gate_mode"] = gm
+    del q, k, v, ws
+    torch.cuda.empty_cache()
+    if not args.no_bwd:
+        out["mask_bwd"] = mask_bwd_leg()
         torch.cuda.empty_cache()
+    if not args.no_decode:
         out["decode"] = decode_leg()
     print(json.dumps(out))
 
