@@ -140,7 +140,9 @@ __device__ inline void block_eval(BlockRed& red, const float* a, int na, const f
     minF = wm;
 }
 
-// Same fixed point as the prefill solver: tau <- (fsum + F - k)/(S - F) until (F, S) reproduce.
+// Same iteration as the prefill solver: tau <- (fsum + F - k)/(S - F), the root of the linear piece
+// through the current point (from whichever side of the root it lies on), until (F, S) reproduce;
+// a bracket of the root is kept and a step that leaves it is replaced by its midpoint.
 __device__ double block_solve_tau(BlockRed& red, const float* a, int na, const float* b, int nb, bool with_z,
                                   float z, int k, double start, int* status)
 {
@@ -152,34 +154,34 @@ __device__ double block_solve_tau(BlockRed& red, const float* a, int na, const f
         float minF;
         block_eval(red, a, na, b, nb, with_z, z, x, F, S, fsum, minF);
         if (F == pF && S == pS) return x;
+        pF = pS = -1;
         const double f = (double)F + fsum - (double)(S - F) * x;
+        double xn = 0.0;
+        bool have = false;
         if (f < (double)k) {
-            hi_b = x;
-            pF = pS = -1;
-            double mid = 0.5 * (lo_b + hi_b);
+            hi_b = x;  // x is right of the root
+            if (S > F) { xn = (fsum + (double)F - (double)k) / (double)(S - F); have = true; }
+        } else {
+            lo_b = x;
+            if (S == F) {  // flat to the right of x, f == F there
+                if (F == k) return (double)minF - 1.0;  // sup of the level set f == k
+                xn = (double)minF - 1.0;                 // F > k: the next breakpoint, still left of the root
+                if (xn < hi_b) { x = xn; continue; }
+            } else {
+                xn = (fsum + (double)F - (double)k) / (double)(S - F);
+                if (!(xn > x)) return x;  // f(x) == k up to rounding
+                have = true;
+            }
+        }
+        if (have && xn > lo_b && xn < hi_b) {
+            pF = F;
+            pS = S;
+            x = xn;
+        } else {
+            const double mid = 0.5 * (lo_b + hi_b);
             if (!(mid > lo_b && mid < hi_b)) return lo_b;
             x = mid;
-            continue;
         }
-        lo_b = x;
-        if (S == F) {
-            if (F == k) return (double)minF - 1.0;
-            x = (double)minF - 1.0;
-            pF = pS = -1;
-            continue;
-        }
-        const double xn = (fsum + (double)F - (double)k) / (double)(S - F);
-        if (!(xn > x)) return x;
-        if (xn >= hi_b) {
-            pF = pS = -1;
-            double mid = 0.5 * (lo_b + hi_b);
-            if (!(mid > lo_b && mid < hi_b)) return lo_b;
-            x = mid;
-            continue;
-        }
-        pF = F;
-        pS = S;
-        x = xn;
     }
     if (threadIdx.x == 0) atomicOr(status, 2);
     return x;
@@ -320,7 +322,10 @@ __global__ __launch_bounds__(NT_ROW) void decode_update_kernel(sparsek_decode_cf
         const int ev_slot = evict ? R.sel_slot[e] : -1;
         __syncthreads();
         if (k > 0 && len > k) {
-            if (tau_new > tau_old) ncand = block_prune(scan, R.cand_u, ncand, 0.0f, tau_new);
+            // Candidates that fell to or below tau do no harm (they count nowhere); they are only
+            // swept out when the set gets three quarters full, not at every rise of tau.
+            if ((tau_new > tau_old && ncand + 2 > (L.cap / 4) * 3) || ncand + 2 > L.cap)
+                ncand = block_prune(scan, R.cand_u, ncand, 0.0f, tau_new);
             if (tid == 0) {
                 float add[2];
                 int na = 0;
