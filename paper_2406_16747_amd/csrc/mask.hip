@@ -86,6 +86,7 @@ __global__ __launch_bounds__(NT_COARSE) void mask_coarse_kernel(const float* __r
                                                                  int k, int nsuper)
 {
     __shared__ double red[NT_COARSE / 64][NPROBE + 1];
+    __shared__ double ftot[NPROBE];
     __shared__ float bracket[2];
     __shared__ float part[1024];
     const int s = blockIdx.x, row = blockIdx.y;
@@ -156,13 +157,17 @@ __global__ __launch_bounds__(NT_COARSE) void mask_coarse_kernel(const float* __r
             if (lane == 0) red[wv][p] = t;
         }
         __syncthreads();
+        if (tid < NPROBE) {  // one thread per probe adds the 16 wave totals
+            double f = 0.0;
+            for (int i = 0; i < NT_COARSE / 64; i++) f += red[i][tid];
+            ftot[tid] = f;
+        }
+        __syncthreads();
         if (tid == 0) {
             float nlo = lo, nhi = hi;
             for (int p = 0; p < NPROBE; p++) {
-                double f = 0.0;
-                for (int i = 0; i < NT_COARSE / 64; i++) f += red[i][p];
                 float x = lo + step * (float)(p + 1);
-                if (f >= (double)k + 0.25) nlo = x;
+                if (ftot[p] >= (double)k + 0.25) nlo = x;
                 else { nhi = x; break; }
             }
             bracket[0] = nlo;
