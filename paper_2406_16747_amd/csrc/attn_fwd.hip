@@ -277,6 +277,12 @@ __device__ __forceinline__ void rescale_o(f32x16 (&acc_o)[D / 32], float alpha)
     }
 }
 
+// The reference point of the online softmax of one query: m (logit units, -inf before the
+// first visible key) and mc = m * scale * log2(e) (0 while m is -inf), what the exponent subtracts.
+struct SoftRef {
+    float m, mc;
+};
+
 // Softmax state of one 32-key half of a tile: this lane holds 16 of its logits (4 groups of 4
 // consecutive keys), their gates and lifetimes.
 struct HalfState {
@@ -306,7 +312,7 @@ __device__ __forceinline__ void load_meta(HalfState& h, const int32_t* jlast, co
 // value gate and bf16 packing of key group U - 4.
 template <int MODE, int KIND, int U>
 __device__ __forceinline__ void softmax_slice(HalfState& h, f32x16& sv, const int32_t* jlast, int half, int hf,
-                                              int qi, int dqh, int dqw, float tau_q, float c2, float& m_run)
+                                              int qi, int dqh, int dqw, float tau_q, float c2, SoftRef& ref)
 {
     using TT = TileTraits<MODE, KIND>;
     constexpr float LAZY_LOG2 = 8.0f;
@@ -339,14 +345,22 @@ __device__ __forceinline__ void softmax_slice(HalfState& h, f32x16& sv, const in
         }
         if (TT::GATED) h.G[g4] = make_float4(gg[0], gg[1], gg[2], gg[3]);
         if (U == 3) {
-            const unsigned tb = __float_as_uint(h.tmax);
-            const auto sw = __builtin_amdgcn_permlane32_swap(tb, tb, false, false);  // both halves, no LDS
-            const float tq = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-            const float m_new = (tq > m_run + LAZY_LOG2 / c2) ? tq : m_run;
-            const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
-            h.alpha = __builtin_amdgcn_exp2f((m_run - m_safe) * c2);
-            h.mc = m_safe * c2;
-            m_run = m_new;
+            // Almost always no lane of the wave has to move its reference point: one compare and
+            // a wave-uniform branch; the exchange with the partner lane, the new reference and
+            // the rescale factor are computed only in the rare other case.
+            const float limit = ref.m + LAZY_LOG2 / c2;
+            h.alpha = 1.0f;
+            if (__any(h.tmax > limit)) {
+                const unsigned tb = __float_as_uint(h.tmax);
+                const auto sw = __builtin_amdgcn_permlane32_swap(tb, tb, false, false);  // both halves, no LDS
+                const float tq = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+                const float m_new = (tq > limit) ? tq : ref.m;
+                const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+                h.alpha = __builtin_amdgcn_exp2f((ref.m - m_safe) * c2);
+                ref.mc = m_safe * c2;
+                ref.m = m_new;
+            }
+            h.mc = ref.mc;
         }
     } else {
         constexpr int g4 = U & 3;
@@ -364,11 +378,11 @@ __device__ __forceinline__ void softmax_slice(HalfState& h, f32x16& sv, const in
 
 template <int MODE, int KIND, int U0, int U1>
 __device__ __forceinline__ void softmax_slices(HalfState& h, f32x16& sv, const int32_t* jlast, int half, int hf,
-                                               int qi, int dqh, int dqw, float tau_q, float c2, float& m_run)
+                                               int qi, int dqh, int dqw, float tau_q, float c2, SoftRef& ref)
 {
     if constexpr (U0 < U1) {
-        softmax_slice<MODE, KIND, U0>(h, sv, jlast, half, hf, qi, dqh, dqw, tau_q, c2, m_run);
-        softmax_slices<MODE, KIND, U0 + 1, U1>(h, sv, jlast, half, hf, qi, dqh, dqw, tau_q, c2, m_run);
+        softmax_slice<MODE, KIND, U0>(h, sv, jlast, half, hf, qi, dqh, dqw, tau_q, c2, ref);
+        softmax_slices<MODE, KIND, U0 + 1, U1>(h, sv, jlast, half, hf, qi, dqh, dqw, tau_q, c2, ref);
     }
 }
 
@@ -389,7 +403,7 @@ template <int D, int MODE, int KIND>
 __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, int jbase, bool more,
                                           const uint16_t* kh, const uint16_t* vh, int wv, int col, int half,
                                           int lane, int qi, int w, float tau_q, float c2,
-                                          const bf16x8 (&qreg)[D / 16], f32x16 (&acc_o)[D / 32], float& m_run,
+                                          const bf16x8 (&qreg)[D / 16], f32x16 (&acc_o)[D / 32], SoftRef& ref,
                                           float& l_run)
 {
     using S = MfmaSmem<D>;
@@ -457,7 +471,7 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
         if (n < NX && more) tile_load_step<D, 64>(sm, buf ^ 1, rows, n, kh, vh, wv, lane);
         if (n >= NS) {
             constexpr int s = n >= NS ? n - NS : 0;
-            softmax_slices<MODE, KIND, US * s, US * (s + 1)>(A, sA, jlast, half, 0, qi, dqh, dqw, tau_q, c2, m_run);
+            softmax_slices<MODE, KIND, US * s, US * (s + 1)>(A, sA, jlast, half, 0, qi, dqh, dqw, tau_q, c2, ref);
             if (US * (s + 1) == 4) load_meta<MODE, KIND>(B, jlast, ju, 1, half);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -473,7 +487,7 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
         const bf16x8 cur = ring[n % DEPTH];
         acc_o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, A.pb[i / DB], acc_o[i % DB], 0, 0, 0);
         if (n + DEPTH < NSLOT) ring[n % DEPTH] = operand(n + DEPTH);
-        softmax_slices<MODE, KIND, UP * i, UP * (i + 1)>(B, sB, jlast, half, 1, qi, dqh, dqw, tau_q, c2, m_run);
+        softmax_slices<MODE, KIND, UP * i, UP * (i + 1)>(B, sB, jlast, half, 1, qi, dqh, dqw, tau_q, c2, ref);
         __builtin_amdgcn_sched_barrier(0);
     });
     asm volatile("" ::"v"(B.pb[0]), "v"(B.pb[1]), "v"(B.psum));
@@ -494,7 +508,7 @@ template <int D, int MODE, int KIND>
 __device__ __forceinline__ void run_tiles(MfmaSmem<D>& sm, int& t, int t_end, int ntiles, int jbase0,
                                           const uint16_t* kh, const uint16_t* vh, int wv, int col, int half,
                                           int lane, int qi, int w, float tau_q, float c2,
-                                          const bf16x8 (&qreg)[D / 16], f32x16 (&acc_o)[D / 32], float& m_run,
+                                          const bf16x8 (&qreg)[D / 16], f32x16 (&acc_o)[D / 32], SoftRef& ref,
                                           float& l_run)
 {
     for (; t < t_end; t++) {
@@ -504,7 +518,7 @@ __device__ __forceinline__ void run_tiles(MfmaSmem<D>& sm, int& t, int t_end, in
         __syncthreads();
         if (KIND != TILE_SKIP)
             tile_body<D, MODE, KIND>(sm, t & 1, t * KT, jbase0 + t * KT, t + 1 < ntiles, kh, vh, wv, col, half, lane,
-                                     qi, w, tau_q, c2, qreg, acc_o, m_run, l_run);
+                                     qi, w, tau_q, c2, qreg, acc_o, ref, l_run);
         else if (t + 1 < ntiles)
             issue_tile_loads<D, 64>(sm, (t + 1) & 1, sm.jpos + (t + 1) * KT, kh, vh, wv, lane);
     }
@@ -595,7 +609,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     for (int x = 0; x < DB; x++)
 #pragma unroll
         for (int r = 0; r < 16; r++) acc_o[x][r] = 0.0f;
-    float m_run = -INFINITY, l_run = 0.0f;
+    SoftRef ref{-INFINITY, 0.0f};
+    float l_run = 0.0f;
     const float c2 = scale * 1.4426950408889634f;
 
     for (int seg0 = 0; seg0 < nk_total; seg0 += SEG) {
@@ -625,7 +640,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
         int t = 0;
 #define SPK_RUN(KIND, bound)                                                                                   \
     run_tiles<D, MODE, KIND>(sm, t, min(ntiles, (bound) - T0), ntiles, jbase0, kh, vh, wv, col, half, lane, qi, \
-                             w, tau_q, c2, qreg, acc_o, m_run, l_run)
+                             w, tau_q, c2, qreg, acc_o, ref, l_run)
         SPK_RUN(TILE_LIST, b0);
         SPK_RUN(TILE_LIST_MASK, b1);
         if (narrow) SPK_RUN(TILE_CONT, b2);
@@ -651,7 +666,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
                 *(bf16x4*)(orow + 32 * x + 8 * g4 + 4 * half) = pk;
             }
         }
-        if (lse && half == 0) lse[(size_t)bh * n + qi] = (m_run * c2 + log2f(l_tot)) * 0.6931471805599453f;
+        if (lse && half == 0) lse[(size_t)bh * n + qi] = (ref.m * c2 + log2f(l_tot)) * 0.6931471805599453f;
     }
 }
 
