@@ -386,16 +386,6 @@ __device__ __forceinline__ void softmax_slices(HalfState& h, f32x16& sv, const i
     }
 }
 
-// Compile-time loop: f(integral_constant<int, I>) for I = 0 .. N-1.
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
-
 // One 64-key tile for one wave (see the schedule in the header comment).  The tile is a
 // sequence of MFMA slots (S_A, S_B, PV_A, PV_B); the LDS operand of slot n is requested DEPTH
 // slots earlier into a small register ring, so that no MFMA waits for a read it has just issued.

@@ -2,6 +2,7 @@
 // geometry, the LDS staging area and the direct-to-LDS gather of one K/V tile.
 #pragma once
 #include "common.hpp"
+#include <type_traits>
 
 namespace spk {
 
@@ -85,5 +86,14 @@ __device__ __forceinline__ void issue_tile_loads(MfmaSmem<D, VPAD>& sm, int buf,
     for (int x = 0; x < MfmaSmem<D, VPAD>::NL / 4; x++) tile_load_step<D, VPAD>(sm, buf, rows, x, kh, vh, wv, lane);
 }
 
+// Compile-time loop: f(integral_constant<int, I>) for I = 0 .. N-1.
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
 
 }  // namespace spk

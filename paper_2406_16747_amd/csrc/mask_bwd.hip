@@ -144,118 +144,185 @@ __global__ __launch_bounds__(256) void mask_bwd_generic_kernel(
 
 // ---------------------------------------------------------------------------------
 // MFMA main kernel (bf16, D = 64 or 128).  Same blocking as the forward: 128 queries x 4
-// waves, 64-key tiles gathered straight into LDS, but only over keys that can carry a soft
-// gate for some query of the block: the block's top-k list and the contiguous keys that have
-// already left the window (positions <= i0 + 127 - w).  Per tile two contractions over d,
+// waves, 64-key tiles gathered straight into LDS.  The candidates of a block are its top-k
+// list and the contiguous keys that have already left some query's window; before any
+// arithmetic they are compacted to the keys that can carry a strictly fractional gate for
+// some live query of the block:
+//     tau_lo < u_j < tau_hi + 1     (tau_lo, tau_hi: extremes of tau over the block's prefixes)
+//     j <= T_max  and  death_j > T_min   (in the prefix of, and still selected for, some query)
+// Saturated keys (gate 1 for every query of the block) and unselected window leavers drop out
+// here, which removes a large share of the tiles.  Per tile two contractions over d,
 //   S^T  = K . Q^T    (recomputes the logits)      DV^T = V . dO^T   (dO_i . v_j),
 // then g_ij elementwise; row sums stay in the lane that owns the query, column sums are
 // reduced across the 32 query lanes with a halving butterfly (31 exchanges for 32 keys, all
 // of them lane permutes in the vector ALU: permlane16_swap, DPP row rotate / mirror / quad),
 // combined over the 4 waves in LDS and added to C[] with one atomic per key and tile.
 // ---------------------------------------------------------------------------------
-template <int D, int MODE, bool LIST>
-__device__ __forceinline__ void bwd_tile(MfmaSmem<D, 16>& sm, float* colsum, int buf, int base, int col, int half,
-                                         int lane, int qi, bool qlive, int jbase, int w, float tau_q, float tau1_up,
-                                         float scale, float lse2, float Di, const bf16x8 (&qreg)[D / 16],
-                                         const bf16x8 (&dreg)[D / 16], float& rowsum)
+constexpr int RAW = 1024;  // candidates examined per segment (4 per thread); at most that many survive
+
+// g_ij for one (key, query) pair from the two dot products (see the header comment).
+// SURE: the key is selected and strictly fractional for every query of the block (decided once
+// per key when the candidates are compacted), so the per-pair tests are skipped.
+template <int MODE, bool SURE>
+__device__ __forceinline__ float bwd_pair(float qk, float dov, int Jj, int Lj, float uj, int Tp, float tau_q,
+                                          float tau1_up, float scale, float c2, float lse2, float Di)
 {
-    using S = MfmaSmem<D, 16>;
-    const unsigned char* kbuf = sm.kb[buf];
-    const unsigned char* vbuf = sm.vb[buf];
-    f32x16 acc_s[2], acc_d[2];
-#pragma unroll
-    for (int mb = 0; mb < 2; mb++) {
-        const int row = 32 * mb + col;
-        const int off = (row % S::NL) * S::GSK + (row / S::NL) * S::RB + 16 * half;
-#pragma unroll
-        for (int r = 0; r < 16; r++) { acc_s[mb][r] = 0.0f; acc_d[mb][r] = 0.0f; }
-#pragma unroll
-        for (int s = 0; s < D / 16; s++) {
-            const bf16x8 ka = *(const bf16x8*)(kbuf + off + 32 * s);
-            const bf16x8 va = *(const bf16x8*)(vbuf + off + 32 * s);
-            acc_s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], acc_s[mb], 0, 0, 0);
-            acc_d[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dreg[s], acc_d[mb], 0, 0, 0);
-            if ((s & 3) == 3) __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    const int dqh = qi - jbase - 4 * half;  // contiguous tiles: key number cst + 4*half sits dq - kk behind the query
-    const int dqw = dqh - w;                // outside the window  <=>  cst <= dqw
-    const float c2 = scale * 1.4426950408889634f;
-    float gv[32];
-#pragma unroll
-    for (int mb = 0; mb < 2; mb++) {
-#pragma unroll
-        for (int g4 = 0; g4 < 4; g4++) {
-            const int kb = 32 * mb + 8 * g4 + 4 * half;
-            const int4 L4 = *(const int4*)&sm.jlast[base + kb];
-            const float4 U4 = *(const float4*)&sm.ju[base + kb];
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-                const int r = 4 * g4 + e;
-                const int Lj = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
-                const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
-                const int cst = 32 * mb + 8 * g4 + e;
-                bool valid = qlive && (qi <= Lj);
-                if (!LIST) valid = valid && (cst <= dqw);
-                // strictly fractional gate: tau < u < tau + 1.  tau1_up is tau + 1 rounded up to fp32:
-                // for an fp32 score, u < tau + 1 (exactly)  <=>  u < tau1_up
-                const float m = uj - tau_q;
-                const bool frac = (uj > tau_q) && (uj < tau1_up);
-                const float mg = clip01(m);
-                const float qk = acc_s[mb][r], dov = acc_d[mb][r];
-                const float p = __builtin_amdgcn_exp2f(fmaf(qk * (MODE == 0 ? mg : 1.0f), c2, -lse2));
-                float g = dov;
-                if (MODE == 0) g = fmaf(scale * qk, fmaf(mg, dov, -Di), dov);
-                g = (valid && frac) ? g * p : 0.0f;
-                gv[16 * mb + r] = g;
-                rowsum += g;
-            }
-        }
-    }
-    // ---- column sums over the 32 queries of this half-wave: halving butterfly ----
-    // after the step with partner lane^b a lane keeps the values whose index has bit b equal to
-    // its own lane bit; at the end lane c (0..31) holds the total of value index c
+    const float mg = clip01(uj - tau_q);
+    const float p = __builtin_amdgcn_exp2f(fmaf(qk * (MODE == 0 ? mg : 1.0f), c2, -lse2));
+    float g = dov;
+    if (MODE == 0) g = fmaf(scale * qk, fmaf(mg, dov, -Di), dov);
+    if (SURE) return g * p;
+    // key j counts for prefix T  <=>  j <= T < death_j  <=>  (unsigned)(T - j) < death_j - j
+    // (T = -1 for a query without gradient, death_j - j = 0 for padding: never true)
+    const bool valid = (uint32_t)(Tp - Jj) < (uint32_t)Lj;
+    // strictly fractional gate: tau < u < tau + 1.  tau1_up is tau + 1 rounded up to fp32:
+    // for an fp32 score, u < tau + 1 (exactly)  <=>  u < tau1_up
+    const bool frac = (uj > tau_q) && (uj < tau1_up);
+    return (valid && frac) ? g * p : 0.0f;
+}
+
+// Column sums over the 32 queries of a half-wave for the 16 keys of one key half: halving
+// butterfly.  gv[r] is this lane's g for key 32 * mb + 8 * (r / 4) + 4 * half + r % 4.  After the
+// step with partner lane ^ b a lane keeps the values whose index has the matching bit equal to its
+// own lane bit; after four steps lanes c and c ^ 1 hold the two halves of the total of value
+// index c >> 1, which the even one adds to the tile's sums in LDS.
+__device__ __forceinline__ void bwd_column_sums(float (&gv)[16], float* colsum, int mb, int lane, int half)
+{
     const int c31 = lane & 31;
 #pragma unroll
-    for (int r = 0; r < 16; r++) {
+    for (int r = 0; r < 8; r++) {
         // lane ^ 16: v_permlane16_swap hands the even row the odd row's first operand and the odd
         // row the even row's second operand, which is exactly "send one, keep the other"
-        const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(gv[r]), __float_as_uint(gv[r + 16]), false, false);
+        const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(gv[r]), __float_as_uint(gv[r + 8]), false, false);
         gv[r] = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
     }
 #pragma unroll
-    for (int r = 0; r < 8; r++) {
+    for (int r = 0; r < 4; r++) {
         const bool up = c31 & 8;
-        const float send = up ? gv[r] : gv[r + 8];
-        const float keep = up ? gv[r + 8] : gv[r];
+        const float send = up ? gv[r] : gv[r + 4];
+        const float keep = up ? gv[r + 4] : gv[r];
         gv[r] = keep + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(send), 0x128, 0xF, 0xF, true));  // row_ror:8 = lane ^ 8
     }
 #pragma unroll
-    for (int r = 0; r < 4; r++) {
+    for (int r = 0; r < 2; r++) {
         const bool up = c31 & 4;
-        const float send = up ? gv[r] : gv[r + 4];
-        const float keep = up ? gv[r + 4] : gv[r];
+        const float send = up ? gv[r] : gv[r + 2];
+        const float keep = up ? gv[r + 2] : gv[r];
         int x = __builtin_amdgcn_update_dpp(0, __float_as_int(send), 0x141, 0xF, 0xF, true);  // half-row mirror: lane ^ 7
         x = __builtin_amdgcn_update_dpp(0, x, 0x1B, 0xF, 0xF, true);                          // quad reverse: lane ^ 3
         gv[r] = keep + __int_as_float(x);
     }
-#pragma unroll
-    for (int r = 0; r < 2; r++) {
-        const bool up = c31 & 2;
-        const float send = up ? gv[r] : gv[r + 2];
-        const float keep = up ? gv[r + 2] : gv[r];
-        gv[r] = keep + dpp_f32(send, 1);  // quad swap [2,3,0,1] = lane ^ 2
-    }
     {
-        const bool up = c31 & 1;
+        const bool up = c31 & 2;
         const float send = up ? gv[0] : gv[1];
         const float keep = up ? gv[1] : gv[0];
-        gv[0] = keep + dpp_f32(send, 0);  // quad swap [1,0,3,2] = lane ^ 1
+        gv[0] = keep + dpp_f32(send, 1);  // quad swap [2,3,0,1] = lane ^ 2
     }
-    // value index c31 = 16*mb + r  ->  key number 32*mb + 8*(r/4) + 4*half + r%4
-    const int mbk = c31 >> 4, rk = c31 & 15;
-    const int keyn = 32 * mbk + 8 * (rk >> 2) + 4 * half + (rk & 3);
-    if (gv[0] != 0.0f) atomicAdd(&colsum[keyn], gv[0]);
+    const float tot = gv[0] + dpp_f32(gv[0], 0);  // quad swap [1,0,3,2] = lane ^ 1
+    const int vi = c31 >> 1;
+    const int keyn = 32 * mb + 8 * (vi >> 2) + 4 * half + (vi & 3);
+    if (!(c31 & 1) && tot != 0.0f) atomicAdd(&colsum[keyn], tot);
+}
+
+// What a wave carries from one tile to the next: the second key half's dot products, whose
+// elementwise work runs under the next tile's first MFMAs.
+struct BwdCarry {
+    f32x16 s1, d1;
+};
+
+// One step of the software pipeline over the tiles of a segment (two key halves 0/1 per tile):
+//   phase A:  MFMAs of (tile t, half 0)   with the elementwise work of (tile t-1, half 1)
+//   phase B:  MFMAs of (tile t, half 1)   with the elementwise work of (tile t, half 0)
+// each followed by the column sums of the 32 keys just finished.
+// PREV = false on a segment's first tile, CUR = false for the drain step after its last one;
+// SP / SC: tile t-1 / tile t holds only keys that need no per-pair tests.
+// Every MFMA slot carries 32 / (D / 8) pairs of elementwise work; the LDS operand of a slot is
+// requested DEPTH slots earlier.
+template <int D, int MODE, bool PREV, bool CUR, bool SP, bool SC>
+__device__ __forceinline__ void bwd_step(MfmaSmem<D, 16>& sm, float* colsum_prev, float* colsum_cur, int buf, int base, int base_prev,
+                                         int col, int half, int lane, int Tp, float tau_q, float tau1_up,
+                                         float scale, float lse2, float Di, const bf16x8 (&qreg)[D / 16],
+                                         const bf16x8 (&dreg)[D / 16], BwdCarry& cy, float& rowsum)
+{
+    using S = MfmaSmem<D, 16>;
+    constexpr int DS = D / 16;
+    constexpr int NM = 2 * DS;     // MFMA slots per key half: K and V fragments alternate
+    constexpr int EPM = 16 / NM;   // pairs of elementwise work per slot
+    constexpr int DEPTH = 2;
+    static_assert(EPM * NM == 16 && (4 % EPM) == 0, "head dim 64 or 128");
+    const unsigned char* kbuf = sm.kb[buf];
+    const unsigned char* vbuf = sm.vb[buf];
+    const float c2 = scale * 1.4426950408889634f;
+    const f32x16 zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    int off[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; mb++) {
+        const int row = 32 * mb + col;
+        off[mb] = (row % S::NL) * S::GSK + (row / S::NL) * S::RB + 16 * half;
+    }
+    auto operand = [&](int n) -> bf16x8 {  // n = slot number over both phases, a constant after unrolling
+        const int mb = n / NM, s = (n % NM) / 2;
+        return *(const bf16x8*)(((n & 1) ? vbuf : kbuf) + off[mb] + 32 * s);
+    };
+    bf16x8 ring[DEPTH];
+    if (CUR) {
+#pragma unroll
+        for (int n = 0; n < DEPTH; n++) ring[n] = operand(n);
+    }
+    f32x16 s0, d0;
+    float gv[16];
+    int4 J4 = {0, 0, 0, 0}, L4 = {0, 0, 0, 0};
+    float4 U4;
+    auto pairs = [&](auto sure_c, int n, int mb, int mbase, const f32x16& as, const f32x16& ad, float* gout) {
+        constexpr bool SURE = decltype(sure_c)::value;
+#pragma unroll
+        for (int e0 = 0; e0 < EPM; e0++) {
+            const int r = n * EPM + e0, g4 = r / 4, e = r % 4;
+            if (e == 0) {
+                const int kb = mbase + 32 * mb + 8 * g4 + 4 * half;
+                if (!SURE) {
+                    J4 = *(const int4*)&sm.jpos[kb];
+                    L4 = *(const int4*)&sm.jlast[kb];
+                }
+                U4 = *(const float4*)&sm.ju[kb];
+            }
+            const int Jj = e == 0 ? J4.x : e == 1 ? J4.y : e == 2 ? J4.z : J4.w;
+            const int Lj = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
+            const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
+            const float g = bwd_pair<MODE, SURE>(as[r], ad[r], Jj, Lj, uj, Tp, tau_q, tau1_up, scale, c2, lse2, Di);
+            gout[r] = g;
+            rowsum += g;
+        }
+    };
+    // ---- phase A ----
+    static_for<0, NM>([&](auto nc) {
+        constexpr int n = decltype(nc)::value;
+        if (CUR) {
+            const bf16x8 cur = ring[n % DEPTH];
+            constexpr int s = n / 2;
+            if (n & 1) d0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, dreg[s], n < 2 ? zero : d0, 0, 0, 0);
+            else s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qreg[s], n < 2 ? zero : s0, 0, 0, 0);
+            ring[n % DEPTH] = operand(n + DEPTH);
+        }
+        if (PREV) pairs(std::bool_constant<SP>{}, n, 1, base_prev, cy.s1, cy.d1, gv);
+        __builtin_amdgcn_sched_barrier(0);
+    });
+    if (PREV) bwd_column_sums(gv, colsum_prev, 1, lane, half);
+    // ---- phase B ----
+    if (CUR) {
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, NM>([&](auto nc) {
+            constexpr int n = decltype(nc)::value;
+            const bf16x8 cur = ring[n % DEPTH];
+            constexpr int s = n / 2;
+            if (n & 1) cy.d1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, dreg[s], n < 2 ? zero : cy.d1, 0, 0, 0);
+            else cy.s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qreg[s], n < 2 ? zero : cy.s1, 0, 0, 0);
+            if (n + DEPTH < NM) ring[n % DEPTH] = operand(NM + n + DEPTH);
+            pairs(std::bool_constant<SC>{}, n, 0, base, s0, d0, gv);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        bwd_column_sums(gv, colsum_cur, 0, lane, half);
+    }
 }
 
 template <int D, int MODE>
@@ -266,8 +333,11 @@ __global__ __launch_bounds__(256, 2) void mask_bwd_mfma_kernel(
     const float* __restrict__ lse, const uint16_t* __restrict__ dO, float* __restrict__ A, float* __restrict__ C,
     int H, int Gu, int n, int k, int w, float scale, int nb, int BH)
 {
+    static_assert(RAW <= SEG, "survivors of one segment must fit the staged metadata");
     __shared__ __align__(16) MfmaSmem<D, 16> sm;
-    __shared__ float colsum[2][KT];  // per tile parity: tile t adds into [t & 1] while [(t-1) & 1] is flushed
+    __shared__ float colsum[3][KT];  // tile t adds into [t % 3] under tiles t and t+1; flushed under tile t+2
+    __shared__ __align__(16) int wcnt[2][RAW / 256][4];  // survivors per (class, round, wave) of the compaction
+    __shared__ float tred[2][4];
     constexpr int DS = D / 16;
     int bh, blk;
     {
@@ -286,6 +356,11 @@ __global__ __launch_bounds__(256, 2) void mask_bwd_mfma_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, col = lane & 31;
     const int i0 = blk * QB;
+    // prefixes of the block's queries that carry gradient: T = i - w with T >= k (prefixes with at
+    // most k entries have every gate at 1)
+    const int Tmax = min(n - 1, i0 + QB - 1) - w;
+    const int Tmin = max(i0 - w, k);
+    if (Tmax < Tmin) return;
     const uint16_t* kh = kk + (size_t)bh * n * D;
     const uint16_t* vh = v + (size_t)bh * n * D;
     const float* ur = u + (size_t)row * n;
@@ -293,89 +368,176 @@ __global__ __launch_bounds__(256, 2) void mask_bwd_mfma_kernel(
     const int32_t* dr = death + (size_t)row * n;
     const int32_t* list = lists + ((size_t)row * nb + blk) * (size_t)(k > 0 ? k : 1);
     const int cnt = counts[(size_t)row * nb + blk];
-    const int c0 = max(0, i0 - w + 1);
-    const int c1 = min(n - 1, i0 + QB - 1) - w;  // last contiguous key that is outside some query's window
-    const int nkl = (cnt + KT - 1) / KT * KT;
-    const int nkc = (c1 >= c0) ? (c1 - c0 + 1 + KT - 1) / KT * KT : 0;
-    const int nk_total = nkl + nkc;
-    if (nk_total == 0) return;
+    const int c0 = max(0, i0 - w + 1);           // contiguous candidates: c0 .. Tmax (outside some query's window)
+    const int ncont = max(0, Tmax - c0 + 1);
+    const int ncand = cnt + ncont;
 
     const int qa = i0 + 32 * wv;
     const int qb = min(qa + 31, n - 1);
     const int qi = qa + col;
     const int qrow = min(qi, n - 1);
-    const int Tp = qi - w;
-    const bool qlive = (qi < n) && (Tp >= k);  // prefixes with at most k entries carry no gradient
+    const bool qlive = (qi < n) && (qi - w >= k);
+    const int Tp = qlive ? qi - w : -1;
     const bool wave_live = (qa < n) && (qb - w >= k);
+    // Order of the prologue's loads: the small, cache-resident ones first (tau, lse, then the
+    // candidates with their dependent score / death reads), the cold query rows of Q, dO, O last.
+    // Loads complete in issue order, so this lets the candidates be classified and compacted, and
+    // the first tile's gather be issued, while the rows are still on their way from HBM.
     const float tau_q = qlive ? tr[Tp] : 0.0f;
-    const float tau1_up = __double2float_ru((double)tau_q + 1.0);
     const float lse2 = lse[(size_t)bh * n + qrow] * 1.4426950408889634f;
-    bf16x8 qreg[DS], dreg[DS];
-    float dpart = 0.0f;
+    // candidates of a segment: position, death - position, score (4 per thread)
+    int cj[RAW / 256], cl[RAW / 256];
+    float cu[RAW / 256];
+    auto load_candidates = [&](int r0) {
+        // Branch-free, and independent of the list length until the values are used: the list
+        // slots are read up to k (those beyond cnt hold stale numbers, clamped into the row and
+        // discarded afterwards), so that cnt, the list and then all score / death reads are two
+        // round trips in flight together rather than a chain of dependent ones.
+        int lv[RAW / 256];
+#pragma unroll
+        for (int x = 0; x < RAW / 256; x++) lv[x] = list[min(r0 + 256 * x + tid, k - 1)];
+#pragma unroll
+        for (int x = 0; x < RAW / 256; x++) {
+            const int E = r0 + 256 * x + tid;
+            cj[x] = E < cnt ? min(max(lv[x], 0), n - 1) : min(c0 + max(E - cnt, 0), n - 1);
+        }
+#pragma unroll
+        for (int x = 0; x < RAW / 256; x++) {
+            cu[x] = ur[cj[x]];
+            cl[x] = dr[cj[x]];  // death; turned into death - position when the candidate is classified
+        }
+    };
+    load_candidates(0);
+    __builtin_amdgcn_sched_barrier(0);
+    bf16x8 qreg[DS], dreg[DS], oreg[DS];
 #pragma unroll
     for (int s = 0; s < DS; s++) {
         const size_t off = ((size_t)bh * n + qrow) * D + 16 * s + 8 * half;
         qreg[s] = *(const bf16x8*)(q + off);
         dreg[s] = *(const bf16x8*)(dO + off);
-        const bf16x8 ov = *(const bf16x8*)(o + off);
-#pragma unroll
-        for (int e = 0; e < 8; e++) dpart += (float)dreg[s][e] * (float)ov[e];
+        oreg[s] = *(const bf16x8*)(o + off);
     }
-    const float Di = dpart + __shfl_xor(dpart, 32, 64);
+    __builtin_amdgcn_sched_barrier(0);
+    const float tau1_up = __double2float_ru((double)tau_q + 1.0);
+    {
+        const float lo = wave_min_f32(qlive ? tau_q : INFINITY);
+        const float hi = wave_max_f32(qlive ? tau_q : -INFINITY);
+        if (lane == 0) { tred[0][wv] = lo; tred[1][wv] = hi; }
+    }
+    float Di = 0.0f;       // dO_i . o_i, formed when the rows have arrived (first segment with tiles)
+    bool have_di = false;
     float rowsum = 0.0f;
-    if (tid < 2 * KT) colsum[tid / KT][tid % KT] = 0.0f;
+    BwdCarry cy;
+    if (tid < 3 * KT) colsum[tid / KT][tid % KT] = 0.0f;
+    const bool all_live = (i0 - w >= k) && (i0 + QB <= n);  // every lane of the block owns a query with gradient
+    __syncthreads();
+    const float tau_lo = fminf(fminf(tred[0][0], tred[0][1]), fminf(tred[0][2], tred[0][3]));
+    const float tau_hi = fmaxf(fmaxf(tred[1][0], tred[1][1]), fmaxf(tred[1][2], tred[1][3]));
+    const float tau_hi1 = __double2float_ru((double)tau_hi + 1.0);
+    const float tau_lo1 = __double2float_ru((double)tau_lo + 1.0);
 
-    for (int seg0 = 0; seg0 < nk_total; seg0 += SEG) {
-        const int seg_n = min(SEG, nk_total - seg0);
-        __syncthreads();
-        for (int e = tid; e < seg_n; e += 256) {
-            const int E = seg0 + e;
-            int j = 0;
-            bool real;
-            if (E < nkl) {
-                real = E < cnt;
-                if (real) j = list[E];
-            } else {
-                j = c0 + (E - nkl);
-                real = j <= c1;
-                if (!real) j = 0;
+    for (int r0 = 0; r0 < ncand; r0 += RAW) {
+        // ---- examine RAW candidates, keep those that can matter to this block ----
+        // class 1 ("sure"): selected and strictly fractional for every query of the block -- placed
+        // first, their tiles skip the per-pair tests; class 2: the other survivors
+        int pre[RAW / 256], cls[RAW / 256];
+        if (r0 > 0) load_candidates(r0);
+#pragma unroll
+        for (int x = 0; x < RAW / 256; x++) {
+            const int j = cj[x], life = cl[x] - cj[x];  // death_j = j + life
+            const float uj = cu[x];
+            cl[x] = life;
+            const bool keep = (r0 + 256 * x + tid < ncand) && (uj > tau_lo) && (uj < tau_hi1) && (j <= Tmax) && (j + life > Tmin) && (life > 0);
+            const bool sure = keep && all_live && (uj > tau_hi) && (uj < tau_lo1) && (j <= Tmin) && (j + life > Tmax);
+            cls[x] = sure ? 1 : keep ? 2 : 0;
+            const unsigned long long b1 = __ballot(cls[x] == 1), b2 = __ballot(cls[x] == 2);
+            const unsigned long long bal = cls[x] == 1 ? b1 : b2;
+            pre[x] = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0));
+            if (lane == 0) {
+                wcnt[0][x][wv] = __popcll(b1);
+                wcnt[1][x][wv] = __popcll(b2);
             }
-            sm.jpos[e] = j;
-            sm.jlast[e] = real ? (w - 1 + dr[j]) : -1;
-            sm.ju[e] = real ? ur[j] : 0.0f;
+        }
+        __syncthreads();  // counts visible; the previous segment's tiles and column sums are done with
+        int n1 = 0, n2 = 0, at1[RAW / 256], at2[RAW / 256];
+#pragma unroll
+        for (int x = 0; x < RAW / 256; x++) {
+            const int4 c1 = *(const int4*)wcnt[0][x];
+            const int4 c2 = *(const int4*)wcnt[1][x];
+            at1[x] = n1 + (wv > 0 ? c1.x : 0) + (wv > 1 ? c1.y : 0) + (wv > 2 ? c1.z : 0);
+            at2[x] = n2 + (wv > 0 ? c2.x : 0) + (wv > 1 ? c2.y : 0) + (wv > 2 ? c2.z : 0);
+            n1 += c1.x + c1.y + c1.z + c1.w;
+            n2 += c2.x + c2.y + c2.z + c2.w;
+        }
+        const int kept = n1 + n2;
+#pragma unroll
+        for (int x = 0; x < RAW / 256; x++) {
+            if (cls[x] != 0) {
+                const int idx = (cls[x] == 1 ? at1[x] : n1 + at2[x]) + pre[x];
+                sm.jpos[idx] = cj[x];
+                sm.jlast[idx] = cl[x];
+                sm.ju[idx] = cu[x];
+            }
+        }
+        const int nsure = n1 / KT;  // tiles made of class-1 keys only
+        const int seg_n = (kept + KT - 1) / KT * KT;
+        if (kept + tid < seg_n) {  // padding of the last tile: row 0, never valid
+            sm.jpos[kept + tid] = 0;
+            sm.jlast[kept + tid] = 0;
+            sm.ju[kept + tid] = 0.0f;
         }
         __syncthreads();
         const int ntiles = seg_n / KT;
+        if (ntiles == 0) continue;
         issue_tile_loads<D, 16>(sm, 0, sm.jpos, kh, vh, wv, lane);
+        if (!have_di) {
+            float dpart = 0.0f;
+#pragma unroll
+            for (int s = 0; s < DS; s++)
+#pragma unroll
+                for (int e = 0; e < 8; e++) dpart += (float)dreg[s][e] * (float)oreg[s][e];
+            Di = dpart + __shfl_xor(dpart, 32, 64);
+            have_di = true;
+        }
+        // column sums of tile t are formed under tiles t and t+1, in colsum[t % 3], and handed to
+        // C[] under tile t+2; tile t+3 is the next one to use that buffer
+        auto flush = [&](int tt, int c) {
+            const float cs = colsum[tt % 3][c];
+            if (cs != 0.0f) unsafeAtomicAdd(C + (size_t)row * n + sm.jpos[tt * KT + c], cs);
+            colsum[tt % 3][c] = 0.0f;
+        };
         for (int t = 0; t < ntiles; t++) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();  // tile t landed; everybody is done with tile t-1 and its column sums
+            __syncthreads();  // tile t landed; everybody is done with the MFMAs of tile t-1 and the sums of tile t-2
             if (t + 1 < ntiles) issue_tile_loads<D, 16>(sm, (t + 1) & 1, sm.jpos + (t + 1) * KT, kh, vh, wv, lane);
-            if (t > 0 && tid < KT) {  // flush the column sums of tile t-1 (nobody adds to that buffer before the next barrier)
-                const float cs = colsum[(t - 1) & 1][tid];
-                const int e = (t - 1) * KT + tid;
-                if (cs != 0.0f && sm.jlast[e] >= 0) unsafeAtomicAdd(C + (size_t)row * n + sm.jpos[e], cs);
-                colsum[(t - 1) & 1][tid] = 0.0f;
-            }
-            const int base = t * KT;
-            const int E0 = seg0 + base;
-            const bool is_list = E0 < nkl;
-            const int jbase = is_list ? 0 : c0 + (E0 - nkl);
+            if (t >= 2 && tid < KT) flush(t - 2, tid);
             if (!wave_live) continue;
-            if (is_list)
-                bwd_tile<D, MODE, true>(sm, colsum[t & 1], t & 1, base, col, half, lane, qi, qlive, jbase, w, tau_q, tau1_up, scale,
-                                        lse2, Di, qreg, dreg, rowsum);
-            else if (jbase <= qb - w)
-                bwd_tile<D, MODE, false>(sm, colsum[t & 1], t & 1, base, col, half, lane, qi, qlive, jbase, w, tau_q, tau1_up,
-                                         scale, lse2, Di, qreg, dreg, rowsum);
+#define SPK_STEP(PREV, CUR, SP, SC)                                                                              \
+    bwd_step<D, MODE, PREV, CUR, SP, SC>(sm, colsum[(t + 2) % 3], colsum[t % 3], t & 1, t * KT, (t - 1) * KT, col, half, lane, Tp, \
+                                         tau_q, tau1_up, scale, lse2, Di, qreg, dreg, cy, rowsum)
+            if (t == 0) {
+                if (nsure > 0) SPK_STEP(false, true, false, true);
+                else SPK_STEP(false, true, false, false);
+            } else if (t < nsure) {
+                SPK_STEP(true, true, true, true);
+            } else if (t == nsure) {
+                SPK_STEP(true, true, true, false);
+            } else {
+                SPK_STEP(true, true, false, false);
+            }
         }
+        if (wave_live) {
+            const int t = ntiles;
+            if (nsure == ntiles) SPK_STEP(true, false, true, false);
+            else SPK_STEP(true, false, false, false);
+        }
+#undef SPK_STEP
         __syncthreads();
-        if (tid < KT) {  // column sums of the segment's last tile
-            const float cs = colsum[(ntiles - 1) & 1][tid];
-            const int e = (ntiles - 1) * KT + tid;
-            if (cs != 0.0f && sm.jlast[e] >= 0) unsafeAtomicAdd(C + (size_t)row * n + sm.jpos[e], cs);
-            colsum[(ntiles - 1) & 1][tid] = 0.0f;
+        if (tid < 2 * KT) {  // column sums of the segment's last two tiles
+            const int tt = ntiles - 2 + tid / KT;
+            if (tt >= 0) flush(tt, tid % KT);
         }
+        __syncthreads();  // ... before the next segment overwrites the positions
     }
     const float rs = rowsum + __shfl_xor(rowsum, 32, 64);
     if (qlive && half == 0 && rs != 0.0f) unsafeAtomicAdd(A + (size_t)row * n + Tp, rs);

@@ -43,6 +43,8 @@ def run_bwd(oracle, inp, gate_mode, heads_all=True):
 @pytest.mark.parametrize("n,d,k,w,Gu,dtype", [
     (200, 64, 12, 9, 1, "bf16"), (333, 128, 20, 0, 1, "bf16"), (520, 64, 30, 40, 2, "bf16"),
     (300, 32, 10, 7, 2, "fp32"), (90, 64, 100, 5, 1, "bf16"), (150, 64, 0, 5, 1, "bf16"), (64, 64, 3, 70, 1, "bf16"),
+    # more than 1024 candidates per query block: the compaction runs over several segments
+    (2500, 64, 1150, 40, 1, "bf16"), (1700, 128, 300, 1000, 1, "bf16"),
 ])
 @pytest.mark.parametrize("gate_mode", [0, 1, 2])
 def test_mask_bwd_small(oracle, n, d, k, w, Gu, dtype, gate_mode):
