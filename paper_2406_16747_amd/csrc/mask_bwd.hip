@@ -24,7 +24,7 @@ void launch_block_lists(const sparsek_cfg& c, const int32_t* death, int32_t* lis
 size_t block_lists_bytes(const sparsek_cfg& c, size_t* counts_offset);
 
 struct BwdWs {
-    size_t lists, counts, A, C, diff, G, total;
+    size_t lists, counts, A, C, diff, G, ab, total;
 };
 static BwdWs bwd_ws(const sparsek_cfg& c)
 {
@@ -39,6 +39,7 @@ static BwdWs bwd_ws(const sparsek_cfg& c)
     W.C = off; off += align_up(rows * c.n * 4, 256);
     W.diff = off; off += align_up(rows * (c.n + 1) * 4, 256);
     W.G = off; off += align_up(rows * (size_t)(c.n + 1) * 8, 256);
+    W.ab = off; off += align_up(rows * (size_t)c.n * 8, 256);
     W.total = off;
     return W;
 }
@@ -562,50 +563,74 @@ static void launch_bwd_mfma(const sparsek_cfg& c, const void* q, const void* k, 
 
 // ---------------------------------------------------------------------------------
 // Epilogue 1: per key j the range [a_j, b_j] of prefixes T with j in S*_T; difference array
-// of |S*_T|.  tau is non-decreasing for T >= k-1, so both ends come from binary searches.
+// of |S*_T|.  tau is non-decreasing for T >= k-1, so both ends come from binary searches:
+//   b_j = last  T in [max(j,k), n-1] with tau_T < u_j
+//   a_j = first T in [max(j,k), n-1] with u_j < tau_T + 1      (compared in fp64, exact)
+// A workgroup holds every stride-th threshold of its row in LDS (all of them up to n = 8192);
+// a search runs on those samples first and finishes in global memory inside one stride.
 // ---------------------------------------------------------------------------------
-__device__ __forceinline__ void frac_range(const float* tr, float uj, int j, int n, int k, int& a, int& b)
+constexpr int RS_MAX = 8192;  // sampled thresholds per row held in LDS
+
+// first T in [lo, n) with pred(tau_T), n if none; pred is monotone (false ... false true ... true)
+template <typename Pred>
+__device__ __forceinline__ int first_true(const float* __restrict__ tr, const float* ts, int lo, int n, int stride,
+                                          int ns, Pred pred)
 {
-    const int lo = max(j, k);  // shorter prefixes have every gate at 1: S* empty
-    a = 1;
-    b = 0;
-    if (lo > n - 1) return;
-    // b = last T in [lo, n-1] with tau_T < u_j
-    int x = lo, y = n;  // first T with !(tau_T < u_j)
+    const int ifirst = (lo + stride - 1) / stride;  // samples sit at T = i * stride
+    int x = ifirst, y = ns;
     while (x < y) {
-        int m = (x + y) >> 1;
-        if (tr[m] < uj) x = m + 1;
-        else y = m;
-    }
-    b = x - 1;
-    // a = first T in [lo, n-1] with u_j < tau_T + 1 (fp64 compare)
-    x = lo;
-    y = n;
-    while (x < y) {
-        int m = (x + y) >> 1;
-        if ((double)uj < (double)tr[m] + 1.0) y = m;
+        const int m = (x + y) >> 1;
+        if (pred(ts[m])) y = m;
         else x = m + 1;
     }
-    a = x;
-}
-
-__global__ void mask_bwd_ranges_kernel(const float* __restrict__ u, const float* __restrict__ tau, int n, int k,
-                                       int32_t* __restrict__ diff)
-{
-    const int row = blockIdx.y;
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= n) return;
-    int a, b;
-    frac_range(tau + (size_t)row * n, u[(size_t)row * n + j], j, n, k, a, b);
-    if (a <= b) {
-        atomicAdd(diff + (size_t)row * (n + 1) + a, 1);
-        atomicAdd(diff + (size_t)row * (n + 1) + b + 1, -1);
+    int t0 = (x == ifirst) ? lo : (x - 1) * stride + 1;  // samples before x are false
+    int t1 = (x < ns) ? x * stride : n;                  // sample x is true
+    while (t0 < t1) {
+        const int m = (t0 + t1) >> 1;
+        if (pred(tr[m])) t1 = m;
+        else t0 = m + 1;
     }
+    return t0;
 }
 
-// Exclusive prefix sum of one value per thread over the 1024 threads of a workgroup.
+__global__ __launch_bounds__(1024) void mask_bwd_ranges_kernel(const float* __restrict__ u,
+                                                                const float* __restrict__ tau, int n, int k,
+                                                                int32_t* __restrict__ diff, int2* __restrict__ ab)
+{
+    __shared__ float ts[RS_MAX];
+    const int row = blockIdx.y;
+    const float* tr = tau + (size_t)row * n;
+    const int stride = (n + RS_MAX - 1) / RS_MAX;
+    const int ns = (n + stride - 1) / stride;
+    for (int i = threadIdx.x; i < ns; i += blockDim.x) ts[i] = tr[(size_t)i * stride];
+    __syncthreads();
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    int a = 1, b = 0;
+    if (j < n) {
+        const float uj = u[(size_t)row * n + j];
+        const int lo = max(j, k);  // shorter prefixes have every gate at 1: S* empty
+        if (lo <= n - 1) {
+            b = first_true(tr, ts, lo, n, stride, ns, [&](float t) { return !(t < uj); }) - 1;
+            a = first_true(tr, ts, lo, n, stride, ns, [&](float t) { return (double)uj < (double)t + 1.0; });
+        }
+        ab[(size_t)row * n + j] = make_int2(a, b);
+    }
+    // difference array: +1 at a_j, -1 at b_j + 1.  Two addresses collect most of the updates and
+    // would serialise them: every key j <= k that is fractional from the start has a_j = k (one
+    // add per wave instead), and every key still fractional at the end has b_j + 1 = n, an entry
+    // the prefix sum never reads (dropped).
+    const bool any = a <= b;
+    int32_t* dr = diff + (size_t)row * (n + 1);
+    const unsigned long long at_k = __ballot(any && a == k);
+    if (any && a != k) atomicAdd(dr + a, 1);
+    if (at_k != 0 && (threadIdx.x & 63) == 0) atomicAdd(dr + k, (int)__popcll(at_k));
+    if (any && b + 1 < n) atomicAdd(dr + b + 1, -1);
+}
+
+// Exclusive prefix sum of one value per thread over the 1024 threads of a workgroup; `total`
+// receives the sum over all of them.
 template <typename T>
-__device__ __forceinline__ T block_exclusive_scan_1024(T x, T* wtot /* [16] LDS */)
+__device__ __forceinline__ T block_exclusive_scan_1024(T x, T* wtot /* [16] LDS */, T& total)
 {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     T inc = x;
@@ -618,14 +643,27 @@ __device__ __forceinline__ T block_exclusive_scan_1024(T x, T* wtot /* [16] LDS 
     if (lane == 63) wtot[wv] = inc;
     __syncthreads();
     T before = inc - x;
-    for (int i = 0; i < wv; i++) before += wtot[i];
+    total = T(0);
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+        const T w = wtot[i];
+        if (i < wv) before += w;
+        total += w;
+    }
     return before;
 }
 
-// Epilogue 2: one workgroup per row: |S*_T| = prefix sum of diff; G_T = sum_{T'<=T} A_T'/|S*_T'| (fp64).
-__global__ __launch_bounds__(1024) void mask_bwd_scan_kernel(const float* __restrict__ A,
-                                                              const int32_t* __restrict__ diff, int n,
-                                                              double* __restrict__ G)
+// Epilogue 2, one workgroup per row:
+//   |S*_T| = prefix sum of diff;   G_T = sum_{T' <= T} A_T' / |S*_T'|  (fp64);
+//   du_j = C_j - (G[b_j] - G[a_j - 1]).
+// The prefix sums go over chunks of 8192 prefixes, 8 consecutive ones per thread, read in one
+// batch; G is written to global memory and read back by the same workgroup after a barrier.
+constexpr int SCAN_PER = 8;
+__global__ __launch_bounds__(1024) void mask_bwd_scan_final_kernel(const float* __restrict__ A,
+                                                                    const int32_t* __restrict__ diff,
+                                                                    const float* __restrict__ C,
+                                                                    const int2* __restrict__ ab, int n,
+                                                                    double* __restrict__ G, float* __restrict__ du)
 {
     __shared__ int cw[16];
     __shared__ double gw[16];
@@ -633,43 +671,68 @@ __global__ __launch_bounds__(1024) void mask_bwd_scan_kernel(const float* __rest
     const float* Ar = A + (size_t)row * n;
     const int32_t* dr = diff + (size_t)row * (n + 1);
     double* Gr = G + (size_t)row * (n + 1);  // Gr[T+1] = sum_{T'<=T}; Gr[0] = 0
-    const int per = (n + 1023) / 1024;
-    const int b = min(tid * per, n), e = min(b + per, n);
-    int c = 0;
-    for (int i = b; i < e; i++) c += dr[i];
-    const int cnt0 = block_exclusive_scan_1024<int>(c, cw);
-    int cnt = cnt0;
-    double g = 0.0;
-    for (int i = b; i < e; i++) {
-        cnt += dr[i];
-        if (cnt > 0) g += (double)Ar[i] / (double)cnt;
-    }
-    double run = block_exclusive_scan_1024<double>(g, gw);
-    cnt = cnt0;
     if (tid == 0) Gr[0] = 0.0;
-    for (int i = b; i < e; i++) {
-        cnt += dr[i];
-        if (cnt > 0) run += (double)Ar[i] / (double)cnt;
-        Gr[i + 1] = run;
+    int cnt_carry = 0;
+    double g_carry = 0.0;
+    for (int base = 0; base < n; base += 1024 * SCAN_PER) {
+        const int i0 = base + SCAN_PER * tid;
+        int dv[SCAN_PER];
+        float av[SCAN_PER];
+#pragma unroll
+        for (int e = 0; e < SCAN_PER; e++) {
+            const int i = min(i0 + e, n - 1);
+            dv[e] = dr[i];
+            av[e] = Ar[i];
+        }
+        int csum = 0;
+#pragma unroll
+        for (int e = 0; e < SCAN_PER; e++) {
+            if (i0 + e >= n) dv[e] = 0;
+            csum += dv[e];
+        }
+        int ctot;
+        int cnt = cnt_carry + block_exclusive_scan_1024<int>(csum, cw, ctot);
+        double gl[SCAN_PER], gsum = 0.0;
+#pragma unroll
+        for (int e = 0; e < SCAN_PER; e++) {
+            cnt += dv[e];
+            if (cnt > 0 && i0 + e < n) gsum += (double)av[e] / (double)cnt;
+            gl[e] = gsum;
+        }
+        double gtot;
+        const double run = g_carry + block_exclusive_scan_1024<double>(gsum, gw, gtot);
+#pragma unroll
+        for (int e = 0; e < SCAN_PER; e++)
+            if (i0 + e < n) Gr[i0 + e + 1] = run + gl[e];
+        cnt_carry += ctot;
+        g_carry += gtot;
     }
-}
-
-// Epilogue 3: du_j = C_j - (G[b_j] - G[a_j - 1]).
-__global__ void mask_bwd_final_kernel(const float* __restrict__ u, const float* __restrict__ tau,
-                                      const float* __restrict__ C, const double* __restrict__ G, int n, int k,
-                                      float* __restrict__ du)
-{
-    const int row = blockIdx.y;
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= n) return;
-    int a, b;
-    frac_range(tau + (size_t)row * n, u[(size_t)row * n + j], j, n, k, a, b);
-    double r = (double)C[(size_t)row * n + j];
-    if (a <= b) {
-        const double* Gr = G + (size_t)row * (n + 1);
-        r -= Gr[b + 1] - Gr[a];
+    __syncthreads();  // the row's G is complete and visible to the whole workgroup
+    const int2* abr = ab + (size_t)row * n;
+    const float* Cr = C + (size_t)row * n;
+    float* dur = du + (size_t)row * n;
+    for (int base = 0; base < n; base += 1024 * SCAN_PER) {
+        int2 r[SCAN_PER];
+        float cv[SCAN_PER];
+        double hi[SCAN_PER], lo[SCAN_PER];
+#pragma unroll
+        for (int e = 0; e < SCAN_PER; e++) {
+            const int j = min(base + 1024 * e + tid, n - 1);
+            r[e] = abr[j];
+            cv[e] = Cr[j];
+        }
+#pragma unroll
+        for (int e = 0; e < SCAN_PER; e++) {
+            const bool any = r[e].x <= r[e].y;
+            hi[e] = Gr[any ? r[e].y + 1 : 0];
+            lo[e] = Gr[any ? r[e].x : 0];
+        }
+#pragma unroll
+        for (int e = 0; e < SCAN_PER; e++) {
+            const int j = base + 1024 * e + tid;
+            if (j < n) dur[j] = (float)((double)cv[e] - (hi[e] - lo[e]));
+        }
     }
-    du[(size_t)row * n + j] = (float)r;
 }
 
 int launch_mask_bwd(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
@@ -686,30 +749,31 @@ int launch_mask_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
     float* C = (float*)(base + W.C);
     int32_t* diff = (int32_t*)(base + W.diff);
     double* G = (double*)(base + W.G);
+    int2* ab = (int2*)(base + W.ab);
+    if (c.gate_mode == 2 || c.k <= 0 || c.n <= c.w) {
+        // no soft gate anywhere: the gradient is identically zero
+        hipLaunchKernelGGL(zero_kernel, dim3(512), dim3(256), 0, st, (uint32_t*)du, (size_t)rows * c.n);
+        return launch_status();
+    }
     // A, C, diff are contiguous: clear them with one fill kernel (safe under graph capture)
     hipLaunchKernelGGL(zero_kernel, dim3(512), dim3(256), 0, st, (uint32_t*)(base + W.A), (W.G - W.A) / 4);
-    if (c.gate_mode != 2 && c.k > 0 && c.n > c.w) {
-        launch_block_lists(c, death, lists, counts, st);
-        dim3 grid(nb, c.B * c.H);
-        if (c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull) {
-            if (c.d == 64) launch_bwd_mfma<64>(c, q, k, v, u, tau, death, lists, counts, o, lse, dO, A, C, nb, st);
-            else launch_bwd_mfma<128>(c, q, k, v, u, tau, death, lists, counts, o, lse, dO, A, C, nb, st);
-        } else if (c.dtype == SPARSEK_F32)
-            hipLaunchKernelGGL(mask_bwd_generic_kernel<float>, grid, dim3(256), 0, st, (const float*)q,
-                               (const float*)k, (const float*)v, u, tau, death, lists, counts, (const float*)o, lse,
-                               (const float*)dO, A, C, c.H, c.Gu, c.n, c.d, c.k, c.w, c.gate_mode, c.softmax_scale,
-                               nb);
-        else
-            hipLaunchKernelGGL(mask_bwd_generic_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)q,
-                               (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts,
-                               (const uint16_t*)o, lse, (const uint16_t*)dO, A, C, c.H, c.Gu, c.n, c.d, c.k, c.w,
-                               c.gate_mode, c.softmax_scale, nb);
-        hipLaunchKernelGGL(mask_bwd_ranges_kernel, dim3((c.n + 255) / 256, rows), dim3(256), 0, st, u, tau, c.n,
-                           c.k, diff);
-    }
-    hipLaunchKernelGGL(mask_bwd_scan_kernel, dim3(rows), dim3(1024), 0, st, A, diff, c.n, G);
-    hipLaunchKernelGGL(mask_bwd_final_kernel, dim3((c.n + 255) / 256, rows), dim3(256), 0, st, u, tau, C, G, c.n,
-                       c.k, du);
+    hipLaunchKernelGGL(mask_bwd_ranges_kernel, dim3((c.n + 1023) / 1024, rows), dim3(1024), 0, st, u, tau, c.n, c.k,
+                       diff, ab);
+    launch_block_lists(c, death, lists, counts, st);
+    dim3 grid(nb, c.B * c.H);
+    if (c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull) {
+        if (c.d == 64) launch_bwd_mfma<64>(c, q, k, v, u, tau, death, lists, counts, o, lse, dO, A, C, nb, st);
+        else launch_bwd_mfma<128>(c, q, k, v, u, tau, death, lists, counts, o, lse, dO, A, C, nb, st);
+    } else if (c.dtype == SPARSEK_F32)
+        hipLaunchKernelGGL(mask_bwd_generic_kernel<float>, grid, dim3(256), 0, st, (const float*)q, (const float*)k,
+                           (const float*)v, u, tau, death, lists, counts, (const float*)o, lse, (const float*)dO, A, C,
+                           c.H, c.Gu, c.n, c.d, c.k, c.w, c.gate_mode, c.softmax_scale, nb);
+    else
+        hipLaunchKernelGGL(mask_bwd_generic_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)q,
+                           (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, (const uint16_t*)o,
+                           lse, (const uint16_t*)dO, A, C, c.H, c.Gu, c.n, c.d, c.k, c.w, c.gate_mode,
+                           c.softmax_scale, nb);
+    hipLaunchKernelGGL(mask_bwd_scan_final_kernel, dim3(rows), dim3(1024), 0, st, A, diff, C, ab, c.n, G, du);
     return launch_status();
 }
 
