@@ -172,6 +172,10 @@ def mask_bwd_leg(iters=20, warm=3):
 
     fwd_ms = timed(lambda: spk.sparsek_attn_fwd(q, kk, v, u, tau, death, k, w, 0, 1.0))
     bwd_ms = timed(lambda: spk.sparsek_mask_bwd(q, kk, v, u, tau, death, o, lse, dO, k, w, 0, 1.0))
+    # straight-through variant (gate_mode 3): forward without the gate multiplications, gradient at m = 1
+    o_st, lse_st = spk.sparsek_attn_fwd(q, kk, v, u, tau, death, k, w, 3, 1.0)
+    st_fwd_ms = timed(lambda: spk.sparsek_attn_fwd(q, kk, v, u, tau, death, k, w, 3, 1.0))
+    st_bwd_ms = timed(lambda: spk.sparsek_mask_bwd(q, kk, v, u, tau, death, o_st, lse_st, dO, k, w, 3, 1.0))
     # pairs outside the window are the only ones with a soft gate: two contractions (Q.K^T and dO.V^T) over them
     sel_pairs = attended_pairs(n, k, w) - (n * w - w * (w - 1) // 2)
     flops = 4.0 * d * sel_pairs * B * H
@@ -181,6 +185,8 @@ def mask_bwd_leg(iters=20, warm=3):
         "workload": "config 3: B=4 H=16 n=8192 d=128 k=w=512 bf16, Gu=1, gate_mode=0",
         "attn_fwd_ms": fwd_ms, "attn_fwd_tflops": fwd_flops / (fwd_ms * 1e-3) / 1e12,
         "mask_bwd_ms": bwd_ms,
+        "straight_through": {"gate_mode": 3, "attn_fwd_ms": st_fwd_ms, "mask_bwd_ms": st_bwd_ms,
+                             "mask_bwd_tflops": flops / (st_bwd_ms * 1e-3) / 1e12},
         "roofline": {"bound": "mfma", "kernel": "mask_bwd_mfma_kernel<128> + epilogue", "achieved": ach,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
                      "algorithmic_flops": flops, "traffic": None},

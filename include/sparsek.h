@@ -47,12 +47,15 @@ extern "C" {
 /* gate_mode: where the soft gate m_ij multiplies.
  *   0  keys and values: s_ij = scale * m_ij * q_i.k_j, o_i = sum_j p_ij m_ij v_j  (soft selection matrix on K and V)
  *   1  values only:     s_ij = scale * q_i.k_j,        o_i = sum_j p_ij m_ij v_j  (Sec. 3.5)
- *   2  nowhere:         plain attention over the selected + window keys (straight-through forward, Sec. 3.4)
+ *   2  nowhere:         plain attention over the selected + window keys (hard selection; no gradient to the scores)
+ *   3  straight-through estimator of Sec. 3.4 for mode 0: the forward is that of mode 2 (the
+ *      multiplication by the gates is skipped), and sparsek_mask_bwd sends dL/dm_ij, taken at m_ij = 1,
+ *      through the soft selection matrix.
  * p_i = softmax_j(s_ij) over the attended keys; the denominator is never gated. */
 typedef struct {
     int32_t B, H, Gu, n, d, k, w;
     int32_t dtype;     /* SPARSEK_F32 or SPARSEK_BF16: storage type of q, k, v, o, dO */
-    int32_t gate_mode; /* 0, 1 or 2 */
+    int32_t gate_mode; /* 0, 1, 2 or 3 */
     float softmax_scale; /* finite and > 0 */
 } sparsek_cfg;
 
@@ -94,7 +97,8 @@ int sparsek_attn_fwd(const sparsek_cfg *cfg, const void *q, const void *k, const
  * soft gates (the hard top-k set is a constant): for every prefix T, with g_j = dL/dm_{T+w,j},
  * du += s * (g - mean_{S*} g), S* = { j <= T : tau_T < u_j < tau_T + 1 }.  Heads of one score
  * group add into the same row.  o and lse are the outputs of sparsek_attn_fwd on the same inputs.
- * gate_mode 2 has no gate in the forward, so du = 0. */
+ * gate_mode 2 has no gate in the forward, so du = 0; gate_mode 3 takes g_j at gate 1 (o, lse from the
+ * mode 3 forward) and applies the same Jacobian. */
 size_t sparsek_mask_bwd_workspace_bytes(const sparsek_cfg *cfg);
 int sparsek_mask_bwd(const sparsek_cfg *cfg, const void *q, const void *k, const void *v,
                      const float *u, const float *tau, const int32_t *death, const void *o,

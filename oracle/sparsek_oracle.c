@@ -20,7 +20,10 @@
  *  - k == 0: mask identically zero, tau = max(prefix);
  *  - gate_mode 0 gates keys and values (Eq. for selected attention with the soft
  *    selection matrix), 1 gates values only (Sec. 3.5 hard-K/soft-V), 2 gates nothing
- *    (forward of the straight-through estimator, Sec. 3.4);
+ *    (hard selection, no gradient to the scores), 3 is the straight-through estimator
+ *    of Sec. 3.4 applied to mode 0: the forward uses the hard selection (all gates 1,
+ *    identical to mode 2) and the gradient flows through the soft selection matrix,
+ *    dL/dm_ij being taken at m_ij = 1;
  *  - the softmax denominator is never re-weighted by the gate.
  */
 #include <math.h>
@@ -210,7 +213,7 @@ static void attend_list(const float *qi, const float *K, const float *V, int d, 
         double dot = 0.0;
         for (int c = 0; c < d; c++) dot += (double)qi[c] * (double)kj[c];
         if (qk_out) qk_out[a] = dot;
-        double gk = (gate_mode == 0) ? gates[a] : 1.0;
+        double gk = (gate_mode == 0) ? gates[a] : 1.0; /* modes 1, 2, 3: keys not gated */
         s[a] = scale * gk * dot;
         if (s[a] > smax) smax = s[a];
     }
@@ -220,7 +223,7 @@ static void attend_list(const float *qi, const float *K, const float *V, int d, 
     for (int a = 0; a < nk; a++) {
         double p = exp(s[a] - smax) / den;
         if (p_out) p_out[a] = p;
-        double gv = (gate_mode == 2) ? 1.0 : gates[a];
+        double gv = (gate_mode == 2 || gate_mode == 3) ? 1.0 : gates[a];
         const float *vj = V + (size_t)keys[a] * d;
         for (int c = 0; c < d; c++) o[c] += p * gv * (double)vj[c];
     }
@@ -370,6 +373,8 @@ int orc_mask_bwd_head(const float *q, const float *K, const float *V, const floa
             double gj = p[a] * dov; /* through the value gate */
             if (gate_mode == 0)     /* through the key gate: ds = p (m dO.v - D) */
                 gj += scale * qk[a] * p[a] * (gates[a] * dov - D);
+            if (gate_mode == 3)     /* straight-through: the same derivative taken at m = 1 */
+                gj += scale * qk[a] * p[a] * (dov - D);
             g[j] = gj;
         }
         int cntS = 0;

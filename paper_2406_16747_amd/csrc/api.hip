@@ -20,7 +20,7 @@ int check_attn(const sparsek_cfg* c)
 {
     int rc = check_common(c);
     if (rc) return rc;
-    if (c->gate_mode < 0 || c->gate_mode > 2) return SPARSEK_ERR_INVALID_ARG;
+    if (c->gate_mode < 0 || c->gate_mode > 3) return SPARSEK_ERR_INVALID_ARG;
     if (c->dtype != SPARSEK_F32 && c->dtype != SPARSEK_BF16) return SPARSEK_ERR_UNSUPPORTED;
     if (c->d < 4 || c->d > 128 || (c->d % 4) != 0) return SPARSEK_ERR_UNSUPPORTED;
     if (!(c->softmax_scale > 0.0f) || !(c->softmax_scale < INFINITY)) return SPARSEK_ERR_INVALID_ARG;
@@ -84,7 +84,9 @@ int sparsek_attn_fwd(const sparsek_cfg* cfg, const void* q, const void* k, const
     if (rc) return rc;
     if (!q || !k || !v || !u || !tau || !death || !o || !ws) return SPARSEK_ERR_INVALID_ARG;
     if (ws_bytes < attn_fwd_ws_bytes(*cfg)) return SPARSEK_ERR_WORKSPACE;
-    return launch_attn_fwd(*cfg, q, k, v, u, tau, death, o, lse, ws, (hipStream_t)stream);
+    sparsek_cfg c = *cfg;
+    if (c.gate_mode == 3) c.gate_mode = 2;  // the straight-through forward is the hard-selection forward
+    return launch_attn_fwd(c, q, k, v, u, tau, death, o, lse, ws, (hipStream_t)stream);
 }
 
 }  // extern "C"
@@ -107,7 +109,7 @@ int check_decode(const sparsek_decode_cfg* c)
     if (c->B < 1 || c->H < 1 || c->k < 0 || c->w < 0 || c->k + c->w < 1 || c->cand_cap < 0)
         return SPARSEK_ERR_INVALID_ARG;
     if (c->Gu != 1 && c->Gu != c->H) return SPARSEK_ERR_INVALID_ARG;
-    if (c->gate_mode < 0 || c->gate_mode > 2) return SPARSEK_ERR_INVALID_ARG;
+    if (c->gate_mode < 0 || c->gate_mode > 3) return SPARSEK_ERR_INVALID_ARG;
     if (c->dtype != SPARSEK_F32 && c->dtype != SPARSEK_BF16) return SPARSEK_ERR_UNSUPPORTED;
     if (c->d < 8 || c->d > 128 || (c->d % 8) != 0) return SPARSEK_ERR_UNSUPPORTED;
     if ((long long)c->B * c->H > (1 << 24)) return SPARSEK_ERR_UNSUPPORTED;
@@ -170,7 +172,9 @@ int sparsek_decode_step(const sparsek_decode_cfg* cfg, void* state, const void* 
     int rc = check_decode(cfg);
     if (rc) return rc;
     if (!state || !q_new || !k_new || !v_new || !u_new || !o) return SPARSEK_ERR_INVALID_ARG;
-    return launch_decode_step(*cfg, state, q_new, k_new, v_new, u_new, o, (hipStream_t)stream);
+    sparsek_decode_cfg c = *cfg;
+    if (c.gate_mode == 3) c.gate_mode = 2;  // straight-through: the forward skips the gates
+    return launch_decode_step(c, state, q_new, k_new, v_new, u_new, o, (hipStream_t)stream);
 }
 
 int sparsek_decode_status(const sparsek_decode_cfg* cfg, const void* state, int32_t* host_flags, void* stream)

@@ -9,8 +9,11 @@
 // contiguous range of T, found by binary search; |S*_T| and the second term then come from
 // difference arrays and prefix sums in an O(n log n) epilogue -- nothing of size n*k is stored.
 //
-//   g_ij = p_ij (dO_i.v_j)                                          value gate (modes 0, 1)
-//        + scale (q_i.k_j) p_ij (m_ij dO_i.v_j - dO_i.o_i)          key gate   (mode 0)
+//   g_ij = p_ij (dO_i.v_j)                                          value gate (modes 0, 1, 3)
+//        + scale (q_i.k_j) p_ij (m_ij dO_i.v_j - dO_i.o_i)          key gate   (mode 0; mode 3 with m_ij = 1)
+// Mode 3 is the straight-through estimator (Sec. 3.4): p, o, lse come from the forward without
+// gates and g_ij is the mode 0 derivative taken at m_ij = 1; membership in S* still follows the
+// soft mask.
 #include "common.hpp"
 #include "attn_tiles.hpp"
 
@@ -132,6 +135,7 @@ __global__ __launch_bounds__(256) void mask_bwd_generic_kernel(
                     const float p = __expf(s - lse_i);
                     gf = p * dov;
                     if (gate_mode == 0) gf += scale * qk * p * (m * dov - Di);
+                    if (gate_mode == 3) gf += scale * qk * p * (dov - Di);
                 }
             }
             if (gf != 0.0f) unsafeAtomicAdd(C + (size_t)row * n + j, gf);
@@ -172,6 +176,7 @@ __device__ __forceinline__ float bwd_pair(float qk, float dov, int Jj, int Lj, f
     const float p = __builtin_amdgcn_exp2f(fmaf(qk * (MODE == 0 ? mg : 1.0f), c2, -lse2));
     float g = dov;
     if (MODE == 0) g = fmaf(scale * qk, fmaf(mg, dov, -Di), dov);
+    if (MODE == 3) g = fmaf(scale * qk, dov - Di, dov);
     if (SURE) return g * p;
     // key j counts for prefix T  <=>  j <= T < death_j  <=>  (unsigned)(T - j) < death_j - j
     // (T = -1 for a query without gradient, death_j - j = 0 for padding: never true)
@@ -557,6 +562,7 @@ static void launch_bwd_mfma(const sparsek_cfg& c, const void* q, const void* k, 
                        (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, (const uint16_t*)o, \
                        lse, (const uint16_t*)dO, A, C, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH)
     if (c.gate_mode == 0) SPK_LAUNCH_B(0);
+    else if (c.gate_mode == 3) SPK_LAUNCH_B(3);
     else SPK_LAUNCH_B(1);
 #undef SPK_LAUNCH_B
 }

@@ -57,7 +57,7 @@ def run_case(oracle, inp, gate_mode=0, scale=None, heads=None, rows=None, qk_boo
     return worst
 
 
-@pytest.mark.parametrize("gate_mode", [0, 1, 2])
+@pytest.mark.parametrize("gate_mode", [0, 1, 2, 3])
 def test_config1_fp32(oracle, gate_mode):
     require_gpu()
     say("attn config 1 mode", gate_mode)

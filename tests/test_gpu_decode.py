@@ -80,7 +80,7 @@ def test_decode_from_empty(oracle, k, w, Gu):
 
 
 @pytest.mark.parametrize("dtype,d", [("bf16", 128), ("fp32", 32), ("bf16", 64)])
-@pytest.mark.parametrize("gate_mode", [0, 1, 2])
+@pytest.mark.parametrize("gate_mode", [0, 1, 2, 3])
 def test_decode_after_prefill(oracle, dtype, d, gate_mode):
     require_gpu()
     say("decode after prefill", dtype, d, gate_mode)

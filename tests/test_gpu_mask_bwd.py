@@ -46,7 +46,7 @@ def run_bwd(oracle, inp, gate_mode, heads_all=True):
     # more than 1024 candidates per query block: the compaction runs over several segments
     (2500, 64, 1150, 40, 1, "bf16"), (1700, 128, 300, 1000, 1, "bf16"),
 ])
-@pytest.mark.parametrize("gate_mode", [0, 1, 2])
+@pytest.mark.parametrize("gate_mode", [0, 1, 2, 3])
 def test_mask_bwd_small(oracle, n, d, k, w, Gu, dtype, gate_mode):
     require_gpu()
     say("mask_bwd", n, d, k, w, Gu, dtype, gate_mode)
@@ -63,3 +63,24 @@ def test_mask_bwd_config3_recipe_reduced(oracle):
     say("mask_bwd config 3 reduced")
     inp = synth.make(3, with_dO=True, B=1, H=2, n=2048, k=128, w=128)
     run_bwd(oracle, inp, 0)
+
+
+def test_straight_through_forward_is_the_ungated_forward_and_has_a_gradient(oracle):
+    """gate_mode 3 (straight-through, Sec. 3.4): the forward skips the gates (bit-identical to
+    mode 2); the score gradient is that of the oracle's mode 3, and differs from the soft one."""
+    require_gpu()
+    say("mask_bwd straight-through")
+    inp = synth.make(3, with_dO=True, B=1, H=2, n=1536, k=96, w=64, seed=5)
+    B, H, n, d, k, w = (inp[x] for x in ("B", "H", "n", "d", "k", "w"))
+    u = dev(inp["u"])
+    Q, K, V, dO = (dev(inp[x], True) for x in ("Q", "K", "V", "dO"))
+    tau, death = spk.sparsek_mask(u, k)
+    o2, lse2 = spk.sparsek_attn_fwd(Q, K, V, u, tau, death, k, w, 2, 1.0)
+    o3, lse3 = spk.sparsek_attn_fwd(Q, K, V, u, tau, death, k, w, 3, 1.0)
+    assert torch.equal(o2, o3) and torch.equal(lse2, lse3)
+    rel3, scale3 = run_bwd(oracle, inp, 3)
+    assert scale3 > 0
+    du3 = host(spk.sparsek_mask_bwd(Q, K, V, u, tau, death, o3, lse3, dO, k, w, 3, 1.0))
+    o0, lse0 = spk.sparsek_attn_fwd(Q, K, V, u, tau, death, k, w, 0, 1.0)
+    du0 = host(spk.sparsek_mask_bwd(Q, K, V, u, tau, death, o0, lse0, dO, k, w, 0, 1.0))
+    assert np.abs(du3 - du0).max() > 1e-2 * scale3

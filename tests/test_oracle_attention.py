@@ -229,6 +229,87 @@ def test_du_matches_finite_differences(oracle, mode):
     assert abs(du.sum()) < 1e-10  # rows of the SPARSEK Jacobian sum to zero (App. A.3)
 
 
+def _forward_with_gate_matrix(q, k, v, G, att, scale):
+    """o_i = sum_j softmax_j(scale * G_ij q_i.k_j) G_ij v_j over the attended pairs att[i, j]
+    (gates on keys and values), written out with numpy for one head."""
+    n = q.shape[0]
+    o = np.zeros((n, q.shape[1]))
+    for i in range(n):
+        js = np.nonzero(att[i])[0]
+        s = scale * G[i, js] * (k[js].astype(np.float64) @ q[i].astype(np.float64))
+        p = np.exp(s - s.max())
+        p /= p.sum()
+        o[i] = (p * G[i, js]) @ v[js].astype(np.float64)
+    return o
+
+
+def test_straight_through_du_matches_finite_differences(oracle):
+    """Mode 3 (Sec. 3.4): the gates that enter the forward are m_soft(u) - m_soft(u0) + m_hard, so
+    the forward value at u0 is the hard selection and the gradient is dL/dm at m = 1 pushed
+    through the soft mask.  Checked against central differences of that forward, written out
+    here with an explicit gate matrix (which is first checked against the oracle's own forward
+    for soft gates, mode 0, and for unit gates, mode 2 = mode 3)."""
+    rng = np.random.default_rng(15)
+    n, d, kk, w = 28, 4, 5, 3
+    h = 2.0 ** -10
+    scale = 0.6
+    q = rng.standard_normal((1, 1, n, d)).astype(np.float32)
+    k = rng.standard_normal((1, 1, n, d)).astype(np.float32)
+    v = rng.standard_normal((1, 1, n, d)).astype(np.float32)
+    dO = rng.standard_normal((1, 1, n, d)).astype(np.float32)
+    u0 = grid_scores(rng, n).reshape(1, 1, n) + np.float32(1.0 / 64)
+    tau0, dth = oracle.mask_all(u0, kk)
+
+    def attended_and_soft_gates(uu):
+        t, dd = oracle.mask_all(uu, kk)
+        np.testing.assert_array_equal(dd, dth)  # the hard set is held fixed
+        att = np.zeros((n, n), bool)
+        M = np.ones((n, n))
+        for i in range(n):
+            for j in range(i + 1):
+                if i - j < w:
+                    att[i, j] = True  # window, gate 1
+                elif j <= i - w < dth[0, 0, j]:
+                    att[i, j] = True
+                    M[i, j] = min(max(float(uu[0, 0, j]) - t[0, 0, i - w], 0.0), 1.0)
+        return att, M
+
+    att, M0 = attended_and_soft_gates(u0)
+    o_soft, _, _ = oracle.attn_fwd(q, k, v, u0, tau0, dth, kk, w, 0, scale, nthreads=1)
+    np.testing.assert_allclose(_forward_with_gate_matrix(q[0, 0], k[0, 0], v[0, 0], M0, att, scale), o_soft[0, 0],
+                               rtol=1e-12, atol=1e-12)
+    for mode in (2, 3):
+        o_hard, _, _ = oracle.attn_fwd(q, k, v, u0, tau0, dth, kk, w, mode, scale, nthreads=1)
+        np.testing.assert_allclose(_forward_with_gate_matrix(q[0, 0], k[0, 0], v[0, 0], np.ones((n, n)), att, scale),
+                                   o_hard[0, 0], rtol=1e-12, atol=1e-12)
+
+    def loss(uu):
+        _, M = attended_and_soft_gates(uu)
+        o = _forward_with_gate_matrix(q[0, 0], k[0, 0], v[0, 0], M - M0 + 1.0, att, scale)
+        return float((o * dO[0, 0]).sum())
+
+    du, _ = oracle.mask_bwd(q, k, v, u0, tau0, dth, dO, kk, w, 3, scale, nthreads=1)
+    du_soft, _ = oracle.mask_bwd(q, k, v, u0, tau0, dth, dO, kk, w, 0, scale, nthreads=1)
+    assert np.abs(du - du_soft).max() > 1e-3  # not the soft-gate gradient
+    checked = 0
+    for j in range(n):
+        near = False
+        for T in range(j, n):
+            for edge in (tau0[0, 0, T], tau0[0, 0, T] + 1):
+                if np.any(np.abs(u0[0, 0, : T + 1].astype(np.float64) - edge) < 4 * h):
+                    near = True
+        if near:
+            continue
+        up, um = u0.copy(), u0.copy()
+        up[0, 0, j] += np.float32(h)
+        um[0, 0, j] -= np.float32(h)
+        fd = (loss(up) - loss(um)) / (2 * h)
+        assert du[0, 0, j] == pytest.approx(fd, abs=2e-5, rel=2e-4), j
+        checked += 1
+    assert checked >= 5
+    assert abs(du.sum()) < 1e-10
+
+
 def test_du_zero_without_fractional_gates_and_in_mode2(oracle):
     rng = np.random.default_rng(14)
     B, H, n, d, kk, w = 1, 1, 30, 4, 4, 2
