@@ -18,4 +18,5 @@ from .ref import (  # noqa: F401
     mask_all,
     decode_bydef,
     max_threads,
+    scores,
 )

@@ -189,3 +189,17 @@ def decode_bydef(q_steps, K_hist, V_hist, u_hist, n_ctx, k, w, gate_mode, scale)
     q_full[n_ctx:] = q_steps
     o, _ = attn_rows(q_full, K_hist, V_hist, u_hist, tau, dth, k, w, gate_mode, scale, n_ctx, n)
     return o
+
+
+def scores(X, w, slope=0.0, norm=False, norm_eps=1e-5):
+    """Importance scores u [B,n] fp64 from hidden states X [B,n,D] and the scorer w [D]:
+    X.w plus the position slope, optionally timestep-normalised (Sec. 3.2 / Sec. 3.5)."""
+    X = _f32(X)
+    w = _f32(w)
+    B, n, D = X.shape
+    u = np.zeros((B, n), np.float64)
+    rc = _L().orc_scores(_p(X), _p(w), B, n, D, C.c_double(slope), int(bool(norm)), C.c_double(norm_eps), _p(u))
+    if rc:
+        raise ValueError("orc_scores: %d" % rc)
+    return u
+

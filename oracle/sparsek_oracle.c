@@ -424,6 +424,57 @@ int orc_mask_bwd(const float *q, const float *K, const float *V, const float *u,
     return bad ? -1 : used;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Importance scores: scoring network + position slope (Sec. 3.2, Eq. for u),  */
+/* optional timestep normalisation (Sec. 3.5, "score normalization")           */
+/* ------------------------------------------------------------------------- */
+
+/* One sequence.  X [n, D] row-major, w [D].  raw_t = X_t . w + t * slope (t counted from 0).
+ * norm == 0: u_t = raw_t.
+ * norm != 0: u_t = (raw_t - mean_t) / sqrt(var_t + norm_eps) with the cumulative statistics of
+ * the timesteps seen so far, mean_t = (1/(t+1)) sum_{i<=t} raw_i and var_t = (1/(t+1))
+ * sum_{i<=t} (raw_i - mean_t)^2, each recomputed from scratch for every t (two passes).
+ * Readings (the paper only says "cumulative mean and variance for each timestep"): population
+ * variance, no learnable gain or bias, norm_eps added under the root. */
+int orc_scores_row(const float *X, const float *w, int n, int D, double slope, int norm,
+                   double norm_eps, double *u)
+{
+    if (n < 1 || D < 1) return -1;
+    double *raw = (double *)malloc(sizeof(double) * (size_t)n);
+    for (int t = 0; t < n; t++) {
+        double acc = 0.0;
+        for (int c = 0; c < D; c++) acc += (double)X[(size_t)t * D + c] * (double)w[c];
+        raw[t] = acc + (double)t * slope;
+    }
+    for (int t = 0; t < n; t++) {
+        if (!norm) { u[t] = raw[t]; continue; }
+        double mean = 0.0, var = 0.0;
+        for (int i = 0; i <= t; i++) mean += raw[i];
+        mean /= (double)(t + 1);
+        for (int i = 0; i <= t; i++) var += (raw[i] - mean) * (raw[i] - mean);
+        var /= (double)(t + 1);
+        u[t] = (raw[t] - mean) / sqrt(var + norm_eps);
+    }
+    free(raw);
+    return 0;
+}
+
+/* X [B, n, D], u [B, n]: every sequence on its own. */
+int orc_scores(const float *X, const float *w, int B, int n, int D, double slope, int norm,
+               double norm_eps, double *u)
+{
+    if (B < 1) return -1;
+    int rc = 0;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (int b = 0; b < B; b++) {
+        int r = orc_scores_row(X + (size_t)b * n * D, w, n, D, slope, norm, norm_eps, u + (size_t)b * n);
+        if (r) rc = r;
+    }
+    return rc;
+}
+
 int orc_max_threads(void)
 {
 #ifdef _OPENMP
