@@ -6,7 +6,7 @@ sparsek_mask (thresholds + lifetimes) followed by sparsek_attn_fwd, at the
 Llama-7B-shaped long-context configuration (B=1, H=32, n=32768, d=128, k=w=1024, bf16).
 Inputs are resident in HBM before the timed region.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-bwd] [--no-decode]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-bwd] [--no-decode] [--no-scores]
 """
 import argparse
 import json
@@ -193,6 +193,41 @@ def mask_bwd_leg(iters=20, warm=3):
     }
 
 
+def scores_leg(iters=20, warm=3):
+    """Importance scores from hidden states (projection + position slope + timestep normalisation):
+    config 2's scorer shape and a Llama-7B-shaped hidden state at 32K.  HBM-bound: the hidden
+    states are read once."""
+    import torch
+
+    import paper_2406_16747_amd as spk
+
+    res = []
+    for name, B, n, D in (("config 2 scorer: B=8 n=4096 D=768 bf16", 8, 4096, 768),
+                          ("Llama-7B-shaped hidden state: B=1 n=32768 D=4096 bf16", 1, 32768, 4096)):
+        g = torch.Generator(device="cuda")
+        g.manual_seed(2000 + D)
+        x = torch.randn(B, n, D, device="cuda", generator=g).bfloat16()
+        w = torch.randn(D, device="cuda", generator=g) / math.sqrt(D)
+        for _ in range(warm):
+            spk.sparsek_scores(x, w, 2.0 ** -14, True, 1e-5)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            spk.sparsek_scores(x, w, 2.0 ** -14, True, 1e-5)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        nbytes = B * n * D * 2 + D * 4 + B * n * 4
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        res.append({"workload": name + ", slope 2^-14, timestep norm", "ms": ms,
+                    "roofline": {"bound": "hbm", "kernel": "scores_dot_kernel + partial + norm", "achieved": gbs,
+                                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                                 "algorithmic_bytes": nbytes, "traffic": None}})
+        del x
+    return res
+
+
 def read_traffic(name):
     """HBM bytes per launch of the dominant kernel, from the committed counter summary."""
     path = os.path.join(ROOT, "profiles", name)
@@ -214,6 +249,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-bwd", action="store_true")
+    ap.add_argument("--no-scores", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (to calibrate FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -312,6 +348,9 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_bwd:
         out["mask_bwd"] = mask_bwd_leg()
+        torch.cuda.empty_cache()
+    if not args.no_scores:
+        out["scores"] = scores_leg()
         torch.cuda.empty_cache()
     if not args.no_decode:
         out["decode"] = decode_leg()

@@ -105,6 +105,28 @@ int sparsek_mask_bwd(const sparsek_cfg *cfg, const void *q, const void *k, const
                      const float *lse, const void *dO, float *du, void *ws, size_t ws_bytes,
                      void *stream);
 
+/* ---- importance scores (Sec. 3.2 scoring network with position slope; Sec. 3.5 score normalisation) ----
+ * u out [B,n] fp32, one row per sequence (the single score group of the paper; feed it to sparsek_mask with Gu = 1):
+ *     raw_t = x_t . w + t * slope        (t counted from 0),
+ *     norm == 0:  u_t = raw_t
+ *     norm == 1:  u_t = (raw_t - mean_t) / sqrt(var_t + norm_eps),  mean_t / var_t = mean and population variance
+ *                 of raw_0 .. raw_t (timestep normalisation: cumulative statistics, no gain or bias).
+ * x  in [B,n,D] hidden states of `dtype` (SPARSEK_BF16 or SPARSEK_F32), contiguous; D a multiple of 8, D <= 8192.
+ * w  in [D] fp32 scorer.  Products and sums are accumulated in fp64; u is rounded once to fp32.
+ * ws scratch of at least sparsek_scores_workspace_bytes(cfg) bytes (raw scores in fp64 and block sums; unused when norm == 0).
+ * Errors: INVALID_ARG for null pointers, B, n, D < 1, norm not 0/1, norm_eps <= 0 with norm == 1, non-finite slope;
+ * UNSUPPORTED for D % 8 != 0, D > 8192 or another dtype. */
+typedef struct {
+    int32_t B, n, D;
+    int32_t dtype;   /* storage type of x */
+    int32_t norm;    /* 0 or 1 */
+    float slope;     /* epsilon of the position slope, >= 0 in the paper */
+    float norm_eps;  /* > 0 when norm == 1 */
+} sparsek_scores_cfg;
+size_t sparsek_scores_workspace_bytes(const sparsek_scores_cfg *cfg);
+int sparsek_scores(const sparsek_scores_cfg *cfg, const void *x, const float *w, float *u, void *ws,
+                   size_t ws_bytes, void *stream);
+
 /* ---- constant-memory decode (Sec. 3.2 irreversibility; Sec. 3.3 incremental evaluation) ----
  * The state holds, per (b,h), k+w key/value slots and, per (b,g), the scores of the window,
  * of the selected keys and of every other key still above the threshold (at most cand_cap of

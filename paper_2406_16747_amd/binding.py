@@ -15,6 +15,10 @@ class SparsekCfg(C.Structure):
     ]
 
 
+class SparsekScoresCfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "n", "D", "dtype", "norm")] + [("slope", C.c_float), ("norm_eps", C.c_float)]
+
+
 class SparsekDecodeCfg(C.Structure):
     _fields_ = [
         (n, C.c_int32) for n in ("B", "H", "Gu", "d", "k", "w", "cand_cap", "dtype", "gate_mode")
@@ -47,6 +51,11 @@ def lib():
         L.sparsek_materialize.argtypes = [cfgp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.sparsek_attn_fwd.argtypes = [cfgp] + [vp] * 8 + [vp, sz, vp]
         L.sparsek_mask_bwd.argtypes = [cfgp] + [vp] * 10 + [vp, sz, vp]
+        scfgp = C.POINTER(SparsekScoresCfg)
+        L.sparsek_scores_workspace_bytes.restype = sz
+        L.sparsek_scores_workspace_bytes.argtypes = [scfgp]
+        L.sparsek_scores.argtypes = [scfgp, vp, vp, vp, vp, sz, vp]
+        L.sparsek_scores.restype = C.c_int
         L.sparsek_decode_state_bytes.restype = sz
         L.sparsek_decode_state_bytes.argtypes = [dcfgp]
         L.sparsek_decode_init.argtypes = [dcfgp, vp, sz, vp]
@@ -162,6 +171,22 @@ def sparsek_mask_bwd(q, k, v, u, tau, death, o, lse, dO, k_sel, w, gate_mode=0, 
     check(lib().sparsek_mask_bwd(C.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(u), _ptr(tau), _ptr(death),
                                  _ptr(o), _ptr(lse), _ptr(dO), _ptr(du), _ptr(ws), ws.numel(), _stream()))
     return du
+
+
+def sparsek_scores(x, w, slope=0.0, norm=False, norm_eps=1e-5, ws=None):
+    """u [B,n] fp32 from hidden states x [B,n,D] (bf16 or fp32) and the scorer w [D] fp32:
+    x.w + position slope, optionally timestep-normalised."""
+    torch = _torch()
+    B, n, D = x.shape
+    assert x.is_contiguous() and w.is_contiguous() and w.dtype == torch.float32 and w.numel() == D
+    dt = BF16 if x.dtype == torch.bfloat16 else F32
+    assert dt == BF16 or x.dtype == torch.float32
+    cfg = SparsekScoresCfg(B=B, n=n, D=D, dtype=dt, norm=int(bool(norm)), slope=float(slope), norm_eps=float(norm_eps))
+    u = torch.empty(B, n, dtype=torch.float32, device=x.device)
+    if ws is None:
+        ws = _ws(lib().sparsek_scores_workspace_bytes(C.byref(cfg)), x.device)
+    check(lib().sparsek_scores(C.byref(cfg), _ptr(x), _ptr(w), _ptr(u), _ptr(ws), ws.numel(), _stream()))
+    return u
 
 
 class DecodeState:

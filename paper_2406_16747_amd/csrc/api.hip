@@ -91,6 +91,49 @@ int sparsek_attn_fwd(const sparsek_cfg* cfg, const void* q, const void* k, const
 
 }  // extern "C"
 
+// ---- importance scores (scores.hip) ----
+namespace spk {
+size_t scores_ws_bytes(int B, int n);
+int launch_scores(int B, int n, int D, int dtype, int norm, double slope, double norm_eps, const void* x,
+                  const float* w, float* u, void* ws, hipStream_t st);
+}  // namespace spk
+
+namespace {
+int check_scores(const sparsek_scores_cfg* c)
+{
+    if (!c) return SPARSEK_ERR_INVALID_ARG;
+    if (c->B < 1 || c->n < 1 || c->D < 1) return SPARSEK_ERR_INVALID_ARG;
+    if (c->norm != 0 && c->norm != 1) return SPARSEK_ERR_INVALID_ARG;
+    if (!(c->slope > -INFINITY) || !(c->slope < INFINITY)) return SPARSEK_ERR_INVALID_ARG;
+    if (c->norm == 1 && (!(c->norm_eps > 0.0f) || !(c->norm_eps < INFINITY))) return SPARSEK_ERR_INVALID_ARG;
+    if (c->dtype != SPARSEK_F32 && c->dtype != SPARSEK_BF16) return SPARSEK_ERR_UNSUPPORTED;
+    if ((c->D % 8) != 0 || c->D > 8192) return SPARSEK_ERR_UNSUPPORTED;
+    if ((long long)c->n > (1 << 28) || c->B > 65535) return SPARSEK_ERR_UNSUPPORTED;
+    return SPARSEK_OK;
+}
+}  // namespace
+
+extern "C" {
+
+size_t sparsek_scores_workspace_bytes(const sparsek_scores_cfg* cfg)
+{
+    if (check_scores(cfg)) return 0;
+    return spk::scores_ws_bytes(cfg->B, cfg->n);
+}
+
+int sparsek_scores(const sparsek_scores_cfg* cfg, const void* x, const float* w, float* u, void* ws,
+                   size_t ws_bytes, void* stream)
+{
+    int rc = check_scores(cfg);
+    if (rc) return rc;
+    if (!x || !w || !u) return SPARSEK_ERR_INVALID_ARG;
+    if (cfg->norm == 1 && (!ws || ws_bytes < spk::scores_ws_bytes(cfg->B, cfg->n))) return SPARSEK_ERR_WORKSPACE;
+    return spk::launch_scores(cfg->B, cfg->n, cfg->D, cfg->dtype, cfg->norm, (double)cfg->slope,
+                              (double)cfg->norm_eps, x, w, u, ws, (hipStream_t)stream);
+}
+
+}  // extern "C"
+
 // ---- entry points whose kernels live in mask_bwd.hip and decode.hip ----
 namespace spk {
 size_t decode_state_bytes(const sparsek_decode_cfg& c);

@@ -114,3 +114,14 @@ def to_device(arr, dtype, device="cuda"):
     if dtype == "bf16" and arr.dtype == np.uint16:
         t = t.view(torch.bfloat16)
     return t.to(device)
+
+
+def hidden_states(B, n, D, seed, dtype="bf16", offset=0.0):
+    """Hidden states x [B,n,D] ~ N(offset,1) in the storage type and a scorer w [D] ~ N(0,1/D)
+    fp32 (the recipe of config 2's scores).  Returns (storage array, fp32 values, w)."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((B, n, D), dtype=np.float32) + np.float32(offset)
+    w = rng.standard_normal(D, dtype=np.float32) / np.float32(math.sqrt(D))
+    xs, x32 = _store(x, dtype)
+    return xs, x32, w
+

@@ -42,3 +42,20 @@ def test_argument_validation_needs_no_gpu():
     assert L.sparsek_attn_fwd(ctypes.byref(bad), *([one] * 8), one, 1 << 20, null) == -2
     assert L.sparsek_attn_fwd(ctypes.byref(cfg), *([one] * 8), one, 8, null) == -3
     assert b"workspace" in L.sparsek_strerror(-3)
+    # importance scores
+    from paper_2406_16747_amd.binding import SparsekScoresCfg
+
+    sc = SparsekScoresCfg(B=2, n=100, D=768, dtype=spk.BF16, norm=1, slope=0.0, norm_eps=1e-5)
+    assert L.sparsek_scores_workspace_bytes(ctypes.byref(sc)) >= 2 * 100 * 8
+    assert L.sparsek_scores(ctypes.byref(sc), null, one, one, one, 1 << 20, null) == -1
+    assert L.sparsek_scores(ctypes.byref(sc), one, one, one, one, 8, null) == -3
+    bad = SparsekScoresCfg(B=2, n=100, D=100, dtype=spk.BF16, norm=0, slope=0.0, norm_eps=1e-5)
+    assert L.sparsek_scores(ctypes.byref(bad), one, one, one, one, 1 << 20, null) == -2  # D % 8
+    bad = SparsekScoresCfg(B=2, n=100, D=768, dtype=spk.BF16, norm=1, slope=0.0, norm_eps=0.0)
+    assert L.sparsek_scores(ctypes.byref(bad), one, one, one, one, 1 << 20, null) == -1  # eps must be > 0
+    bad = SparsekScoresCfg(B=2, n=100, D=768, dtype=spk.BF16, norm=2, slope=0.0, norm_eps=1e-5)
+    assert L.sparsek_scores(ctypes.byref(bad), one, one, one, one, 1 << 20, null) == -1
+    # gate modes 0..3 are valid, 4 is not
+    bad = spk.SparsekCfg(B=1, H=2, Gu=1, n=16, d=64, k=4, w=4, dtype=spk.BF16, gate_mode=4, softmax_scale=1.0)
+    assert L.sparsek_attn_fwd(ctypes.byref(bad), *([one] * 8), one, 1 << 20, null) == -1
+
