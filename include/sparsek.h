@@ -160,6 +160,46 @@ int sparsek_decode_step(const sparsek_decode_cfg *cfg, void *state, const void *
 int sparsek_decode_status(const sparsek_decode_cfg *cfg, const void *state, int32_t *host_flags,
                           void *stream);
 
+/* ---- chunk-wise recurrent prefill with a fixed-size scored cache (Sec. 3.4, the chunk recurrence) ----
+ * A sequence is consumed chunk by chunk; every call returns the attention output of its chunk's queries, equal to
+ * rows of sparsek_attn_fwd on the whole sequence.  Between calls the state keeps, per score row and in position
+ * order, the scores and (per head) the K/V rows of the last w keys, of the keys still selected and of every other
+ * key whose score is still above the SPARSEK threshold: at most R_cap = k + w + cand_cap entries (rounded up to a
+ * multiple of 128) whatever the sequence length.  A key outside that set can never be selected again nor move a
+ * later threshold, because the threshold does not decrease.  If more than cand_cap unselected keys stay above the
+ * threshold, the oldest of them are dropped and bit 0 of the row's flag word is set (thresholds are then approximate,
+ * as with the bounded heap of Sec. 3.3).
+ * q,k,v in [B,H,c,d], u in [B,Gu,c], o out [B,H,c,d]; 1 <= c <= chunk_max; d*sizeof(dtype) a multiple of 16.
+ * state: caller-owned device buffer of sparsek_chunk_state_bytes(cfg) bytes, set up by sparsek_chunk_init;
+ * ws: scratch of sparsek_chunk_workspace_bytes(cfg) bytes (sized for chunk_max).  Calls on one state must be
+ * ordered on one stream.  gate_mode as in sparsek_cfg (3 runs as 2). */
+typedef struct {
+    int32_t B, H, Gu, d, k, w;
+    int32_t cand_cap;   /* 0 = default 4*max(k,16) */
+    int32_t chunk_max;  /* longest chunk of a call */
+    int32_t dtype;      /* SPARSEK_BF16 or SPARSEK_F32 */
+    int32_t gate_mode;
+    float softmax_scale;
+} sparsek_chunk_cfg;
+size_t sparsek_chunk_state_bytes(const sparsek_chunk_cfg *cfg);
+size_t sparsek_chunk_workspace_bytes(const sparsek_chunk_cfg *cfg);
+int sparsek_chunk_init(const sparsek_chunk_cfg *cfg, void *state, size_t state_bytes, void *stream);
+int sparsek_chunk_prefill(const sparsek_chunk_cfg *cfg, void *state, size_t state_bytes, int32_t c,
+                          const void *q, const void *k, const void *v, const float *u, void *o, void *ws,
+                          size_t ws_bytes, void *stream);
+/* Hands the sequence over to the single-token decode: fills decode_state (of sparsek_decode_state_bytes(dcfg)
+ * bytes) with the state after the n_consumed tokens passed so far, so that sparsek_decode_step continues exactly
+ * where the chunks ended.  dcfg must agree with cfg in B, H, Gu, d, k, w and dtype.  n_consumed (the caller's count
+ * of tokens passed to sparsek_chunk_prefill) must be at least k + w (UNSUPPORTED otherwise).  Uses ws; the chunk
+ * state is left unchanged. */
+int sparsek_chunk_to_decode(const sparsek_chunk_cfg *cfg, void *state, size_t state_bytes, int64_t n_consumed,
+                            void *ws, size_t ws_bytes, const sparsek_decode_cfg *dcfg, void *decode_state,
+                            size_t decode_state_bytes, void *stream);
+/* Copies the number of retained entries and the flag word of every score row ([B*Gu] int32 each, either may be
+ * null) to host memory and synchronises the stream. */
+int sparsek_chunk_status(const sparsek_chunk_cfg *cfg, const void *state, int32_t *host_counts,
+                         int32_t *host_flags, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -16,6 +16,10 @@ from .binding import (  # noqa: F401
     sparsek_attn_fwd,
     sparsek_mask_bwd,
     sparsek_scores,
+    ChunkState,
+    sparsek_chunk_prefill,
+    sparsek_chunk_status,
+    sparsek_chunk_to_decode,
     sparsek_decode_init,
     sparsek_decode_load,
     sparsek_decode_step,

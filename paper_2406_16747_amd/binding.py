@@ -19,6 +19,12 @@ class SparsekScoresCfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "n", "D", "dtype", "norm")] + [("slope", C.c_float), ("norm_eps", C.c_float)]
 
 
+class SparsekChunkCfg(C.Structure):
+    _fields_ = [
+        (n, C.c_int32) for n in ("B", "H", "Gu", "d", "k", "w", "cand_cap", "chunk_max", "dtype", "gate_mode")
+    ] + [("softmax_scale", C.c_float)]
+
+
 class SparsekDecodeCfg(C.Structure):
     _fields_ = [
         (n, C.c_int32) for n in ("B", "H", "Gu", "d", "k", "w", "cand_cap", "dtype", "gate_mode")
@@ -56,6 +62,16 @@ def lib():
         L.sparsek_scores_workspace_bytes.argtypes = [scfgp]
         L.sparsek_scores.argtypes = [scfgp, vp, vp, vp, vp, sz, vp]
         L.sparsek_scores.restype = C.c_int
+        ccfgp = C.POINTER(SparsekChunkCfg)
+        for name in ("sparsek_chunk_state_bytes", "sparsek_chunk_workspace_bytes"):
+            getattr(L, name).restype = sz
+            getattr(L, name).argtypes = [ccfgp]
+        L.sparsek_chunk_init.argtypes = [ccfgp, vp, sz, vp]
+        L.sparsek_chunk_prefill.argtypes = [ccfgp, vp, sz, i32] + [vp] * 5 + [vp, sz, vp]
+        L.sparsek_chunk_status.argtypes = [ccfgp, vp, vp, vp, vp]
+        L.sparsek_chunk_to_decode.argtypes = [ccfgp, vp, sz, C.c_int64, vp, sz, dcfgp, vp, sz, vp]
+        for name in ("sparsek_chunk_init", "sparsek_chunk_prefill", "sparsek_chunk_status", "sparsek_chunk_to_decode"):
+            getattr(L, name).restype = C.c_int
         L.sparsek_decode_state_bytes.restype = sz
         L.sparsek_decode_state_bytes.argtypes = [dcfgp]
         L.sparsek_decode_init.argtypes = [dcfgp, vp, sz, vp]
@@ -187,6 +203,51 @@ def sparsek_scores(x, w, slope=0.0, norm=False, norm_eps=1e-5, ws=None):
         ws = _ws(lib().sparsek_scores_workspace_bytes(C.byref(cfg)), x.device)
     check(lib().sparsek_scores(C.byref(cfg), _ptr(x), _ptr(w), _ptr(u), _ptr(ws), ws.numel(), _stream()))
     return u
+
+
+class ChunkState:
+    """Caller-owned state of the chunk-wise recurrent prefill: a config, the state buffer and scratch."""
+
+    def __init__(self, B, H, Gu, d, k, w, dtype, chunk_max, gate_mode=0, scale=1.0, cand_cap=0, device="cuda"):
+        torch = _torch()
+        self.cfg = SparsekChunkCfg(B=B, H=H, Gu=Gu, d=d, k=int(k), w=int(w), cand_cap=int(cand_cap),
+                                   chunk_max=int(chunk_max), dtype=dtype, gate_mode=int(gate_mode),
+                                   softmax_scale=float(scale))
+        nbytes = lib().sparsek_chunk_state_bytes(C.byref(self.cfg))
+        if nbytes == 0:
+            raise ValueError("invalid chunk configuration")
+        self.buf = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.ws = torch.empty(lib().sparsek_chunk_workspace_bytes(C.byref(self.cfg)), dtype=torch.uint8, device=device)
+        check(lib().sparsek_chunk_init(C.byref(self.cfg), _ptr(self.buf), self.buf.numel(), _stream()))
+
+
+def sparsek_chunk_prefill(state, q, k, v, u):
+    """Attention output [B,H,c,d] of one chunk; the state moves on to the end of the chunk."""
+    torch = _torch()
+    c = q.shape[2]
+    o = torch.empty_like(q)
+    check(lib().sparsek_chunk_prefill(C.byref(state.cfg), _ptr(state.buf), state.buf.numel(), c, _ptr(q), _ptr(k),
+                                      _ptr(v), _ptr(u), _ptr(o), _ptr(state.ws), state.ws.numel(), _stream()))
+    return o
+
+
+def sparsek_chunk_to_decode(state, n_consumed, decode_state):
+    """Fills a DecodeState with the state after the n_consumed tokens the chunks have covered."""
+    check(lib().sparsek_chunk_to_decode(C.byref(state.cfg), _ptr(state.buf), state.buf.numel(), int(n_consumed),
+                                        _ptr(state.ws), state.ws.numel(), C.byref(decode_state.cfg),
+                                        _ptr(decode_state.buf), decode_state.buf.numel(), _stream()))
+
+
+def sparsek_chunk_status(state):
+    """(retained entries, flag word) per score row, as two int32 numpy arrays; synchronises."""
+    import numpy as np
+
+    rows = state.cfg.B * state.cfg.Gu
+    counts = np.zeros(rows, np.int32)
+    flags = np.zeros(rows, np.int32)
+    check(lib().sparsek_chunk_status(C.byref(state.cfg), _ptr(state.buf), counts.ctypes.data_as(C.c_void_p),
+                                     flags.ctypes.data_as(C.c_void_p), _stream()))
+    return counts, flags
 
 
 class DecodeState:

@@ -229,3 +229,100 @@ int sparsek_decode_status(const sparsek_decode_cfg* cfg, const void* state, int3
 }
 
 }  // extern "C"
+
+// ---- chunk-wise recurrent prefill (chunk.hip) ----
+namespace spk {
+size_t chunk_state_bytes(const sparsek_chunk_cfg& c);
+size_t chunk_ws_bytes(const sparsek_chunk_cfg& c);
+int launch_chunk_init(const sparsek_chunk_cfg& c, void* state, hipStream_t st);
+int launch_chunk_prefill(const sparsek_chunk_cfg& c, void* state, int clen, const void* q, const void* k,
+                         const void* v, const float* u, void* o, void* ws, hipStream_t st);
+int chunk_status(const sparsek_chunk_cfg& c, const void* state, int32_t* host_counts, int32_t* host_flags,
+                 hipStream_t st);
+int launch_chunk_to_decode(const sparsek_chunk_cfg& c, void* state, void* ws, const sparsek_decode_cfg& dc,
+                           void* dstate, hipStream_t st);
+}  // namespace spk
+
+namespace {
+int check_chunk(const sparsek_chunk_cfg* c)
+{
+    if (!c) return SPARSEK_ERR_INVALID_ARG;
+    if (c->B < 1 || c->H < 1 || c->k < 0 || c->w < 0 || c->k + c->w < 1 || c->cand_cap < 0 || c->chunk_max < 1)
+        return SPARSEK_ERR_INVALID_ARG;
+    if (c->Gu != 1 && c->Gu != c->H) return SPARSEK_ERR_INVALID_ARG;
+    if (c->gate_mode < 0 || c->gate_mode > 3) return SPARSEK_ERR_INVALID_ARG;
+    if (!(c->softmax_scale > 0.0f) || !(c->softmax_scale < INFINITY)) return SPARSEK_ERR_INVALID_ARG;
+    if (c->dtype != SPARSEK_F32 && c->dtype != SPARSEK_BF16) return SPARSEK_ERR_UNSUPPORTED;
+    if (c->d < 4 || c->d > 128 || (c->d % 4) != 0) return SPARSEK_ERR_UNSUPPORTED;
+    if ((c->d * (c->dtype == SPARSEK_BF16 ? 2 : 4)) % 16 != 0) return SPARSEK_ERR_UNSUPPORTED;
+    if ((long long)c->B * c->H > 65535) return SPARSEK_ERR_UNSUPPORTED;
+    if ((long long)c->k + c->w + c->cand_cap + c->chunk_max > (1 << 26)) return SPARSEK_ERR_UNSUPPORTED;
+    return SPARSEK_OK;
+}
+}  // namespace
+
+extern "C" {
+
+size_t sparsek_chunk_state_bytes(const sparsek_chunk_cfg* cfg)
+{
+    if (check_chunk(cfg)) return 0;
+    return spk::chunk_state_bytes(*cfg);
+}
+
+size_t sparsek_chunk_workspace_bytes(const sparsek_chunk_cfg* cfg)
+{
+    if (check_chunk(cfg)) return 0;
+    return spk::chunk_ws_bytes(*cfg);
+}
+
+int sparsek_chunk_init(const sparsek_chunk_cfg* cfg, void* state, size_t state_bytes, void* stream)
+{
+    int rc = check_chunk(cfg);
+    if (rc) return rc;
+    if (!state) return SPARSEK_ERR_INVALID_ARG;
+    if (state_bytes < spk::chunk_state_bytes(*cfg)) return SPARSEK_ERR_WORKSPACE;
+    return spk::launch_chunk_init(*cfg, state, (hipStream_t)stream);
+}
+
+int sparsek_chunk_prefill(const sparsek_chunk_cfg* cfg, void* state, size_t state_bytes, int32_t c, const void* q,
+                          const void* k, const void* v, const float* u, void* o, void* ws, size_t ws_bytes,
+                          void* stream)
+{
+    int rc = check_chunk(cfg);
+    if (rc) return rc;
+    if (!state || !q || !k || !v || !u || !o || !ws) return SPARSEK_ERR_INVALID_ARG;
+    if (c < 1 || c > cfg->chunk_max) return SPARSEK_ERR_INVALID_ARG;
+    if (state_bytes < spk::chunk_state_bytes(*cfg) || ws_bytes < spk::chunk_ws_bytes(*cfg)) return SPARSEK_ERR_WORKSPACE;
+    return spk::launch_chunk_prefill(*cfg, state, c, q, k, v, u, o, ws, (hipStream_t)stream);
+}
+
+int sparsek_chunk_to_decode(const sparsek_chunk_cfg* cfg, void* state, size_t state_bytes, int64_t n_consumed,
+                            void* ws, size_t ws_bytes, const sparsek_decode_cfg* dcfg, void* decode_state,
+                            size_t decode_state_bytes, void* stream)
+{
+    int rc = check_chunk(cfg);
+    if (rc) return rc;
+    rc = check_decode(dcfg);
+    if (rc) return rc;
+    if (!state || !ws || !decode_state) return SPARSEK_ERR_INVALID_ARG;
+    if (dcfg->B != cfg->B || dcfg->H != cfg->H || dcfg->Gu != cfg->Gu || dcfg->d != cfg->d || dcfg->k != cfg->k ||
+        dcfg->w != cfg->w || dcfg->dtype != cfg->dtype)
+        return SPARSEK_ERR_INVALID_ARG;
+    if (n_consumed < (int64_t)cfg->k + cfg->w) return SPARSEK_ERR_UNSUPPORTED;
+    if (state_bytes < spk::chunk_state_bytes(*cfg) || ws_bytes < spk::chunk_ws_bytes(*cfg) ||
+        decode_state_bytes < spk::decode_state_bytes(*dcfg))
+        return SPARSEK_ERR_WORKSPACE;
+    return spk::launch_chunk_to_decode(*cfg, state, ws, *dcfg, decode_state, (hipStream_t)stream);
+}
+
+int sparsek_chunk_status(const sparsek_chunk_cfg* cfg, const void* state, int32_t* host_counts, int32_t* host_flags,
+                         void* stream)
+{
+    int rc = check_chunk(cfg);
+    if (rc) return rc;
+    if (!state) return SPARSEK_ERR_INVALID_ARG;
+    return spk::chunk_status(*cfg, state, host_counts, host_flags, (hipStream_t)stream);
+}
+
+}  // extern "C"
+

@@ -142,7 +142,8 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(
     const T* __restrict__ q, const T* __restrict__ kk, const T* __restrict__ v,
     const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
     const int32_t* __restrict__ lists, const int32_t* __restrict__ counts, T* __restrict__ o,
-    float* __restrict__ lse, int H, int Gu, int n, int d, int k, int w, int gate_mode, float scale, int nb)
+    float* __restrict__ lse, int H, int Gu, int n, int d, int k, int w, int gate_mode, float scale, int nb,
+    int q_begin, const int32_t* __restrict__ first_valid)
 {
     __shared__ float qs[4][128];
     const int blk = blockIdx.x, bh = blockIdx.y;
@@ -150,6 +151,7 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(
     const int row = b * Gu + (Gu == 1 ? 0 : h);
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int i0 = blk * QB;
+    if (i0 + QB <= q_begin) return;  // queries before q_begin are not wanted (chunked prefill)
     const T* qh = q + (size_t)bh * n * d;
     const T* kh = kk + (size_t)bh * n * d;
     const T* vh = v + (size_t)bh * n * d;
@@ -159,7 +161,8 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(
     const int32_t* dr = death + (size_t)row * n;
     const int32_t* list = lists + ((size_t)row * nb + blk) * (size_t)(k > 0 ? k : 1);
     const int cnt = counts[(size_t)row * nb + blk];
-    const int c0 = max(0, i0 - w + 1);
+    // keys before first_valid[row] (padding of a chunked prefill) are attended by nobody
+    const int c0 = max(max(0, i0 - w + 1), first_valid ? first_valid[row] : 0);
 
     for (int qi = wv; qi < QB; qi += 4) {
         const int i = i0 + qi;
@@ -519,7 +522,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ kk, const uint16_t* __restrict__ v,
     const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
     const int32_t* __restrict__ lists, const int32_t* __restrict__ counts, uint16_t* __restrict__ o,
-    float* __restrict__ lse, int H, int Gu, int n, int k, int w, float scale, int nb, int BH, int nrows)
+    float* __restrict__ lse, int H, int Gu, int n, int k, int w, float scale, int nb, int BH, int nrows,
+    int q_begin, const int32_t* __restrict__ first_valid)
 {
     __shared__ __align__(16) MfmaSmem<D> sm;
     constexpr int DS = D / 16;   // MFMA k-steps over the head dim
@@ -544,6 +548,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, col = lane & 31;
     const int i0 = blk * QB;
+    if (i0 + QB <= q_begin) return;  // queries before q_begin are not wanted (chunked prefill)
     const uint16_t* qh = q + (size_t)bh * n * D;
     const uint16_t* kh = kk + (size_t)bh * n * D;
     const uint16_t* vh = v + (size_t)bh * n * D;
@@ -553,7 +558,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     const int32_t* list = lists + ((size_t)row * nb + blk) * (size_t)(k > 0 ? k : 1);
     const int cnt = counts[(size_t)row * nb + blk];
     const int nstay = counts[(size_t)nrows * nb + (size_t)row * nb + blk];
-    const int c0 = max(0, i0 - w + 1);
+    // keys before first_valid[row] (padding of a chunked prefill) are attended by nobody
+    const int c0 = max(max(0, i0 - w + 1), first_valid ? first_valid[row] : 0);
     const int c_end = min(n - 1, i0 + QB - 1);
     const int nkl = (cnt + KT - 1) / KT * KT;                // list part, padded to whole tiles
     const int nkc = (c_end - c0 + 1 + KT - 1) / KT * KT;     // contiguous part, padded
@@ -663,14 +669,15 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
 template <int D>
 static void launch_mfma(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                         const float* tau, const int32_t* death, const int32_t* lists, const int32_t* counts,
-                        void* o, float* lse, int nb, hipStream_t st)
+                        void* o, float* lse, int nb, int q_begin, const int32_t* first_valid,
+                        hipStream_t st)
 {
     const int BH = c.B * c.H;
     dim3 grid(nb * BH);
 #define SPK_LAUNCH(MODE)                                                                                   \
     hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q,        \
                        (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, (uint16_t*)o, \
-                       lse, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH, c.B * c.Gu)
+                       lse, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH, c.B * c.Gu, q_begin, first_valid)
     if (c.gate_mode == 0) SPK_LAUNCH(0);
     else if (c.gate_mode == 1) SPK_LAUNCH(1);
     else SPK_LAUNCH(2);
@@ -687,7 +694,7 @@ void launch_block_lists(const sparsek_cfg& c, const int32_t* death, int32_t* lis
 
 int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                     const float* tau, const int32_t* death, void* o, float* lse, void* ws,
-                    hipStream_t st)
+                    hipStream_t st, int q_begin, const int32_t* first_valid)
 {
     const int nb = nblocks(c.n);
     size_t coff = 0;
@@ -696,19 +703,19 @@ int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const vo
     int32_t* counts = (int32_t*)((char*)ws + coff);
     launch_block_lists(c, death, lists, counts, st);
     if (c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull) {
-        if (c.d == 64) launch_mfma<64>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, st);
-        else launch_mfma<128>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, st);
+        if (c.d == 64) launch_mfma<64>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, q_begin, first_valid, st);
+        else launch_mfma<128>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, q_begin, first_valid, st);
         return launch_status();
     }
     dim3 grid(nb, c.B * c.H);
     if (c.dtype == SPARSEK_F32) {
         hipLaunchKernelGGL(attn_fwd_generic_kernel<float>, grid, dim3(256), 0, st, (const float*)q,
                            (const float*)k, (const float*)v, u, tau, death, lists, counts, (float*)o, lse, c.H,
-                           c.Gu, c.n, c.d, c.k, c.w, c.gate_mode, c.softmax_scale, nb);
+                           c.Gu, c.n, c.d, c.k, c.w, c.gate_mode, c.softmax_scale, nb, q_begin, first_valid);
     } else {
         hipLaunchKernelGGL(attn_fwd_generic_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)q,
                            (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, (uint16_t*)o,
-                           lse, c.H, c.Gu, c.n, c.d, c.k, c.w, c.gate_mode, c.softmax_scale, nb);
+                           lse, c.H, c.Gu, c.n, c.d, c.k, c.w, c.gate_mode, c.softmax_scale, nb, q_begin, first_valid);
     }
     return launch_status();
 }

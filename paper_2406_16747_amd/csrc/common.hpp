@@ -17,7 +17,8 @@ int launch_materialize(const sparsek_cfg& c, const float* u, const float* tau, c
                        int t_begin, int t_end, int32_t* idx, float* gate, hipStream_t st);
 int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const void* v,
                     const float* u, const float* tau, const int32_t* death, void* o, float* lse,
-                    void* ws, hipStream_t st);
+                    void* ws, hipStream_t st, int q_begin = 0, const int32_t* first_valid = nullptr);
+// (query blocks that end at or before q_begin are skipped; keys before first_valid[row] are never attended)
 size_t attn_fwd_ws_bytes(const sparsek_cfg& c);
 int launch_mask_bwd(const sparsek_cfg& c, const void* q, const void* k, const void* v,
                     const float* u, const float* tau, const int32_t* death, const void* o,
