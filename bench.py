@@ -6,7 +6,7 @@ sparsek_mask (thresholds + lifetimes) followed by sparsek_attn_fwd, at the
 Llama-7B-shaped long-context configuration (B=1, H=32, n=32768, d=128, k=w=1024, bf16).
 Inputs are resident in HBM before the timed region.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-bwd] [--no-decode] [--no-scores]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-bwd] [--no-decode] [--no-scores] [--no-chunk] [--only LEG]
 """
 import argparse
 import json
@@ -228,6 +228,45 @@ def scores_leg(iters=20, warm=3):
     return res
 
 
+def chunk_leg(n=131072, c=8192):
+    """Chunk-wise recurrent prefill (fixed-size scored cache): a 128K-token sequence of the config-4
+    head shape (H=32, d=128, k=w=1024, bf16) consumed in chunks of 8192; the state never grows."""
+    import torch
+
+    import paper_2406_16747_amd as spk
+
+    B, H, d, k, w = 1, 32, 128, 1024, 1024
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1104)
+    div = math.sqrt(d)
+    chunks = []
+    for _ in range(n // c):  # drawn chunk by chunk: the whole sequence never has to be resident
+        q, kk, v = ((torch.randn(B, H, c, d, device="cuda", generator=g) / div).bfloat16() for _ in range(3))
+        chunks.append((q, kk, v, torch.randn(B, 1, c, device="cuda", generator=g)))
+    st = spk.ChunkState(B, H, 1, d, k, w, spk.BF16, c, 0, 1.0)
+    for ch in chunks[:2]:
+        spk.sparsek_chunk_prefill(st, *ch)
+    st = spk.ChunkState(B, H, 1, d, k, w, spk.BF16, c, 0, 1.0)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for ch in chunks:
+        spk.sparsek_chunk_prefill(st, *ch)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    counts, flags = spk.sparsek_chunk_status(st)
+    flops = 4.0 * d * attended_pairs(n, k, w) * B * H
+    ach = flops / (ms * 1e-3) / 1e12
+    return {"workload": "B=1 H=32 n=%d d=128 k=w=1024 bf16, Gu=1, gate_mode=0, chunks of %d" % (n, c),
+            "ms_total": ms, "ms_per_chunk": ms / len(chunks), "tokens_per_s": n / (ms * 1e-3),
+            "retained_entries": int(counts.max()), "overflow": bool(flags.any()),
+            "state_bytes": int(st.buf.numel()), "workspace_bytes": int(st.ws.numel()),
+            "roofline": {"bound": "mfma", "kernel": "whole chunk step (mask + attn_fwd_mfma_kernel<128> + state upkeep)",
+                         "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": ach / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops": flops, "traffic": None}}
+
+
 def read_traffic(name):
     """HBM bytes per launch of the dominant kernel, from the committed counter summary."""
     path = os.path.join(ROOT, "profiles", name)
@@ -250,6 +289,9 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-bwd", action="store_true")
     ap.add_argument("--no-scores", action="store_true")
+    ap.add_argument("--no-chunk", action="store_true")
+    ap.add_argument("--only", choices=["chunk", "scores", "bwd", "decode"],
+                    help="run one of the side legs alone and print its object (for profiling that leg)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (to calibrate FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -263,6 +305,10 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     spk.lib()  # fail loudly if the HIP library is missing
+    if args.only:
+        leg = {"chunk": chunk_leg, "scores": scores_leg, "bwd": mask_bwd_leg, "decode": decode_leg}[args.only]
+        print(json.dumps({"only": args.only, "result": leg()}))
+        return
     if args.copy_calibration:
         a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         b = torch.empty_like(a)
@@ -351,6 +397,9 @@ def main():
         torch.cuda.empty_cache()
     if not args.no_scores:
         out["scores"] = scores_leg()
+        torch.cuda.empty_cache()
+    if not args.no_chunk:
+        out["chunked_prefill"] = chunk_leg()
         torch.cuda.empty_cache()
     if not args.no_decode:
         out["decode"] = decode_leg()
