@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(
     const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
     const int32_t* __restrict__ lists, const int32_t* __restrict__ counts, T* __restrict__ o,
     float* __restrict__ lse, int H, int Gu, int n, int d, int k, int w, int gate_mode, float scale, int nb,
-    int q_begin, const int32_t* __restrict__ first_valid)
+    int q_begin, const int32_t* __restrict__ first_valid, int q_rows)
 {
     __shared__ float qs[4][128];
     const int blk = blockIdx.x, bh = blockIdx.y;
@@ -152,10 +152,12 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int i0 = blk * QB;
     if (i0 + QB <= q_begin) return;  // queries before q_begin are not wanted (chunked prefill)
-    const T* qh = q + (size_t)bh * n * d;
+    // q and o hold q_rows rows per head starting at query q_begin (0: all n rows)
+    const ptrdiff_t qo = q_rows ? (ptrdiff_t)bh * q_rows - q_begin : (ptrdiff_t)bh * n;
+    const T* qh = q + qo * d;
     const T* kh = kk + (size_t)bh * n * d;
     const T* vh = v + (size_t)bh * n * d;
-    T* oh = o + (size_t)bh * n * d;
+    T* oh = o + qo * d;
     const float* ur = u + (size_t)row * n;
     const float* tr = tau + (size_t)row * n;
     const int32_t* dr = death + (size_t)row * n;
@@ -523,7 +525,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
     const int32_t* __restrict__ lists, const int32_t* __restrict__ counts, uint16_t* __restrict__ o,
     float* __restrict__ lse, int H, int Gu, int n, int k, int w, float scale, int nb, int BH, int nrows,
-    int q_begin, const int32_t* __restrict__ first_valid)
+    int q_begin, const int32_t* __restrict__ first_valid, int q_rows)
 {
     __shared__ __align__(16) MfmaSmem<D> sm;
     constexpr int DS = D / 16;   // MFMA k-steps over the head dim
@@ -549,7 +551,9 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     const int half = lane >> 5, col = lane & 31;
     const int i0 = blk * QB;
     if (i0 + QB <= q_begin) return;  // queries before q_begin are not wanted (chunked prefill)
-    const uint16_t* qh = q + (size_t)bh * n * D;
+    // q and o hold q_rows rows per head starting at query q_begin (0: all n rows)
+    const ptrdiff_t qo = q_rows ? (ptrdiff_t)bh * q_rows - q_begin : (ptrdiff_t)bh * n;
+    const uint16_t* qh = q + qo * D;
     const uint16_t* kh = kk + (size_t)bh * n * D;
     const uint16_t* vh = v + (size_t)bh * n * D;
     const float* ur = u + (size_t)row * n;
@@ -651,7 +655,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     if (qi < n) {
         const float inv = 1.0f / l_tot;
-        uint16_t* orow = o + ((size_t)bh * n + qi) * D;
+        uint16_t* orow = o + (qo + qi) * D;
 #pragma unroll
         for (int x = 0; x < DB; x++) {
 #pragma unroll
@@ -670,14 +674,14 @@ template <int D>
 static void launch_mfma(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                         const float* tau, const int32_t* death, const int32_t* lists, const int32_t* counts,
                         void* o, float* lse, int nb, int q_begin, const int32_t* first_valid,
-                        hipStream_t st)
+                        int q_rows, hipStream_t st)
 {
     const int BH = c.B * c.H;
     dim3 grid(nb * BH);
 #define SPK_LAUNCH(MODE)                                                                                   \
     hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q,        \
                        (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, (uint16_t*)o, \
-                       lse, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH, c.B * c.Gu, q_begin, first_valid)
+                       lse, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH, c.B * c.Gu, q_begin, first_valid, q_rows)
     if (c.gate_mode == 0) SPK_LAUNCH(0);
     else if (c.gate_mode == 1) SPK_LAUNCH(1);
     else SPK_LAUNCH(2);
@@ -694,7 +698,7 @@ void launch_block_lists(const sparsek_cfg& c, const int32_t* death, int32_t* lis
 
 int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                     const float* tau, const int32_t* death, void* o, float* lse, void* ws,
-                    hipStream_t st, int q_begin, const int32_t* first_valid)
+                    hipStream_t st, int q_begin, const int32_t* first_valid, int q_rows)
 {
     const int nb = nblocks(c.n);
     size_t coff = 0;
@@ -703,19 +707,19 @@ int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const vo
     int32_t* counts = (int32_t*)((char*)ws + coff);
     launch_block_lists(c, death, lists, counts, st);
     if (c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull) {
-        if (c.d == 64) launch_mfma<64>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, q_begin, first_valid, st);
-        else launch_mfma<128>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, q_begin, first_valid, st);
+        if (c.d == 64) launch_mfma<64>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, q_begin, first_valid, q_rows, st);
+        else launch_mfma<128>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, q_begin, first_valid, q_rows, st);
         return launch_status();
     }
     dim3 grid(nb, c.B * c.H);
     if (c.dtype == SPARSEK_F32) {
         hipLaunchKernelGGL(attn_fwd_generic_kernel<float>, grid, dim3(256), 0, st, (const float*)q,
                            (const float*)k, (const float*)v, u, tau, death, lists, counts, (float*)o, lse, c.H,
-                           c.Gu, c.n, c.d, c.k, c.w, c.gate_mode, c.softmax_scale, nb, q_begin, first_valid);
+                           c.Gu, c.n, c.d, c.k, c.w, c.gate_mode, c.softmax_scale, nb, q_begin, first_valid, q_rows);
     } else {
         hipLaunchKernelGGL(attn_fwd_generic_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)q,
                            (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, (uint16_t*)o,
-                           lse, c.H, c.Gu, c.n, c.d, c.k, c.w, c.gate_mode, c.softmax_scale, nb, q_begin, first_valid);
+                           lse, c.H, c.Gu, c.n, c.d, c.k, c.w, c.gate_mode, c.softmax_scale, nb, q_begin, first_valid, q_rows);
     }
     return launch_status();
 }

@@ -24,7 +24,7 @@ namespace spk {
 
 struct ChunkLayout {
     int rcap;                              // capacity of the retained set (multiple of 128)
-    size_t count, flags, ret_u, ret_k, ret_v, total;
+    size_t count, flags, ret_u, ret_sel, ret_k, ret_v, total;
 };
 
 static int chunk_rcap(const sparsek_chunk_cfg& c)
@@ -44,6 +44,7 @@ static ChunkLayout chunk_layout(const sparsek_chunk_cfg& c)
     L.count = off; off += align_up(rows * 4, 256);
     L.flags = off; off += align_up(rows * 4, 256);
     L.ret_u = off; off += align_up(rows * L.rcap * 4, 256);
+    L.ret_sel = off; off += align_up(rows * L.rcap * 4, 256);
     L.ret_k = off; off += align_up(BH * L.rcap * c.d * esize(c.dtype), 256);
     L.ret_v = off; off += align_up(BH * L.rcap * c.d * esize(c.dtype), 256);
     L.total = off;
@@ -63,7 +64,7 @@ static sparsek_cfg virtual_cfg(const sparsek_chunk_cfg& c, int nv)
 }
 
 struct ChunkWs {
-    size_t u, tau, death, map, newcount, first, q, k, v, o, mask, attn, total;
+    size_t u, tau, death, map, first, k, v, mask, attn, total;
 };
 static ChunkWs chunk_ws(const sparsek_chunk_cfg& c, int clen)
 {
@@ -77,13 +78,10 @@ static ChunkWs chunk_ws(const sparsek_chunk_cfg& c, int clen)
     W.tau = off; off += align_up(rows * nv * 4, 256);
     W.death = off; off += align_up(rows * nv * 4, 256);
     W.map = off; off += align_up(rows * L.rcap * 4, 256);
-    W.newcount = off; off += align_up(rows * 4, 256);
     W.first = off; off += align_up(rows * 4, 256);
     const size_t tens = align_up(BH * nv * c.d * esize(c.dtype), 256);
-    W.q = off; off += tens;
     W.k = off; off += tens;
     W.v = off; off += tens;
-    W.o = off; off += tens;
     W.mask = off; off += align_up(mask_ws_bytes(v), 256);
     W.attn = off; off += align_up(attn_fwd_ws_bytes(v), 256);
     W.total = off;
@@ -98,13 +96,13 @@ __global__ void chunk_init_kernel(int32_t* count, int32_t* flags, int rows)
 }
 
 // Scores of the virtual sequence of one row: padding (min - 2), retained, chunk.
-__global__ __launch_bounds__(256) void chunk_assemble_scores_kernel(const int32_t* __restrict__ count,
-                                                                    const float* __restrict__ ret_u,
-                                                                    const float* __restrict__ u_chunk, int rcap,
-                                                                    int clen, float* __restrict__ u_v,
-                                                                    int32_t* __restrict__ first_valid)
+__global__ __launch_bounds__(1024) void chunk_assemble_scores_kernel(const int32_t* __restrict__ count,
+                                                                     const float* __restrict__ ret_u,
+                                                                     const float* __restrict__ u_chunk, int rcap,
+                                                                     int clen, float* __restrict__ u_v,
+                                                                     int32_t* __restrict__ first_valid)
 {
-    __shared__ float red[4];
+    __shared__ float red[16];
     const int row = blockIdx.x, tid = threadIdx.x;
     const int R = count[row];
     const int pad = rcap - R, nv = rcap + clen;
@@ -112,23 +110,26 @@ __global__ __launch_bounds__(256) void chunk_assemble_scores_kernel(const int32_
     const float* ru = ret_u + (size_t)row * rcap;
     const float* cu = u_chunk + (size_t)row * clen;
     float mn = INFINITY;
-    for (int i = tid; i < R; i += 256) mn = fminf(mn, ru[i]);
-    for (int i = tid; i < clen; i += 256) mn = fminf(mn, cu[i]);
+    for (int i = tid; i < R; i += 1024) mn = fminf(mn, ru[i]);
+    for (int i = tid; i < clen; i += 1024) mn = fminf(mn, cu[i]);
     mn = wave_min_f32(mn);
     if ((tid & 63) == 0) red[tid >> 6] = mn;
     __syncthreads();
-    const float dummy = fminf(fminf(red[0], red[1]), fminf(red[2], red[3])) - 2.0f;
+    float m = red[0];
+#pragma unroll
+    for (int i = 1; i < 16; i++) m = fminf(m, red[i]);
+    const float dummy = m - 2.0f;
     float* out = u_v + (size_t)row * nv;
-    for (int e = tid; e < nv; e += 256) out[e] = e < pad ? dummy : e < rcap ? ru[e - pad] : cu[e - rcap];
+    for (int e = tid; e < nv; e += 1024) out[e] = e < pad ? dummy : e < rcap ? ru[e - pad] : cu[e - rcap];
 }
 
-// K, V and Q rows of the virtual sequence of one head (16 bytes per thread and step).  Padding
-// rows are zero; Q is only needed for the chunk's positions.
+// K and V rows of the virtual sequence of one head (16 bytes per thread and step).  Padding rows
+// are zero.  (Q and O stay in the caller's chunk tensors: the attention kernel addresses them from
+// its first query.)
 __global__ __launch_bounds__(256) void chunk_assemble_rows_kernel(
     const int32_t* __restrict__ count, const uint4* __restrict__ ret_k, const uint4* __restrict__ ret_v,
-    const uint4* __restrict__ q_c, const uint4* __restrict__ k_c, const uint4* __restrict__ v_c, int H, int Gu,
-    int rcap, int clen, int row16 /* 16-byte units per row */, uint4* __restrict__ q_v, uint4* __restrict__ k_v,
-    uint4* __restrict__ v_v)
+    const uint4* __restrict__ k_c, const uint4* __restrict__ v_c, int H, int Gu, int rcap, int clen,
+    int row16 /* 16-byte units per row */, uint4* __restrict__ k_v, uint4* __restrict__ v_v)
 {
     const int bh = blockIdx.y;
     const int b = bh / H, h = bh % H;
@@ -143,7 +144,6 @@ __global__ __launch_bounds__(256) void chunk_assemble_rows_kernel(
             const size_t src = ((size_t)bh * clen + (e - rcap)) * row16 + c16;
             kk = k_c[src];
             vv = v_c[src];
-            q_v[dst] = q_c[src];
         } else if (e >= pad) {
             const size_t src = ((size_t)bh * rcap + (e - pad)) * row16 + c16;
             kk = ret_k[src];
@@ -154,24 +154,17 @@ __global__ __launch_bounds__(256) void chunk_assemble_rows_kernel(
     }
 }
 
-// Padding entries are never selected: death[e] = e.
-__global__ void chunk_clear_padding_kernel(const int32_t* __restrict__ count, int rcap, int nv,
-                                           int32_t* __restrict__ death)
+// Padding entries are never selected: death[e] = e.  The same holds for retained keys that were
+// kept only because their score is above the threshold: they left the top-k in an earlier chunk, at
+// a prefix whose block the mask skips, so their lifetime is still at its preset.
+__global__ void chunk_clear_padding_kernel(const int32_t* __restrict__ count, const int32_t* __restrict__ ret_sel,
+                                           int rcap, int nv, int32_t* __restrict__ death)
 {
     const int row = blockIdx.y;
     const int pad = rcap - count[row];
     const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e < pad) death[(size_t)row * nv + e] = e;
-}
-
-__global__ __launch_bounds__(256) void chunk_copy_out_kernel(const uint4* __restrict__ o_v, int rcap, int clen,
-                                                             int row16, uint4* __restrict__ o_c)
-{
-    const int bh = blockIdx.y;
-    const int nv = rcap + clen;
-    const size_t total = (size_t)clen * row16;
-    for (size_t x = (size_t)blockIdx.x * 256 + threadIdx.x; x < total; x += (size_t)gridDim.x * 256)
-        o_c[(size_t)bh * total + x] = o_v[((size_t)bh * nv + rcap) * row16 + x];
+    if (e >= rcap) return;
+    if (e < pad || !ret_sel[(size_t)row * rcap + (e - pad)]) death[(size_t)row * nv + e] = e;
 }
 
 // Exclusive prefix sums of two counters over the 1024 threads of a workgroup.
@@ -199,18 +192,22 @@ __device__ __forceinline__ void block_scan2_1024(int a, int b, int (*wt)[16], in
 // last prefix used so far (T = nv - 1 - w) and every other real key whose score is above that
 // prefix's threshold.  The first two classes always fit; if the third does not, its oldest members
 // are dropped and bit 0 of the row's flag word is set (later thresholds are then approximate).
-__global__ __launch_bounds__(1024) void chunk_retain_kernel(const int32_t* __restrict__ count, int32_t* __restrict__ flags,
+constexpr int RETAIN_LDS = 48 * 1024;  // classes of up to this many virtual positions are cached in LDS
+
+__global__ __launch_bounds__(1024) void chunk_retain_kernel(int32_t* __restrict__ count, int32_t* __restrict__ flags,
                                                             const float* __restrict__ u_v,
                                                             const float* __restrict__ tau_v,
                                                             const int32_t* __restrict__ death_v, int rcap, int clen,
-                                                            int w, int32_t* __restrict__ map,
-                                                            int32_t* __restrict__ newcount, float* __restrict__ ret_u)
+                                                            int w, int32_t* __restrict__ map, float* __restrict__ ret_u,
+                                                            int32_t* __restrict__ ret_sel)
 {
     __shared__ int wt[2][16];
+    __shared__ unsigned char cls[RETAIN_LDS];
     const int row = blockIdx.x, tid = threadIdx.x;
     const int nv = rcap + clen;
     const int pad = rcap - count[row];
     const int T = nv - 1 - w;  // last prefix any query has used
+    const bool cached = nv <= RETAIN_LDS;
     const float* ur = u_v + (size_t)row * nv;
     const int32_t* dr = death_v + (size_t)row * nv;
     const float thr = T >= pad ? tau_v[(size_t)row * nv + T] : -INFINITY;
@@ -224,30 +221,27 @@ __global__ __launch_bounds__(1024) void chunk_retain_kernel(const int32_t* __res
     int n1 = 0, n2 = 0;
     for (int e = tid; e < nv; e += 1024) {
         const int c = classify(e);
+        if (cached) cls[e] = (unsigned char)c;
         n1 += c == 1;
         n2 += c == 2;
     }
     int e1, e2, t1, t2;
-    block_scan2_1024(n1, n2, wt, e1, e2, t1, t2);
+    block_scan2_1024(n1, n2, wt, e1, e2, t1, t2);  // (its barriers also publish cls[])
     const int allowed = rcap - t1;        // >= 0: the mandatory classes hold at most k + w entries
     const int drop = t2 > allowed ? t2 - allowed : 0;  // the oldest `drop` members of class 2 go
-    if (tid == 0) {
-        newcount[row] = t1 + t2 - drop;
-        if (drop > 0) flags[row] |= 1;
-    }
     // second pass in position order: contiguous slices per thread keep the order
     const int per = (nv + 1023) / 1024;
     const int b0 = min(tid * per, nv), b1 = min(b0 + per, nv);
     int c1 = 0, c2 = 0;
     for (int e = b0; e < b1; e++) {
-        const int c = classify(e);
+        const int c = cached ? cls[e] : classify(e);
         c1 += c == 1;
         c2 += c == 2;
     }
     int p1, p2, u1, u2;
     block_scan2_1024(c1, c2, wt, p1, p2, u1, u2);
     for (int e = b0; e < b1; e++) {
-        const int c = classify(e);
+        const int c = cached ? cls[e] : classify(e);
         if (c == 0) continue;
         const bool keep = c == 1 || p2 >= drop;
         if (keep) {
@@ -255,13 +249,18 @@ __global__ __launch_bounds__(1024) void chunk_retain_kernel(const int32_t* __res
             const int j = p1 + kept2;
             map[(size_t)row * rcap + j] = e;
             ret_u[(size_t)row * rcap + j] = ur[e];
+            ret_sel[(size_t)row * rcap + j] = c == 1;
         }
         p1 += c == 1;
         p2 += c == 2;
     }
+    if (tid == 0) {  // every thread has read the old count (before the first scan's barriers)
+        count[row] = t1 + t2 - drop;
+        if (drop > 0) flags[row] |= 1;
+    }
 }
 
-__global__ __launch_bounds__(256) void chunk_retain_rows_kernel(const int32_t* __restrict__ newcount,
+__global__ __launch_bounds__(256) void chunk_retain_rows_kernel(const int32_t* __restrict__ count,
                                                                 const int32_t* __restrict__ map,
                                                                 const uint4* __restrict__ k_v,
                                                                 const uint4* __restrict__ v_v, int H, int Gu, int rcap,
@@ -271,7 +270,7 @@ __global__ __launch_bounds__(256) void chunk_retain_rows_kernel(const int32_t* _
     const int bh = blockIdx.y;
     const int b = bh / H, h = bh % H;
     const int row = b * Gu + (Gu == 1 ? 0 : h);
-    const size_t total = (size_t)newcount[row] * row16;
+    const size_t total = (size_t)count[row] * row16;
     for (size_t x = (size_t)blockIdx.x * 256 + threadIdx.x; x < total; x += (size_t)gridDim.x * 256) {
         const int j = (int)(x / row16), c16 = (int)(x % row16);
         const int e = map[(size_t)row * rcap + j];
@@ -280,12 +279,6 @@ __global__ __launch_bounds__(256) void chunk_retain_rows_kernel(const int32_t* _
         ret_k[dst] = k_v[src];
         ret_v[dst] = v_v[src];
     }
-}
-
-__global__ void chunk_commit_kernel(const int32_t* __restrict__ newcount, int32_t* __restrict__ count, int rows)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < rows) count[i] = newcount[i];
 }
 
 int launch_chunk_init(const sparsek_chunk_cfg& c, void* state, hipStream_t st)
@@ -317,34 +310,28 @@ int launch_chunk_prefill(const sparsek_chunk_cfg& c, void* state, int clen, cons
     float* tau_v = (float*)(w + W.tau);
     int32_t* death_v = (int32_t*)(w + W.death);
     int32_t* map = (int32_t*)(w + W.map);
-    int32_t* newcount = (int32_t*)(w + W.newcount);
     int32_t* first_valid = (int32_t*)(w + W.first);
-    uint4* q_v = (uint4*)(w + W.q);
     uint4* k_v = (uint4*)(w + W.k);
     uint4* v_v = (uint4*)(w + W.v);
-    uint4* o_v = (uint4*)(w + W.o);
     const sparsek_cfg cv = virtual_cfg(c, nv);
 
-    hipLaunchKernelGGL(chunk_assemble_scores_kernel, dim3(rows), dim3(256), 0, st, count, ret_u, u, L.rcap, clen, u_v,
+    hipLaunchKernelGGL(chunk_assemble_scores_kernel, dim3(rows), dim3(1024), 0, st, count, ret_u, u, L.rcap, clen, u_v,
                        first_valid);
     const int gx = (int)std::min<size_t>(((size_t)nv * row16 + 255) / 256, 2048);
-    hipLaunchKernelGGL(chunk_assemble_rows_kernel, dim3(gx, BH), dim3(256), 0, st, count, ret_k, ret_v, (const uint4*)q,
-                       (const uint4*)k, (const uint4*)v, c.H, c.Gu, L.rcap, clen, row16, q_v, k_v, v_v);
-    int rc = launch_mask(cv, u_v, tau_v, death_v, w + W.mask, st);
+    hipLaunchKernelGGL(chunk_assemble_rows_kernel, dim3(gx, BH), dim3(256), 0, st, count, ret_k, ret_v, (const uint4*)k,
+                       (const uint4*)v, c.H, c.Gu, L.rcap, clen, row16, k_v, v_v);
+    // thresholds are needed from prefix R_cap - w - 1 on (the last one the previous call used)
+    int rc = launch_mask(cv, u_v, tau_v, death_v, w + W.mask, st, std::max(0, L.rcap - c.w - 1));
     if (rc) return rc;
-    hipLaunchKernelGGL(chunk_clear_padding_kernel, dim3((L.rcap + 255) / 256, rows), dim3(256), 0, st, count, L.rcap, nv,
-                       death_v);
-    rc = launch_attn_fwd(cv, q_v, k_v, v_v, u_v, tau_v, death_v, o_v, nullptr, w + W.attn, st, L.rcap,
-                         first_valid);
+    hipLaunchKernelGGL(chunk_clear_padding_kernel, dim3((L.rcap + 255) / 256, rows), dim3(256), 0, st, count,
+                       (const int32_t*)(s + L.ret_sel), L.rcap, nv, death_v);
+    rc = launch_attn_fwd(cv, q, k_v, v_v, u_v, tau_v, death_v, o, nullptr, w + W.attn, st, L.rcap, first_valid, clen);
     if (rc) return rc;
-    const int go = (int)std::min<size_t>(((size_t)clen * row16 + 255) / 256, 2048);
-    hipLaunchKernelGGL(chunk_copy_out_kernel, dim3(go, BH), dim3(256), 0, st, o_v, L.rcap, clen, row16, (uint4*)o);
     hipLaunchKernelGGL(chunk_retain_kernel, dim3(rows), dim3(1024), 0, st, count, flags, u_v, tau_v, death_v, L.rcap,
-                       clen, c.w, map, newcount, ret_u);
+                       clen, c.w, map, ret_u, (int32_t*)(s + L.ret_sel));
     const int gr = (int)std::min<size_t>(((size_t)L.rcap * row16 + 255) / 256, 2048);
-    hipLaunchKernelGGL(chunk_retain_rows_kernel, dim3(gr, BH), dim3(256), 0, st, newcount, map, k_v, v_v, c.H, c.Gu,
+    hipLaunchKernelGGL(chunk_retain_rows_kernel, dim3(gr, BH), dim3(256), 0, st, count, map, k_v, v_v, c.H, c.Gu,
                        L.rcap, nv, row16, ret_k, ret_v);
-    hipLaunchKernelGGL(chunk_commit_kernel, dim3((rows + 255) / 256), dim3(256), 0, st, newcount, count, rows);
     return launch_status();
 }
 
@@ -372,16 +359,16 @@ int launch_chunk_to_decode(const sparsek_chunk_cfg& c, void* state, void* ws, co
     uint4* k_v = (uint4*)(w + W.k);
     uint4* v_v = (uint4*)(w + W.v);
     const sparsek_cfg cv = virtual_cfg(c, nv);
-    hipLaunchKernelGGL(chunk_assemble_scores_kernel, dim3(rows), dim3(256), 0, st, count, (const float*)(s + L.ret_u),
+    hipLaunchKernelGGL(chunk_assemble_scores_kernel, dim3(rows), dim3(1024), 0, st, count, (const float*)(s + L.ret_u),
                        (const float*)nullptr, L.rcap, 0, u_v, (int32_t*)(w + W.first));
     const int gx = (int)std::min<size_t>(((size_t)nv * row16 + 255) / 256, 2048);
     hipLaunchKernelGGL(chunk_assemble_rows_kernel, dim3(gx, BH), dim3(256), 0, st, count, (const uint4*)(s + L.ret_k),
-                       (const uint4*)(s + L.ret_v), (const uint4*)nullptr, (const uint4*)nullptr, (const uint4*)nullptr,
-                       c.H, c.Gu, L.rcap, 0, row16, (uint4*)(w + W.q), k_v, v_v);
-    int rc = launch_mask(cv, u_v, tau_v, death_v, w + W.mask, st);
+                       (const uint4*)(s + L.ret_v), (const uint4*)nullptr, (const uint4*)nullptr, c.H, c.Gu, L.rcap, 0,
+                       row16, k_v, v_v);
+    int rc = launch_mask(cv, u_v, tau_v, death_v, w + W.mask, st, std::max(0, L.rcap - c.w - 1));
     if (rc) return rc;
-    hipLaunchKernelGGL(chunk_clear_padding_kernel, dim3((L.rcap + 255) / 256, rows), dim3(256), 0, st, count, L.rcap, nv,
-                       death_v);
+    hipLaunchKernelGGL(chunk_clear_padding_kernel, dim3((L.rcap + 255) / 256, rows), dim3(256), 0, st, count,
+                       (const int32_t*)(s + L.ret_sel), L.rcap, nv, death_v);
     return launch_decode_load(dc, dstate, nv, k_v, v_v, u_v, tau_v, death_v, st);
 }
 

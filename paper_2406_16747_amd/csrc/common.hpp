@@ -10,15 +10,19 @@
 namespace spk {
 
 // Launch wrappers implemented in the .hip files; all return a SPARSEK_* code.
+// t_begin > 0: thresholds of prefixes before t_begin are not needed and deaths that fall before it are left at
+// their preset (chunked prefill); the 128-prefix blocks that end at or before t_begin are skipped.
 int launch_mask(const sparsek_cfg& c, const float* u, float* tau, int32_t* death, void* ws,
-                hipStream_t st);
+                hipStream_t st, int t_begin = 0);
 size_t mask_ws_bytes(const sparsek_cfg& c);
 int launch_materialize(const sparsek_cfg& c, const float* u, const float* tau, const int32_t* death,
                        int t_begin, int t_end, int32_t* idx, float* gate, hipStream_t st);
 int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const void* v,
                     const float* u, const float* tau, const int32_t* death, void* o, float* lse,
-                    void* ws, hipStream_t st, int q_begin = 0, const int32_t* first_valid = nullptr);
-// (query blocks that end at or before q_begin are skipped; keys before first_valid[row] are never attended)
+                    void* ws, hipStream_t st, int q_begin = 0, const int32_t* first_valid = nullptr,
+                    int q_rows = 0);
+// (query blocks that end at or before q_begin are skipped; keys before first_valid[row] are never attended;
+//  q_rows != 0: q and o hold q_rows rows per head, the first being query q_begin, a multiple of 128; lse unused)
 size_t attn_fwd_ws_bytes(const sparsek_cfg& c);
 int launch_mask_bwd(const sparsek_cfg& c, const void* q, const void* k, const void* v,
                     const float* u, const float* tau, const int32_t* death, const void* o,

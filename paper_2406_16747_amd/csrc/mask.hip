@@ -917,7 +917,7 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
                                                                const float* __restrict__ lo_in,
                                                                float* __restrict__ tau,
                                                                int32_t* __restrict__ death, int n, int k,
-                                                               int nsuper, int* __restrict__ status)
+                                                               int nsuper, int* __restrict__ status, int t_begin)
 {
     __shared__ __align__(16) unsigned long long skey[CAP];
     __shared__ __align__(16) double pref[CAP + 1];
@@ -933,6 +933,7 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int t0 = c * CHUNK, t1 = min(n, t0 + CHUNK);
     if (t1 <= k) return;  // no prefix here is longer than k: tau is written elsewhere, nothing dies
+    if (t1 <= t_begin) return;  // the caller needs neither these thresholds nor the deaths that fall here
     const float* ur = u + (size_t)row * n;
     float* tr = tau + (size_t)row * n;
     int32_t* dr = death + (size_t)row * n;
@@ -1059,7 +1060,7 @@ __global__ __launch_bounds__(256) void materialize_kernel(const float* __restric
 }
 
 int launch_mask(const sparsek_cfg& c, const float* u, float* tau, int32_t* death, void* ws,
-                hipStream_t st)
+                hipStream_t st, int t_begin)
 {
     const int rows = c.B * c.Gu;
     const int nsuper = (c.n + SUPER - 1) / SUPER;
@@ -1071,7 +1072,7 @@ int launch_mask(const sparsek_cfg& c, const float* u, float* tau, int32_t* death
     if (c.k < c.n) {
         const int nchunks = (c.n + CHUNK - 1) / CHUNK;
         hipLaunchKernelGGL(mask_chunk_kernel, dim3(nchunks, rows), dim3(NT_CHUNK), 0, st, u, lo, tau, death,
-                           c.n, c.k, nsuper, status);
+                           c.n, c.k, nsuper, status, t_begin);
     }
     return launch_status();
 }
