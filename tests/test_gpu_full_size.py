@@ -148,3 +148,38 @@ def test_config5_full_decode(oracle):
         err = np.abs(got - ref).max()
         scale = np.abs(ref).max()
         assert err <= 1e-2 and err <= scale * 2.0 ** -7, (b, h, err, scale)
+
+
+def test_chunked_prefill_at_bench_shape(oracle):
+    """The chunk leg of bench.py (H=32 d=128 k=w=1024, chunks of 8192) over a 32K sequence: sampled
+    query spans of two heads against the oracle's attention on the whole sequence; the retained set
+    stays within its capacity, far below the sequence length."""
+    require_gpu()
+    say("chunked prefill at the bench shape: H=32 n=32768 d=128 k=w=1024, chunks of 8192")
+    B, H, n, d, k, w, c = 1, 32, 32768, 128, 1024, 1024, 8192
+    g = torch.Generator(device="cuda")
+    g.manual_seed(2204)
+    div = math.sqrt(d)
+    q, kk, v = ((torch.randn(B, H, n, d, device="cuda", generator=g) / div).bfloat16() for _ in range(3))
+    u = torch.randn(B, 1, n, device="cuda", generator=g)
+    st = spk.ChunkState(B, H, 1, d, k, w, spk.BF16, c, 0, 1.0)
+    outs = []
+    for p in range(0, n, c):
+        outs.append(spk.sparsek_chunk_prefill(st, q[:, :, p:p + c].contiguous(), kk[:, :, p:p + c].contiguous(),
+                                              v[:, :, p:p + c].contiguous(), u[:, :, p:p + c].contiguous()))
+    o = torch.cat(outs, 2)
+    torch.cuda.synchronize()
+    counts, flags = spk.sparsek_chunk_status(st)
+    assert not flags.any() and counts.max() < 6144
+    u_np = host(u)
+    tau_r = oracle.tau_prefixes(u_np[0, 0], k)[0]
+    death_r = oracle.death(u_np[0, 0], k)
+    for h in (3, 30):
+        o_g = host(o[0, h])
+        q32, k32, v32 = host(q[0, h]), host(kk[0, h]), host(v[0, h])
+        for (a, e) in [(0, 150), (8100, 8300), (16384, 16500), (24500, 24600), (32700, n)]:
+            o_r, _ = oracle.attn_rows(q32, k32, v32, u_np[0, 0], tau_r, death_r, k, w, 0, 1.0, a, e)
+            err = np.abs(o_g[a:e] - o_r).max()
+            ref = np.abs(o_r).max()
+            assert err <= 1e-2 and err <= ref * 2.0 ** -7 + 1e-6, (h, a, err, ref)
+
