@@ -58,4 +58,24 @@ def test_argument_validation_needs_no_gpu():
     # gate modes 0..3 are valid, 4 is not
     bad = spk.SparsekCfg(B=1, H=2, Gu=1, n=16, d=64, k=4, w=4, dtype=spk.BF16, gate_mode=4, softmax_scale=1.0)
     assert L.sparsek_attn_fwd(ctypes.byref(bad), *([one] * 8), one, 1 << 20, null) == -1
+    # chunk-wise recurrent prefill
+    from paper_2406_16747_amd.binding import SparsekChunkCfg, SparsekDecodeCfg
+
+    cc = SparsekChunkCfg(B=1, H=2, Gu=1, d=64, k=8, w=8, cand_cap=0, chunk_max=256, dtype=spk.BF16, gate_mode=0,
+                         softmax_scale=1.0)
+    sb, wb = L.sparsek_chunk_state_bytes(ctypes.byref(cc)), L.sparsek_chunk_workspace_bytes(ctypes.byref(cc))
+    assert sb > 0 and wb > 0
+    assert L.sparsek_chunk_init(ctypes.byref(cc), null, sb, null) == -1
+    assert L.sparsek_chunk_init(ctypes.byref(cc), one, 8, null) == -3
+    assert L.sparsek_chunk_prefill(ctypes.byref(cc), one, sb, 0, one, one, one, one, one, one, wb, null) == -1  # c < 1
+    assert L.sparsek_chunk_prefill(ctypes.byref(cc), one, sb, 257, one, one, one, one, one, one, wb, null) == -1  # c > chunk_max
+    assert L.sparsek_chunk_prefill(ctypes.byref(cc), one, sb, 16, one, one, one, one, one, one, 8, null) == -3
+    bad = SparsekChunkCfg(B=1, H=2, Gu=1, d=4, k=8, w=8, cand_cap=0, chunk_max=256, dtype=spk.BF16, gate_mode=0,
+                          softmax_scale=1.0)
+    assert L.sparsek_chunk_state_bytes(ctypes.byref(bad)) == 0  # rows of 8 bytes: not a multiple of 16
+    dc = SparsekDecodeCfg(B=1, H=2, Gu=1, d=64, k=8, w=8, cand_cap=0, dtype=spk.BF16, gate_mode=0, softmax_scale=1.0)
+    db = L.sparsek_decode_state_bytes(ctypes.byref(dc))
+    assert L.sparsek_chunk_to_decode(ctypes.byref(cc), one, sb, 15, one, wb, ctypes.byref(dc), one, db, null) == -2  # < k + w
+    dc.k = 9
+    assert L.sparsek_chunk_to_decode(ctypes.byref(cc), one, sb, 100, one, wb, ctypes.byref(dc), one, db, null) == -1
 
