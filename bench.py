@@ -390,6 +390,38 @@ def main():
         torch.cuda.synchronize()
         gm[str(mode)] = e0.elapsed_time(e1) / 10
     out["attn_ms_by_gate_mode"] = gm
+
+    # variants at the same shape: one score row per head (Gu = H), and selection only (w = 0, k = 2048)
+    def step_ms(uu, kk_sel, ww, iters=10):
+        wsx = None
+        for i in range(3 + iters):
+            if i == 3:
+                torch.cuda.synchronize()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+            if i == 3 + iters - 1:
+                m0.record()
+            t2, d2 = spk.sparsek_mask(uu, kk_sel)
+            if i == 3 + iters - 1:
+                m1.record()
+            spk.sparsek_attn_fwd(q, k, v, uu, t2, d2, kk_sel, ww, 0, 1.0, return_lse=True, ws=wsx)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / iters, m0.elapsed_time(m1)
+
+    gq = torch.Generator(device="cuda")
+    gq.manual_seed(1204)
+    u_heads = torch.randn(cfg["B"], cfg["H"], cfg["n"], device="cuda", generator=gq)
+    ms_h, mask_h = step_ms(u_heads, cfg["k"], cfg["w"])
+    ms_w0, mask_w0 = step_ms(u, 2 * cfg["k"], 0)
+    out["variants"] = {
+        "per_head_selection": {"workload": "config 4 shape with Gu=H (32 score rows)", "ms_per_step": ms_h,
+                               "mask_ms": mask_h, "tokens_per_s": cfg["B"] * cfg["n"] / (ms_h * 1e-3)},
+        "selection_only": {"workload": "config 4 shape with w=0, k=2048", "ms_per_step": ms_w0, "mask_ms": mask_w0,
+                           "tokens_per_s": cfg["B"] * cfg["n"] / (ms_w0 * 1e-3)},
+    }
+    del u_heads
     del q, k, v, ws
     torch.cuda.empty_cache()
     if not args.no_bwd:
