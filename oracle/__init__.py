@@ -15,6 +15,7 @@ from .ref import (  # noqa: F401
     attn_rows,
     attn_fwd,
     mask_bwd,
+    attn_bwd,
     mask_all,
     decode_bydef,
     max_threads,

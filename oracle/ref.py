@@ -174,6 +174,21 @@ def mask_bwd(q, K, V, u, tau, dth, dO, k, w, gate_mode, scale, nthreads=0):
     return du, used
 
 
+def attn_bwd(q, K, V, u, tau, dth, dO, k, w, gate_mode, scale, nthreads=0):
+    """dQ, dK, dV [B,H,n,d] fp64 of L = sum(dO*O), the gates held fixed (their gradient is mask_bwd)."""
+    q, K, V, u, dO = _f32(q), _f32(K), _f32(V), _f32(u), _f32(dO)
+    tau, dth = _f64(tau), _i32(dth)
+    B, H, n, d = q.shape
+    Gu = u.shape[1]
+    dQ, dK, dV = (np.empty((B, H, n, d), np.float64) for _ in range(3))
+    used = _L().orc_attn_bwd(
+        _p(q), _p(K), _p(V), _p(u), _p(tau), _p(dth), _p(dO), B, H, Gu, n, d, int(k), int(w),
+        int(gate_mode), C.c_double(scale), _p(dQ), _p(dK), _p(dV), int(nthreads),
+    )
+    assert used > 0
+    return dQ, dK, dV
+
+
 def decode_bydef(q_steps, K_hist, V_hist, u_hist, n_ctx, k, w, gate_mode, scale):
     """Decode by definition for one head: the output of the step that appends position t
     is row t of the prefill attention over the whole history (the chunk-recurrence

@@ -425,6 +425,83 @@ int orc_mask_bwd(const float *q, const float *K, const float *V, const float *u,
 }
 
 /* ------------------------------------------------------------------------- */
+/* Gradient of L = sum(dO * O) with respect to q, k, v (the gates held fixed)   */
+/* ------------------------------------------------------------------------- */
+
+/* One head: plain backward of the selected-attention equations of Sec. 3.2 with the gating
+ * variants.  With s_j = scale gk_j (q.k_j), p = softmax(s), o = sum_j p_j gv_j v_j and D = dO.o:
+ *   dV_j += p_j gv_j dO,   dp_j = gv_j (dO.v_j),   ds_j = p_j (dp_j - D),
+ *   dq   += ds_j scale gk_j k_j,   dK_j += ds_j scale gk_j q.
+ * The scores enter only through the gates, whose gradient is orc_mask_bwd's business.
+ * dQ, dK, dV [n,d] are accumulated into. */
+int orc_attn_bwd_head(const float *q, const float *K, const float *V, const float *u, const double *tau,
+                      const int32_t *death, const float *dO, int n, int d, int k, int w, int gate_mode,
+                      double scale, double *dQ, double *dK, double *dV)
+{
+    if (k < 0 || w < 0 || k + w < 1) return -1;
+    int *keys = (int *)malloc(sizeof(int) * (size_t)(n + 1));
+    double *gates = (double *)malloc(sizeof(double) * (size_t)(n + 1));
+    double *p = (double *)malloc(sizeof(double) * (size_t)(n + 1));
+    double *qk = (double *)malloc(sizeof(double) * (size_t)(n + 1));
+    double *o = (double *)malloc(sizeof(double) * (size_t)d);
+    for (int i = 0; i < n; i++) {
+        int nk = build_keys(u, tau, death, i, k, w, keys, gates);
+        const float *qi = q + (size_t)i * d;
+        const float *dOi = dO + (size_t)i * d;
+        attend_list(qi, K, V, d, keys, gates, nk, gate_mode, scale, o, NULL, p, qk);
+        double D = 0.0;
+        for (int c = 0; c < d; c++) D += (double)dOi[c] * o[c];
+        for (int a = 0; a < nk; a++) {
+            int j = keys[a];
+            double gk = (gate_mode == 0) ? gates[a] : 1.0;
+            double gv = (gate_mode == 2 || gate_mode == 3) ? 1.0 : gates[a];
+            const float *kj = K + (size_t)j * d;
+            const float *vj = V + (size_t)j * d;
+            double dov = 0.0;
+            for (int c = 0; c < d; c++) dov += (double)dOi[c] * (double)vj[c];
+            double ds = p[a] * (gv * dov - D);
+            double coef = ds * scale * gk;
+            for (int c = 0; c < d; c++) {
+                dV[(size_t)j * d + c] += p[a] * gv * (double)dOi[c];
+                dQ[(size_t)i * d + c] += coef * (double)kj[c];
+                dK[(size_t)j * d + c] += coef * (double)qi[c];
+            }
+        }
+    }
+    free(keys); free(gates); free(p); free(qk); free(o);
+    return 0;
+}
+
+/* All heads; dQ, dK, dV [B,H,n,d] fp64 are zeroed first. */
+int orc_attn_bwd(const float *q, const float *K, const float *V, const float *u, const double *tau,
+                 const int32_t *death, const float *dO, int B, int H, int Gu, int n, int d, int k,
+                 int w, int gate_mode, double scale, double *dQ, double *dK, double *dV, int nthreads)
+{
+    if (B < 1 || H < 1 || (Gu != 1 && Gu != H)) return -1;
+    size_t tot = (size_t)B * H * n * d;
+    memset(dQ, 0, sizeof(double) * tot);
+    memset(dK, 0, sizeof(double) * tot);
+    memset(dV, 0, sizeof(double) * tot);
+    int used = 1;
+#ifdef _OPENMP
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+    used = nthreads > 0 ? nthreads : omp_get_max_threads();
+#endif
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < B * H; bh++) {
+        int b = bh / H, h = bh % H;
+        int g = (Gu == 1) ? 0 : h;
+        size_t row = ((size_t)b * Gu + g) * (size_t)n;
+        size_t off = (size_t)bh * n * d;
+        int rc = orc_attn_bwd_head(q + off, K + off, V + off, u + row, tau + row, death + row, dO + off, n, d,
+                                   k, w, gate_mode, scale, dQ + off, dK + off, dV + off);
+        if (rc) bad = 1;
+    }
+    return bad ? -1 : used;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Importance scores: scoring network + position slope (Sec. 3.2, Eq. for u),  */
 /* optional timestep normalisation (Sec. 3.5, "score normalization")           */
 /* ------------------------------------------------------------------------- */

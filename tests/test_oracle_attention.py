@@ -332,3 +332,49 @@ def test_du_zero_without_fractional_gates_and_in_mode2(oracle):
         frac = any(tau[0, 0, T] < u[0, 0, j] < tau[0, 0, T] + 1 for T in range(j, n - w))
         if not frac:
             assert du[0, 0, j] == 0
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+def test_qkv_gradients_match_finite_differences(oracle, mode):
+    """dQ, dK, dV against central differences of the oracle's own forward (the scores, hence the
+    gates, are held fixed)."""
+    rng = np.random.default_rng(40 + mode)
+    B, H, n, d, kk, w = 1, 2, 14, 3, 4, 3
+    h = 2.0 ** -12
+    q, k, v, dO = (rng.standard_normal((B, H, n, d)).astype(np.float32) for _ in range(4))
+    u = rng.standard_normal((1, 1, n)).astype(np.float32)
+    tau, dth = oracle.mask_all(u, kk)
+    dQ, dK, dV = oracle.attn_bwd(q, k, v, u, tau, dth, dO, kk, w, mode, 0.7, nthreads=1)
+
+    def loss(qq, kx, vx):
+        o, _, _ = oracle.attn_fwd(qq, kx, vx, u, tau, dth, kk, w, mode, 0.7, nthreads=1)
+        return float((o * dO).sum())
+
+    for which, grad in (("q", dQ), ("k", dK), ("v", dV)):
+        for idx in [(0, 0, 0, 0), (0, 1, 5, 2), (0, 0, 9, 1), (0, 1, 13, 0), (0, 0, 3, 2)]:
+            args = {"q": q, "k": k, "v": v}
+            xp, xm = args[which].copy(), args[which].copy()
+            xp[idx] += np.float32(h)
+            xm[idx] -= np.float32(h)
+            ap, am = dict(args), dict(args)
+            ap[which], am[which] = xp, xm
+            fd = (loss(ap["q"], ap["k"], ap["v"]) - loss(am["q"], am["k"], am["v"])) / (2 * h)
+            assert grad[idx] == pytest.approx(fd, abs=5e-6, rel=5e-5), (which, idx)
+
+
+def test_qkv_gradients_dense_limit_against_autograd(oracle):
+    """k >= n: plain causal attention, whose gradients torch's autograd gives (fp64, CPU)."""
+    rng = np.random.default_rng(44)
+    n, d = 24, 5
+    q, k, v, dO = (rng.standard_normal((1, 1, n, d)).astype(np.float32) for _ in range(4))
+    u = rng.standard_normal((1, 1, n)).astype(np.float32)
+    tau, dth = oracle.mask_all(u, n + 3)
+    dQ, dK, dV = oracle.attn_bwd(q, k, v, u, tau, dth, dO, n + 3, 4, 0, 0.5)
+    tq, tk, tv = (torch.from_numpy(x[0, 0]).double().requires_grad_(True) for x in (q, k, v))
+    mask = torch.tril(torch.ones(n, n, dtype=torch.bool))
+    o = torch.nn.functional.scaled_dot_product_attention(tq[None], tk[None], tv[None], attn_mask=mask[None], scale=0.5)
+    (o[0] * torch.from_numpy(dO[0, 0]).double()).sum().backward()
+    np.testing.assert_allclose(dQ[0, 0], tq.grad.numpy(), rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(dK[0, 0], tk.grad.numpy(), rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(dV[0, 0], tv.grad.numpy(), rtol=1e-9, atol=1e-11)
+
