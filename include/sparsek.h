@@ -105,6 +105,20 @@ int sparsek_mask_bwd(const sparsek_cfg *cfg, const void *q, const void *k, const
                      const float *lse, const void *dO, float *du, void *ws, size_t ws_bytes,
                      void *stream);
 
+/* ---- attention backward: gradients with respect to q, k, v (selected-attention equations of Sec. 3.2) ----
+ * dq, dk, dv out [B,H,n,d] of cfg->dtype: gradient of L = sum(dO * O) with the gates held fixed; the gradient that
+ * flows through the gates to the scores is sparsek_mask_bwd.  With s_ij = scale gk_ij (q_i.k_j), p = softmax_j(s),
+ * o_i = sum_j p_ij gv_ij v_j and D_i = dO_i.o_i:
+ *     dv_j = sum_i p_ij gv_ij dO_i,   ds_ij = p_ij (gv_ij dO_i.v_j - D_i),
+ *     dq_i = sum_j ds_ij scale gk_ij k_j,   dk_j = sum_i ds_ij scale gk_ij q_i
+ * (gk / gv: the gate where gate_mode puts it, else 1; gate_mode 3 differentiates its hard forward, like mode 2).
+ * o, lse in: outputs of sparsek_attn_fwd on the same inputs and gate_mode; dO in [B,H,n,d] of cfg->dtype.
+ * ws: scratch of at least sparsek_attn_bwd_workspace_bytes(cfg) bytes (block lists, D_i, fp32 accumulators of dk, dv). */
+size_t sparsek_attn_bwd_workspace_bytes(const sparsek_cfg *cfg);
+int sparsek_attn_bwd(const sparsek_cfg *cfg, const void *q, const void *k, const void *v, const float *u,
+                     const float *tau, const int32_t *death, const void *o, const float *lse, const void *dO,
+                     void *dq, void *dk, void *dv, void *ws, size_t ws_bytes, void *stream);
+
 /* ---- importance scores (Sec. 3.2 scoring network with position slope; Sec. 3.5 score normalisation) ----
  * u out [B,n] fp32, one row per sequence (the single score group of the paper; feed it to sparsek_mask with Gu = 1):
  *     raw_t = x_t . w + t * slope        (t counted from 0),

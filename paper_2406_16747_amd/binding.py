@@ -50,13 +50,15 @@ def lib():
         L.sparsek_strerror.restype = C.c_char_p
         L.sparsek_strerror.argtypes = [C.c_int]
         for name in ("sparsek_mask_workspace_bytes", "sparsek_attn_fwd_workspace_bytes",
-                     "sparsek_mask_bwd_workspace_bytes"):
+                     "sparsek_mask_bwd_workspace_bytes", "sparsek_attn_bwd_workspace_bytes"):
             getattr(L, name).restype = sz
             getattr(L, name).argtypes = [cfgp]
         L.sparsek_mask.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
         L.sparsek_materialize.argtypes = [cfgp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.sparsek_attn_fwd.argtypes = [cfgp] + [vp] * 8 + [vp, sz, vp]
         L.sparsek_mask_bwd.argtypes = [cfgp] + [vp] * 10 + [vp, sz, vp]
+        L.sparsek_attn_bwd.argtypes = [cfgp] + [vp] * 12 + [vp, sz, vp]
+        L.sparsek_attn_bwd.restype = C.c_int
         scfgp = C.POINTER(SparsekScoresCfg)
         L.sparsek_scores_workspace_bytes.restype = sz
         L.sparsek_scores_workspace_bytes.argtypes = [scfgp]
@@ -187,6 +189,18 @@ def sparsek_mask_bwd(q, k, v, u, tau, death, o, lse, dO, k_sel, w, gate_mode=0, 
     check(lib().sparsek_mask_bwd(C.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(u), _ptr(tau), _ptr(death),
                                  _ptr(o), _ptr(lse), _ptr(dO), _ptr(du), _ptr(ws), ws.numel(), _stream()))
     return du
+
+
+def sparsek_attn_bwd(q, k, v, u, tau, death, o, lse, dO, k_sel, w, gate_mode=0, scale=1.0, ws=None):
+    """dq, dk, dv [B,H,n,d]: gradients of sum(dO*O) with respect to q, k, v (gates held fixed)."""
+    torch = _torch()
+    cfg = _attn_cfg(q, u, k_sel, w, gate_mode, scale)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    if ws is None:
+        ws = _ws(lib().sparsek_attn_bwd_workspace_bytes(C.byref(cfg)), q.device)
+    check(lib().sparsek_attn_bwd(C.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(u), _ptr(tau), _ptr(death), _ptr(o),
+                                 _ptr(lse), _ptr(dO), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(), _stream()))
+    return dq, dk, dv
 
 
 def sparsek_scores(x, w, slope=0.0, norm=False, norm_eps=1e-5, ws=None):

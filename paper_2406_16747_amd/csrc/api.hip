@@ -91,6 +91,38 @@ int sparsek_attn_fwd(const sparsek_cfg* cfg, const void* q, const void* k, const
 
 }  // extern "C"
 
+// ---- attention backward (attn_bwd.hip) ----
+namespace spk {
+size_t attn_bwd_ws_bytes(const sparsek_cfg& c);
+int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
+                    const float* tau, const int32_t* death, const void* o, const float* lse, const void* dO, void* dq,
+                    void* dk, void* dv, void* ws, hipStream_t st);
+}  // namespace spk
+
+extern "C" {
+
+size_t sparsek_attn_bwd_workspace_bytes(const sparsek_cfg* cfg)
+{
+    if (check_attn(cfg)) return 0;
+    return spk::attn_bwd_ws_bytes(*cfg);
+}
+
+int sparsek_attn_bwd(const sparsek_cfg* cfg, const void* q, const void* k, const void* v, const float* u,
+                     const float* tau, const int32_t* death, const void* o, const float* lse, const void* dO, void* dq,
+                     void* dk, void* dv, void* ws, size_t ws_bytes, void* stream)
+{
+    int rc = check_attn(cfg);
+    if (rc) return rc;
+    if (!q || !k || !v || !u || !tau || !death || !o || !lse || !dO || !dq || !dk || !dv || !ws)
+        return SPARSEK_ERR_INVALID_ARG;
+    if (ws_bytes < spk::attn_bwd_ws_bytes(*cfg)) return SPARSEK_ERR_WORKSPACE;
+    sparsek_cfg c = *cfg;
+    if (c.gate_mode == 3) c.gate_mode = 2;  // the straight-through forward has no gates on q, k, v
+    return spk::launch_attn_bwd(c, q, k, v, u, tau, death, o, lse, dO, dq, dk, dv, ws, (hipStream_t)stream);
+}
+
+}  // extern "C"
+
 // ---- importance scores (scores.hip) ----
 namespace spk {
 size_t scores_ws_bytes(int B, int n);

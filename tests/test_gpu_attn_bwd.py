@@ -1,0 +1,62 @@
+"""GPU parity of sparsek_attn_bwd (gradients with respect to q, k, v) against the CPU oracle.
+
+Bars: |g - ref| <= 1e-2 max|ref| per tensor for bf16 storage (outputs are rounded to bf16, the
+stored bf16 O enters D = dO.O with relative error 2^-9), <= 2e-4 max|ref| for fp32.  The gates are
+functions of (u, tau): the oracle is fed the GPU's fp32 thresholds, checked to 1e-5 elsewhere.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2406_16747_amd as spk
+from paper_2406_16747_amd import synth
+from gpu_util import dev, host, require_gpu, say
+
+pytestmark = pytest.mark.gpu
+
+
+def run_bwd(oracle, inp, gate_mode, heads=None):
+    B, H, n, d, k, w, Gu = (inp[x] for x in ("B", "H", "n", "d", "k", "w", "Gu"))
+    bf16 = inp["dtype"] == "bf16"
+    u = dev(inp["u"])
+    Q, K, V, dO = (dev(inp[x], bf16) for x in ("Q", "K", "V", "dO"))
+    tau, death = spk.sparsek_mask(u, k)
+    o, lse = spk.sparsek_attn_fwd(Q, K, V, u, tau, death, k, w, gate_mode, inp["scale"])
+    dq, dk, dv = spk.sparsek_attn_bwd(Q, K, V, u, tau, death, o, lse, dO, k, w, gate_mode, inp["scale"])
+    torch.cuda.synchronize()
+    got = [host(x) for x in (dq, dk, dv)]
+    ref = oracle.attn_bwd(inp["Q32"], inp["K32"], inp["V32"], inp["u"], host(tau).astype(np.float64), host(death),
+                          inp["dO32"], k, w, gate_mode, inp["scale"])
+    worst = 0.0
+    common = max(np.abs(r).max() for r in ref)
+    for name, g, r in zip(("dq", "dk", "dv"), got, ref):
+        assert np.isfinite(g).all(), name
+        # a tensor whose exact gradient (nearly) vanishes, e.g. dq with a single key, is held to the others' scale
+        scale = max(np.abs(r).max(), 1e-3 * common)
+        err = np.abs(g - r).max()
+        tol = (1e-2 if bf16 else 2e-4) * scale
+        assert err <= tol + 1e-30, (name, err, scale, np.unravel_index(np.abs(g - r).argmax(), g.shape))
+        worst = max(worst, err / max(scale, 1e-30))
+    return worst
+
+
+@pytest.mark.parametrize("n,d,k,w,Gu,dtype", [
+    (200, 64, 12, 9, 1, "bf16"), (333, 128, 20, 0, 1, "bf16"), (520, 64, 30, 40, 2, "bf16"),
+    (300, 32, 10, 7, 2, "fp32"), (90, 64, 100, 5, 1, "bf16"), (150, 64, 0, 5, 1, "bf16"), (64, 64, 3, 70, 1, "bf16"),
+    (1, 64, 4, 4, 1, "bf16"), (257, 128, 16, 16, 1, "fp32"),
+])
+@pytest.mark.parametrize("gate_mode", [0, 1, 2, 3])
+def test_attn_bwd_small(oracle, n, d, k, w, Gu, dtype, gate_mode):
+    require_gpu()
+    say("attn_bwd", n, d, k, w, Gu, dtype, gate_mode)
+    inp = synth.make(3, Gu=Gu, seed=n + k, with_dO=True, B=2, H=2, n=n, d=d, k=k, w=w, dtype=dtype,
+                     qk_div=float(np.sqrt(d)) / 4)
+    run_bwd(oracle, inp, gate_mode)
+
+
+def test_attn_bwd_config3_recipe_reduced(oracle):
+    """Config 3 recipe (drifting scores, k=w=512 at n=8192 scaled down 4x), one batch, 2 heads."""
+    require_gpu()
+    say("attn_bwd config 3 reduced")
+    inp = synth.make(3, with_dO=True, B=1, H=2, n=2048, k=128, w=128)
+    run_bwd(oracle, inp, 0)
