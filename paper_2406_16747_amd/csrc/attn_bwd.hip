@@ -165,10 +165,223 @@ __global__ __launch_bounds__(256) void attn_bwd_generic_kernel(
                 }
             }
         }
-        if (lane < d) stg(dq + hb + (size_t)i * d + lane, dq0);
-        if (lane + 64 < d) stg(dq + hb + (size_t)i * d + lane + 64, dq1);
+        if (dq) {  // null: dQ comes from the MFMA kernel
+            if (lane < d) stg(dq + hb + (size_t)i * d + lane, dq0);
+            if (lane + 64 < d) stg(dq + hb + (size_t)i * d + lane + 64, dq1);
+        }
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     }
+}
+
+// ---------------------------------------------------------------------------------
+// MFMA kernel for dQ (bf16, D = 64 or 128).  Same blocking as the forward: 128 queries x 4 waves,
+// 64-key tiles (the block's top-k list, then the contiguous keys up to the block's last query)
+// gathered straight into LDS.  Per 32-key half: S^T = K.Q^T and DV^T = V.dO^T (row reads), the
+// elementwise step to ds_ij scale gk_ij in bf16, then dQ^T += K^T.dS^T with K^T read through
+// transposing LDS loads.  Row reads and transposing reads want different paddings of the tile, so K
+// lands in LDS twice (a second direct-to-LDS load of rows that are in cache by then); the tile is
+// single-buffered and the two workgroups of a CU cover each other's gathers.
+// ---------------------------------------------------------------------------------
+template <int D>
+struct DqSmem {
+    using S = MfmaSmem<D, 64>;
+    unsigned char kr[S::NL * S::GSK];  // K rows, padded for row reads
+    unsigned char kt[S::NL * S::GSV];  // K rows, padded for transposing reads
+    unsigned char vr[S::NL * S::GSK];  // V rows, padded for row reads
+    int32_t jpos[SEG];
+    int32_t jlast[SEG];  // last query that attends the key: w - 1 + death[j]; -1 = filler
+    float ju[SEG];
+};
+
+template <int D, int MODE>
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ kk, const uint16_t* __restrict__ v,
+    const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
+    const int32_t* __restrict__ lists, const int32_t* __restrict__ counts, const float* __restrict__ lse,
+    const uint16_t* __restrict__ dO, const float* __restrict__ delta, uint16_t* __restrict__ dq, int H, int Gu, int n,
+    int k, int w, float scale, int nb, int BH)
+{
+    using S = MfmaSmem<D, 64>;
+    __shared__ __align__(16) DqSmem<D> sm;
+    constexpr int DS = D / 16, DB = D / 32, NX = S::NL / 4, LPR = S::RB / 16;
+    int bh, blk;
+    {
+        const int id = blockIdx.x;
+        if (BH % 8 == 0) {
+            const int xcd = id & 7, slot = id >> 3;
+            bh = (slot / nb) * 8 + xcd;
+            blk = nb - 1 - (slot % nb);
+        } else {
+            bh = id / nb;
+            blk = nb - 1 - (id % nb);
+        }
+    }
+    const int b = bh / H, h = bh % H;
+    const int row = b * Gu + (Gu == 1 ? 0 : h);
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, col = lane & 31;
+    const int i0 = blk * QB;
+    const unsigned char* kh = (const unsigned char*)(kk + (size_t)bh * n * D);
+    const unsigned char* vh = (const unsigned char*)(v + (size_t)bh * n * D);
+    const float* ur = u + (size_t)row * n;
+    const float* tr = tau + (size_t)row * n;
+    const int32_t* dr = death + (size_t)row * n;
+    const int32_t* list = lists + ((size_t)row * nb + blk) * (size_t)(k > 0 ? k : 1);
+    const int cnt = counts[(size_t)row * nb + blk];
+    const int c0 = max(0, i0 - w + 1);
+    const int c_end = min(n - 1, i0 + QB - 1);
+    const int nkl = (cnt + KT - 1) / KT * KT;
+    const int nkc = (c_end - c0 + 1 + KT - 1) / KT * KT;
+    const int nk_total = nkl + nkc;
+
+    const int qa = i0 + 32 * wv;
+    const int qi = qa + col;
+    const int qrow = min(qi, n - 1);
+    const bool wave_live = qa < n;
+    const int qv = qi < n ? qi : -1;  // -1: no key passes "j <= query"
+    const float tau_q = (qi < n && qi - w >= 0) ? tr[qi - w] : 0.0f;
+    const float lse2 = lse[(size_t)bh * n + qrow] * 1.4426950408889634f;
+    const float Di = delta[(size_t)bh * n + qrow];
+    bf16x8 qreg[DS], dreg[DS];
+#pragma unroll
+    for (int s = 0; s < DS; s++) {
+        const size_t off = ((size_t)bh * n + qrow) * D + 16 * s + 8 * half;
+        qreg[s] = *(const bf16x8*)(q + off);
+        dreg[s] = *(const bf16x8*)(dO + off);
+    }
+    f32x16 acc_q[DB];
+#pragma unroll
+    for (int x = 0; x < DB; x++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc_q[x][r] = 0.0f;
+    const float c2 = scale * 1.4426950408889634f;
+
+    // transposing reads of K^T (see the forward's V^T operand): lane -> (row, column block)
+    const int r16 = lane & 15, grp2 = (lane >> 4) & 1;
+    const int tcol = (16 * grp2 + 4 * (r16 & 3)) * 2;
+    const int trow = 4 * half + (r16 >> 2);
+    auto kt_operand = [&](int g, int x) -> bf16x8 {
+        const int row0 = 16 * g + trow, row1 = row0 + 8;
+        const unsigned char* p0 = sm.kt + (row0 % S::NL) * S::GSV + (row0 / S::NL) * S::RB + tcol + 64 * x;
+        const unsigned char* p1 = sm.kt + (row1 % S::NL) * S::GSV + (row1 / S::NL) * S::RB + tcol + 64 * x;
+        const i16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)p0);
+        const i16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)p1);
+        const bf16x4 lo = __builtin_bit_cast(bf16x4, lo4), hi = __builtin_bit_cast(bf16x4, hi4);
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+
+    for (int seg0 = 0; seg0 < nk_total; seg0 += SEG) {
+        const int seg_n = min(SEG, nk_total - seg0);
+        __syncthreads();  // previous segment fully consumed
+        for (int e = tid; e < seg_n; e += 256) {
+            const int E = seg0 + e;
+            int j = 0;
+            bool real;
+            if (E < nkl) {
+                real = E < cnt;
+                if (real) j = list[E];
+            } else {
+                j = c0 + (E - nkl);
+                real = j <= c_end;
+                if (!real) j = 0;
+            }
+            sm.jpos[e] = j;
+            sm.jlast[e] = real ? (w - 1 + dr[j]) : -1;
+            sm.ju[e] = real ? ur[j] : 0.0f;
+        }
+        const int ntiles = seg_n / KT;
+        for (int t = 0; t < ntiles; t++) {
+            __syncthreads();  // metadata staged / everybody done with the previous tile
+            {
+                const TileRows<D, 64> rows = tile_rows<D, 64>(sm.jpos + t * KT, wv, lane);
+                const int c = lane % LPR;
+#pragma unroll
+                for (int x = 0; x < NX; x++) {
+                    const int L = wv * NX + x;
+                    const uint32_t off = (uint32_t)rows.j[x] * (uint32_t)S::RB + 16u * (uint32_t)c;
+                    __builtin_amdgcn_global_load_lds((glb_void_t*)(kh + off), (lds_void_t*)&sm.kr[L * S::GSK], 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((glb_void_t*)(vh + off), (lds_void_t*)&sm.vr[L * S::GSK], 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((glb_void_t*)(kh + off), (lds_void_t*)&sm.kt[L * S::GSV], 16, 0, 0);
+                }
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();  // the tile has landed
+            if (!wave_live) continue;
+            const int base = t * KT;
+#pragma unroll
+            for (int mb = 0; mb < 2; mb++) {
+                const int trw = 32 * mb + col;
+                const int off = (trw % S::NL) * S::GSK + (trw / S::NL) * S::RB + 16 * half;
+                f32x16 acc_s, acc_d;
+#pragma unroll
+                for (int r = 0; r < 16; r++) { acc_s[r] = 0.0f; acc_d[r] = 0.0f; }
+#pragma unroll
+                for (int s = 0; s < DS; s++) {
+                    const bf16x8 ka = *(const bf16x8*)(sm.kr + off + 32 * s);
+                    const bf16x8 va = *(const bf16x8*)(sm.vr + off + 32 * s);
+                    acc_s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], acc_s, 0, 0, 0);
+                    acc_d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dreg[s], acc_d, 0, 0, 0);
+                }
+                bf16x8 dsb[2];
+#pragma unroll
+                for (int g4 = 0; g4 < 4; g4++) {
+                    const int kb = base + 32 * mb + 8 * g4 + 4 * half;
+                    const int4 J4 = *(const int4*)&sm.jpos[kb];
+                    const int4 L4 = *(const int4*)&sm.jlast[kb];
+                    const float4 U4 = *(const float4*)&sm.ju[kb];
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
+                        const int r = 4 * g4 + e;
+                        const int Jj = e == 0 ? J4.x : e == 1 ? J4.y : e == 2 ? J4.z : J4.w;
+                        const int Lj = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
+                        const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
+                        // attended  <=>  j <= i <= w - 1 + death_j; inside the window the gate is 1
+                        const bool valid = (Jj <= qv) && (qv <= Lj);
+                        const float gate = (qv - Jj < w) ? 1.0f : clip01(uj - tau_q);
+                        const float gk = MODE == 0 ? gate : 1.0f, gv = MODE == 2 ? 1.0f : gate;
+                        const float qk = acc_s[r], dov = acc_d[r];
+                        const float p = __builtin_amdgcn_exp2f(fmaf(qk * gk, c2, -lse2));
+                        const float ds = p * fmaf(gv, dov, -Di) * (scale * gk);
+                        dsb[r >> 3][r & 7] = (__bf16)(valid ? ds : 0.0f);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 2 * DB; i++)
+                    acc_q[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt_operand(2 * mb + i / DB, i % DB), dsb[i / DB],
+                                                                            acc_q[i % DB], 0, 0, 0);
+            }
+        }
+    }
+    if (qi < n) {
+        uint16_t* orow = dq + ((size_t)bh * n + qi) * D;
+#pragma unroll
+        for (int x = 0; x < DB; x++) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; g4++) {
+                bf16x4 pk;
+#pragma unroll
+                for (int e = 0; e < 4; e++) pk[e] = (__bf16)acc_q[x][4 * g4 + e];
+                *(bf16x4*)(orow + 32 * x + 8 * g4 + 4 * half) = pk;
+            }
+        }
+    }
+}
+
+template <int D>
+static void launch_dq_mfma(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
+                           const float* tau, const int32_t* death, const int32_t* lists, const int32_t* counts,
+                           const float* lse, const void* dO, const float* delta, void* dq, int nb, hipStream_t st)
+{
+    const int BH = c.B * c.H;
+    dim3 grid(nb * BH);
+#define SPK_LAUNCH_DQ(MODE)                                                                                        \
+    hipLaunchKernelGGL((attn_bwd_dq_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q, (const uint16_t*)k, \
+                       (const uint16_t*)v, u, tau, death, lists, counts, lse, (const uint16_t*)dO, delta,          \
+                       (uint16_t*)dq, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH)
+    if (c.gate_mode == 0) SPK_LAUNCH_DQ(0);
+    else if (c.gate_mode == 1) SPK_LAUNCH_DQ(1);
+    else SPK_LAUNCH_DQ(2);
+#undef SPK_LAUNCH_DQ
 }
 
 int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
@@ -198,10 +411,15 @@ int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
     } else {
         hipLaunchKernelGGL(abwd_delta_kernel<uint16_t>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st,
                            (const uint16_t*)o, (const uint16_t*)dO, rows, c.d, delta);
+        const bool mfma = (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull;
+        if (mfma) {
+            if (c.d == 64) launch_dq_mfma<64>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st);
+            else launch_dq_mfma<128>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st);
+        }
         hipLaunchKernelGGL(attn_bwd_generic_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)q,
                            (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, lse, (const uint16_t*)dO,
-                           delta, (uint16_t*)dq, dk32, dv32, c.H, c.Gu, c.n, c.d, c.k, c.w, c.gate_mode, c.softmax_scale,
-                           nb);
+                           delta, mfma ? (uint16_t*)nullptr : (uint16_t*)dq, dk32, dv32, c.H, c.Gu, c.n, c.d, c.k, c.w,
+                           c.gate_mode, c.softmax_scale, nb);
         hipLaunchKernelGGL(abwd_convert_kernel<uint16_t>, dim3(2048), dim3(256), 0, st, dk32, dv32, (uint16_t*)dk,
                            (uint16_t*)dv, nelem);
     }
