@@ -16,7 +16,7 @@ void launch_block_lists(const sparsek_cfg& c, const int32_t* death, int32_t* lis
 size_t block_lists_bytes(const sparsek_cfg& c, size_t* counts_offset);
 
 struct AbwdWs {
-    size_t lists, counts, delta, dk32, dv32, total;
+    size_t lists, counts, delta, elist, ecount, dk32, dv32, total;
 };
 static AbwdWs abwd_ws(const sparsek_cfg& c)
 {
@@ -28,6 +28,8 @@ static AbwdWs abwd_ws(const sparsek_cfg& c)
     W.counts = coff;
     size_t off = align_up(lb, 256);
     W.delta = off; off += align_up(BH * c.n * 4, 256);
+    W.elist = off; off += align_up((size_t)c.B * c.Gu * c.n * 4, 256);
+    W.ecount = off; off += align_up((size_t)c.B * c.Gu * 4, 256);
     W.dk32 = off; off += align_up(BH * c.n * c.d * 4, 256);
     W.dv32 = off; off += align_up(BH * c.n * c.d * 4, 256);
     W.total = off;
@@ -384,6 +386,262 @@ static void launch_dq_mfma(const sparsek_cfg& c, const void* q, const void* k, c
 #undef SPK_LAUNCH_DQ
 }
 
+// ---------------------------------------------------------------------------------
+// MFMA kernel for dK and dV (bf16, D = 64 or 128): the mirror image of the forward.  A workgroup
+// owns 128 keys (4 waves x 32 keys) whose K and V fragments stay in registers, and streams 64-query
+// tiles of Q and dO through LDS, so S = Q.K^T and dO.V^T land with lane = key; P and dS are then
+// directly the B operands of dV^T += dO^T.P and dK^T += Q^T.dS (Q^T, dO^T through transposing LDS
+// reads).  Nothing is reduced across waves and no row data goes through atomics inside the loop.
+// Because a key is attended on one contiguous range of queries, two kinds of key blocks cover all
+// pairs with one interval test per pair:
+//   window blocks    128 consecutive positions, queries j <= i <= j + w - 1, gate 1;
+//   selected blocks  128 ever-selected keys (death_j > j, compacted in position order), queries
+//                    j + w <= i <= death_j + w - 1, gate clip(u_j - tau_{i-w}).
+// Both add their fp32 result into dk32 / dv32 (a key can appear in one block of each kind).
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ int wave_max_i32(int x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = max(x, __shfl_xor(x, o, 64));
+    return x;
+}
+__device__ __forceinline__ int wave_min_i32(int x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = min(x, __shfl_xor(x, o, 64));
+    return x;
+}
+
+__global__ __launch_bounds__(1024) void abwd_elist_kernel(const int32_t* __restrict__ death, int n,
+                                                          int32_t* __restrict__ elist, int32_t* __restrict__ ecount)
+{
+    __shared__ int wt[16];
+    const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int32_t* dr = death + (size_t)row * n;
+    int32_t* el = elist + (size_t)row * n;
+    int base = 0;
+    for (int j0 = 0; j0 < n; j0 += 1024) {
+        const int j = j0 + tid;
+        const bool sel = j < n && dr[j] > j;
+        const unsigned long long bal = __ballot(sel);
+        __syncthreads();
+        if (lane == 0) wt[wv] = __popcll(bal);
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            if (i < wv) before += wt[i];
+            total += wt[i];
+        }
+        if (sel) el[base + before + __popcll(bal & ((1ull << lane) - 1ull))] = j;
+        base += total;
+    }
+    if (tid == 0) ecount[row] = base;
+}
+
+template <int D>
+struct DkvSmem {
+    using S = MfmaSmem<D, 64>;
+    unsigned char qr[2][S::NL * S::GSK];   // Q rows of the tile, padded for row reads
+    unsigned char qt[2][S::NL * S::GSV];   // ... for transposing reads
+    unsigned char gr[2][S::NL * S::GSK];   // dO rows, row reads
+    unsigned char gt[2][S::NL * S::GSV];   // dO rows, transposing reads
+    float lse2[2][KT], del[2][KT], tq[2][KT];  // per query of the tile: lse * log2(e), D_i, tau_{i-w}
+    int red[2][4];
+};
+
+template <int D, int MODE>
+__global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ kk, const uint16_t* __restrict__ v,
+    const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
+    const int32_t* __restrict__ elist, const int32_t* __restrict__ ecount, const float* __restrict__ lse,
+    const uint16_t* __restrict__ dO, const float* __restrict__ delta, float* __restrict__ dk32,
+    float* __restrict__ dv32, int H, int Gu, int n, int w, float scale, int nb)
+{
+    using S = MfmaSmem<D, 64>;
+    __shared__ __align__(16) DkvSmem<D> sm;
+    constexpr int DS = D / 16, DB = D / 32, NX = S::NL / 4, LPR = S::RB / 16;
+    const int bh = blockIdx.y;
+    const int b = bh / H, h = bh % H;
+    const int row = b * Gu + (Gu == 1 ? 0 : h);
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, col = lane & 31;
+    const bool selected_kind = (int)blockIdx.x >= nb;
+    const int kblk = selected_kind ? blockIdx.x - nb : blockIdx.x;
+    const float* ur = u + (size_t)row * n;
+    const float* tr = tau + (size_t)row * n;
+    const int32_t* dr = death + (size_t)row * n;
+    const int ne = selected_kind ? ecount[row] : n;
+    if (kblk * 128 >= ne) return;  // no such block of selected keys
+    if (!selected_kind && w == 0) return;  // no window pairs at all
+
+    // ---- this lane's key and the queries that attend it ----
+    const int kidx = kblk * 128 + 32 * wv + col;
+    const bool kreal = kidx < ne;
+    const int j = !kreal ? 0 : selected_kind ? elist[(size_t)row * n + kidx] : kidx;
+    int lo = 1, hi = 0;  // empty for a filler lane
+    float uj = 0.0f;
+    if (kreal) {
+        if (selected_kind) { lo = j + w; hi = min(n - 1, dr[j] + w - 1); uj = ur[j]; }
+        else { lo = j; hi = min(n - 1, j + w - 1); }
+    }
+    const bool kvalid = lo <= hi;
+    const int wlo = wave_min_i32(kvalid ? lo : 0x7fffffff);
+    const int whi = wave_max_i32(kvalid ? hi : -1);
+    if (lane == 0) { sm.red[0][wv] = wlo; sm.red[1][wv] = whi; }
+    bf16x8 kreg[DS], vreg[DS];
+#pragma unroll
+    for (int s = 0; s < DS; s++) {
+        const size_t off = ((size_t)bh * n + j) * D + 16 * s + 8 * half;
+        kreg[s] = *(const bf16x8*)(kk + off);
+        vreg[s] = *(const bf16x8*)(v + off);
+    }
+    f32x16 acc_k[DB], acc_v[DB];
+#pragma unroll
+    for (int x = 0; x < DB; x++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) { acc_k[x][r] = 0.0f; acc_v[x][r] = 0.0f; }
+    __syncthreads();
+    const int blo = min(min(sm.red[0][0], sm.red[0][1]), min(sm.red[0][2], sm.red[0][3]));
+    const int bhi = max(max(sm.red[1][0], sm.red[1][1]), max(sm.red[1][2], sm.red[1][3]));
+    if (blo > bhi) return;  // (uniform) nothing attends these keys
+    const int ntiles = (bhi - blo) / KT + 1;
+    const float c2 = scale * 1.4426950408889634f;
+    const unsigned char* qh = (const unsigned char*)(q + (size_t)bh * n * D);
+    const unsigned char* gh = (const unsigned char*)(dO + (size_t)bh * n * D);
+
+    const int r16 = lane & 15, grp2 = (lane >> 4) & 1;
+    const int tcol = (16 * grp2 + 4 * (r16 & 3)) * 2;
+    const int trow = 4 * half + (r16 >> 2);
+    auto t_operand = [&](const unsigned char* tbuf, int g, int x) -> bf16x8 {
+        const int row0 = 16 * g + trow, row1 = row0 + 8;
+        const unsigned char* p0 = tbuf + (row0 % S::NL) * S::GSV + (row0 / S::NL) * S::RB + tcol + 64 * x;
+        const unsigned char* p1 = tbuf + (row1 % S::NL) * S::GSV + (row1 / S::NL) * S::RB + tcol + 64 * x;
+        const i16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)p0);
+        const i16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)p1);
+        const bf16x4 l4 = __builtin_bit_cast(bf16x4, lo4), h4 = __builtin_bit_cast(bf16x4, hi4);
+        return __builtin_shufflevector(l4, h4, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+    // the gather of one tile (64 consecutive queries from i_first, clamped to the last row)
+    auto issue = [&](int buf, int i_first) {
+        const int c = lane % LPR;
+#pragma unroll
+        for (int x = 0; x < NX; x++) {
+            const int L = wv * NX + x;
+            const int rr = min(i_first + L + S::NL * (lane / LPR), n - 1);  // tile row L + NL * jrow
+            const uint32_t off = (uint32_t)rr * (uint32_t)S::RB + 16u * (uint32_t)c;
+            __builtin_amdgcn_global_load_lds((glb_void_t*)(qh + off), (lds_void_t*)&sm.qr[buf][L * S::GSK], 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_void_t*)(qh + off), (lds_void_t*)&sm.qt[buf][L * S::GSV], 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_void_t*)(gh + off), (lds_void_t*)&sm.gr[buf][L * S::GSK], 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_void_t*)(gh + off), (lds_void_t*)&sm.gt[buf][L * S::GSV], 16, 0, 0);
+        }
+    };
+    auto load_meta = [&](int i_first, float& a, float& bq, float& cq) {
+        if (tid < KT) {
+            const int i = min(i_first + tid, n - 1);
+            a = lse[(size_t)bh * n + i] * 1.4426950408889634f;
+            bq = delta[(size_t)bh * n + i];
+            cq = tr[max(i - w, 0)];
+        }
+    };
+    {
+        float a = 0, bq = 0, cq = 0;
+        load_meta(blo, a, bq, cq);
+        if (tid < KT) { sm.lse2[0][tid] = a; sm.del[0][tid] = bq; sm.tq[0][tid] = cq; }
+    }
+    issue(0, blo);
+    for (int t = 0; t < ntiles; t++) {
+        const int buf = t & 1;
+        const int i_first = blo + t * KT;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();  // tile t landed (rows and per-query values); everybody is done with tile t-1
+        float ma = 0, mb_ = 0, mc = 0;
+        const bool more = t + 1 < ntiles;
+        if (more) {
+            issue(buf ^ 1, i_first + KT);
+            load_meta(i_first + KT, ma, mb_, mc);
+        }
+        if (i_first <= whi && i_first + KT - 1 >= wlo) {  // some key of this wave is attended from this tile
+#pragma unroll
+            for (int qb = 0; qb < 2; qb++) {
+                const int trw = 32 * qb + col;
+                const int off = (trw % S::NL) * S::GSK + (trw / S::NL) * S::RB + 16 * half;
+                f32x16 acc_s, acc_d;
+#pragma unroll
+                for (int r = 0; r < 16; r++) { acc_s[r] = 0.0f; acc_d[r] = 0.0f; }
+#pragma unroll
+                for (int s = 0; s < DS; s++) {
+                    const bf16x8 qa = *(const bf16x8*)(sm.qr[buf] + off + 32 * s);
+                    const bf16x8 ga = *(const bf16x8*)(sm.gr[buf] + off + 32 * s);
+                    acc_s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kreg[s], acc_s, 0, 0, 0);
+                    acc_d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vreg[s], acc_d, 0, 0, 0);
+                }
+                bf16x8 pb[2], dsb[2];
+#pragma unroll
+                for (int g4 = 0; g4 < 4; g4++) {
+                    const int qo = 32 * qb + 8 * g4 + 4 * half;  // first of 4 consecutive queries of the tile
+                    const float4 L4 = *(const float4*)&sm.lse2[buf][qo];
+                    const float4 D4 = *(const float4*)&sm.del[buf][qo];
+                    const float4 T4 = *(const float4*)&sm.tq[buf][qo];
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
+                        const int r = 4 * g4 + e;
+                        const int i = i_first + qo + e;
+                        const float l2 = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
+                        const float Di = e == 0 ? D4.x : e == 1 ? D4.y : e == 2 ? D4.z : D4.w;
+                        const float tq = e == 0 ? T4.x : e == 1 ? T4.y : e == 2 ? T4.z : T4.w;
+                        const bool valid = (i >= lo) && (i <= hi);
+                        const float gate = selected_kind ? clip01(uj - tq) : 1.0f;
+                        const float gk = MODE == 0 ? gate : 1.0f, gv = MODE == 2 ? 1.0f : gate;
+                        const float qk = acc_s[r], dov = acc_d[r];
+                        const float p = __builtin_amdgcn_exp2f(fmaf(qk * gk, c2, -l2));
+                        const float pvv = p * gv;
+                        const float ds = p * fmaf(gv, dov, -Di) * (scale * gk);
+                        pb[r >> 3][r & 7] = (__bf16)(valid ? pvv : 0.0f);
+                        dsb[r >> 3][r & 7] = (__bf16)(valid ? ds : 0.0f);
+                    }
+                }
+#pragma unroll
+                for (int i2 = 0; i2 < 2 * DB; i2++) {
+                    const int g = 2 * qb + i2 / DB, x = i2 % DB;
+                    acc_v[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t_operand(sm.gt[buf], g, x), pb[i2 / DB], acc_v[x], 0, 0, 0);
+                    acc_k[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t_operand(sm.qt[buf], g, x), dsb[i2 / DB], acc_k[x], 0, 0, 0);
+                }
+            }
+        }
+        if (more && tid < KT) { sm.lse2[buf ^ 1][tid] = ma; sm.del[buf ^ 1][tid] = mb_; sm.tq[buf ^ 1][tid] = mc; }
+    }
+    if (kvalid) {
+        float* pk = dk32 + ((size_t)bh * n + j) * D;
+        float* pv = dv32 + ((size_t)bh * n + j) * D;
+#pragma unroll
+        for (int x = 0; x < DB; x++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) {
+                const int dcol = 32 * x + 8 * (r >> 2) + 4 * half + (r & 3);
+                unsafeAtomicAdd(pk + dcol, acc_k[x][r]);
+                unsafeAtomicAdd(pv + dcol, acc_v[x][r]);
+            }
+    }
+}
+
+template <int D>
+static void launch_dkv_mfma(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
+                            const float* tau, const int32_t* death, const int32_t* elist, const int32_t* ecount,
+                            const float* lse, const void* dO, const float* delta, float* dk32, float* dv32, int nb,
+                            hipStream_t st)
+{
+    dim3 grid(2 * nb, c.B * c.H);  // window blocks, then (up to) as many blocks of selected keys
+#define SPK_LAUNCH_KV(MODE)                                                                                         \
+    hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q, (const uint16_t*)k, \
+                       (const uint16_t*)v, u, tau, death, elist, ecount, lse, (const uint16_t*)dO, delta, dk32, dv32,  \
+                       c.H, c.Gu, c.n, c.w, c.softmax_scale, nb)
+    if (c.gate_mode == 0) SPK_LAUNCH_KV(0);
+    else if (c.gate_mode == 1) SPK_LAUNCH_KV(1);
+    else SPK_LAUNCH_KV(2);
+#undef SPK_LAUNCH_KV
+}
+
 int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                     const float* tau, const int32_t* death, const void* o, const float* lse, const void* dO, void* dq,
                     void* dk, void* dv, void* ws, hipStream_t st)
@@ -413,13 +671,22 @@ int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
                            (const uint16_t*)o, (const uint16_t*)dO, rows, c.d, delta);
         const bool mfma = (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull;
         if (mfma) {
-            if (c.d == 64) launch_dq_mfma<64>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st);
-            else launch_dq_mfma<128>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st);
+            int32_t* elist = (int32_t*)(base + W.elist);
+            int32_t* ecount = (int32_t*)(base + W.ecount);
+            hipLaunchKernelGGL(abwd_elist_kernel, dim3(c.B * c.Gu), dim3(1024), 0, st, death, c.n, elist, ecount);
+            if (c.d == 64) {
+                launch_dq_mfma<64>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st);
+                launch_dkv_mfma<64>(c, q, k, v, u, tau, death, elist, ecount, lse, dO, delta, dk32, dv32, nb, st);
+            } else {
+                launch_dq_mfma<128>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st);
+                launch_dkv_mfma<128>(c, q, k, v, u, tau, death, elist, ecount, lse, dO, delta, dk32, dv32, nb, st);
+            }
+        } else {
+            hipLaunchKernelGGL(attn_bwd_generic_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)q,
+                               (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, lse,
+                               (const uint16_t*)dO, delta, (uint16_t*)dq, dk32, dv32, c.H, c.Gu, c.n, c.d, c.k, c.w,
+                               c.gate_mode, c.softmax_scale, nb);
         }
-        hipLaunchKernelGGL(attn_bwd_generic_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)q,
-                           (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, lse, (const uint16_t*)dO,
-                           delta, mfma ? (uint16_t*)nullptr : (uint16_t*)dq, dk32, dv32, c.H, c.Gu, c.n, c.d, c.k, c.w,
-                           c.gate_mode, c.softmax_scale, nb);
         hipLaunchKernelGGL(abwd_convert_kernel<uint16_t>, dim3(2048), dim3(256), 0, st, dk32, dv32, (uint16_t*)dk,
                            (uint16_t*)dv, nelem);
     }
