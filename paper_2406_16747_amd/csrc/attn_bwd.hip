@@ -16,7 +16,7 @@ void launch_block_lists(const sparsek_cfg& c, const int32_t* death, int32_t* lis
 size_t block_lists_bytes(const sparsek_cfg& c, size_t* counts_offset);
 
 struct AbwdWs {
-    size_t lists, counts, delta, elist, ecount, dk32, dv32, total;
+    size_t lists, counts, delta, elist, ecount, eslot, dk32, dv32, sk32, sv32, total;
 };
 static AbwdWs abwd_ws(const sparsek_cfg& c)
 {
@@ -30,8 +30,11 @@ static AbwdWs abwd_ws(const sparsek_cfg& c)
     W.delta = off; off += align_up(BH * c.n * 4, 256);
     W.elist = off; off += align_up((size_t)c.B * c.Gu * c.n * 4, 256);
     W.ecount = off; off += align_up((size_t)c.B * c.Gu * 4, 256);
+    W.eslot = off; off += align_up((size_t)c.B * c.Gu * c.n * 4, 256);
     W.dk32 = off; off += align_up(BH * c.n * c.d * 4, 256);
     W.dv32 = off; off += align_up(BH * c.n * c.d * 4, 256);
+    W.sk32 = off; off += align_up(BH * c.n * c.d * 4, 256);
+    W.sv32 = off; off += align_up(BH * c.n * c.d * 4, 256);
     W.total = off;
     return W;
 }
@@ -397,7 +400,10 @@ static void launch_dq_mfma(const sparsek_cfg& c, const void* q, const void* k, c
 //   window blocks    128 consecutive positions, queries j <= i <= j + w - 1, gate 1;
 //   selected blocks  128 ever-selected keys (death_j > j, compacted in position order), queries
 //                    j + w <= i <= death_j + w - 1, gate clip(u_j - tau_{i-w}).
-// Both add their fp32 result into dk32 / dv32 (a key can appear in one block of each kind).
+// Every key belongs to exactly one window block and at most one selected block, so both kinds
+// store their fp32 result without atomics: window blocks into dk32 / dv32 [B,H,n,d] (every element,
+// zeros included), selected blocks into sk32 / sv32 at the key's slot of the compacted list; the
+// final pass adds the two and rounds to the storage type.
 // ---------------------------------------------------------------------------------
 __device__ __forceinline__ int wave_max_i32(int x)
 {
@@ -412,8 +418,11 @@ __device__ __forceinline__ int wave_min_i32(int x)
     return x;
 }
 
+// elist: the ever-selected keys of a score row (death_j > j) in position order; eslot[j]: where key j
+// sits in that list, -1 if it is not in it.
 __global__ __launch_bounds__(1024) void abwd_elist_kernel(const int32_t* __restrict__ death, int n,
-                                                          int32_t* __restrict__ elist, int32_t* __restrict__ ecount)
+                                                          int32_t* __restrict__ elist, int32_t* __restrict__ ecount,
+                                                          int32_t* __restrict__ eslot)
 {
     __shared__ int wt[16];
     const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -433,7 +442,9 @@ __global__ __launch_bounds__(1024) void abwd_elist_kernel(const int32_t* __restr
             if (i < wv) before += wt[i];
             total += wt[i];
         }
-        if (sel) el[base + before + __popcll(bal & ((1ull << lane) - 1ull))] = j;
+        const int slot = base + before + __popcll(bal & ((1ull << lane) - 1ull));
+        if (sel) el[slot] = j;
+        if (j < n) eslot[(size_t)row * n + j] = sel ? slot : -1;
         base += total;
     }
     if (tid == 0) ecount[row] = base;
@@ -456,7 +467,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
     const int32_t* __restrict__ elist, const int32_t* __restrict__ ecount, const float* __restrict__ lse,
     const uint16_t* __restrict__ dO, const float* __restrict__ delta, float* __restrict__ dk32,
-    float* __restrict__ dv32, int H, int Gu, int n, int w, float scale, int nb)
+    float* __restrict__ dv32, float* __restrict__ sk32, float* __restrict__ sv32, int H, int Gu, int n, int w,
+    float scale, int nb)
 {
     using S = MfmaSmem<D, 64>;
     __shared__ __align__(16) DkvSmem<D> sm;
@@ -466,14 +478,14 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     const int row = b * Gu + (Gu == 1 ? 0 : h);
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, col = lane & 31;
-    const bool selected_kind = (int)blockIdx.x >= nb;
-    const int kblk = selected_kind ? blockIdx.x - nb : blockIdx.x;
+    // blocks of selected keys first: they run longest
+    const bool selected_kind = (int)blockIdx.x < nb;
+    const int kblk = selected_kind ? blockIdx.x : blockIdx.x - nb;
     const float* ur = u + (size_t)row * n;
     const float* tr = tau + (size_t)row * n;
     const int32_t* dr = death + (size_t)row * n;
     const int ne = selected_kind ? ecount[row] : n;
     if (kblk * 128 >= ne) return;  // no such block of selected keys
-    if (!selected_kind && w == 0) return;  // no window pairs at all
 
     // ---- this lane's key and the queries that attend it ----
     const int kidx = kblk * 128 + 32 * wv + col;
@@ -504,8 +516,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     __syncthreads();
     const int blo = min(min(sm.red[0][0], sm.red[0][1]), min(sm.red[0][2], sm.red[0][3]));
     const int bhi = max(max(sm.red[1][0], sm.red[1][1]), max(sm.red[1][2], sm.red[1][3]));
-    if (blo > bhi) return;  // (uniform) nothing attends these keys
-    const int ntiles = (bhi - blo) / KT + 1;
+    const int ntiles = blo > bhi ? 0 : (bhi - blo) / KT + 1;  // (uniform) 0: nothing attends these keys
     const float c2 = scale * 1.4426950408889634f;
     const unsigned char* qh = (const unsigned char*)(q + (size_t)bh * n * D);
     const unsigned char* gh = (const unsigned char*)(dO + (size_t)bh * n * D);
@@ -544,12 +555,12 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
             cq = tr[max(i - w, 0)];
         }
     };
-    {
+    if (ntiles > 0) {
         float a = 0, bq = 0, cq = 0;
         load_meta(blo, a, bq, cq);
         if (tid < KT) { sm.lse2[0][tid] = a; sm.del[0][tid] = bq; sm.tq[0][tid] = cq; }
+        issue(0, blo);
     }
-    issue(0, blo);
     for (int t = 0; t < ntiles; t++) {
         const int buf = t & 1;
         const int i_first = blo + t * KT;
@@ -562,20 +573,25 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
             load_meta(i_first + KT, ma, mb_, mc);
         }
         if (i_first <= whi && i_first + KT - 1 >= wlo) {  // some key of this wave is attended from this tile
+            // both query halves' S and dO.V first, so that the second half's MFMAs can run under the
+            // first half's elementwise work, and the first half's dV / dK MFMAs under the second's
+            f32x16 acc_s[2], acc_d[2];
 #pragma unroll
             for (int qb = 0; qb < 2; qb++) {
                 const int trw = 32 * qb + col;
                 const int off = (trw % S::NL) * S::GSK + (trw / S::NL) * S::RB + 16 * half;
-                f32x16 acc_s, acc_d;
 #pragma unroll
-                for (int r = 0; r < 16; r++) { acc_s[r] = 0.0f; acc_d[r] = 0.0f; }
+                for (int r = 0; r < 16; r++) { acc_s[qb][r] = 0.0f; acc_d[qb][r] = 0.0f; }
 #pragma unroll
                 for (int s = 0; s < DS; s++) {
                     const bf16x8 qa = *(const bf16x8*)(sm.qr[buf] + off + 32 * s);
                     const bf16x8 ga = *(const bf16x8*)(sm.gr[buf] + off + 32 * s);
-                    acc_s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kreg[s], acc_s, 0, 0, 0);
-                    acc_d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vreg[s], acc_d, 0, 0, 0);
+                    acc_s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kreg[s], acc_s[qb], 0, 0, 0);
+                    acc_d[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vreg[s], acc_d[qb], 0, 0, 0);
                 }
+            }
+#pragma unroll
+            for (int qb = 0; qb < 2; qb++) {
                 bf16x8 pb[2], dsb[2];
 #pragma unroll
                 for (int g4 = 0; g4 < 4; g4++) {
@@ -593,7 +609,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
                         const bool valid = (i >= lo) && (i <= hi);
                         const float gate = selected_kind ? clip01(uj - tq) : 1.0f;
                         const float gk = MODE == 0 ? gate : 1.0f, gv = MODE == 2 ? 1.0f : gate;
-                        const float qk = acc_s[r], dov = acc_d[r];
+                        const float qk = acc_s[qb][r], dov = acc_d[qb][r];
                         const float p = __builtin_amdgcn_exp2f(fmaf(qk * gk, c2, -l2));
                         const float pvv = p * gv;
                         const float ds = p * fmaf(gv, dov, -Di) * (scale * gk);
@@ -611,31 +627,61 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
         }
         if (more && tid < KT) { sm.lse2[buf ^ 1][tid] = ma; sm.del[buf ^ 1][tid] = mb_; sm.tq[buf ^ 1][tid] = mc; }
     }
-    if (kvalid) {
-        float* pk = dk32 + ((size_t)bh * n + j) * D;
-        float* pv = dv32 + ((size_t)bh * n + j) * D;
+    if (kreal) {
+        const size_t ro = selected_kind ? ((size_t)bh * n + kidx) * D : ((size_t)bh * n + j) * D;
+        float* pk = (selected_kind ? sk32 : dk32) + ro;
+        float* pv = (selected_kind ? sv32 : dv32) + ro;
 #pragma unroll
         for (int x = 0; x < DB; x++)
 #pragma unroll
-            for (int r = 0; r < 16; r++) {
-                const int dcol = 32 * x + 8 * (r >> 2) + 4 * half + (r & 3);
-                unsafeAtomicAdd(pk + dcol, acc_k[x][r]);
-                unsafeAtomicAdd(pv + dcol, acc_v[x][r]);
+            for (int g4 = 0; g4 < 4; g4++) {
+                const int dcol = 32 * x + 8 * g4 + 4 * half;
+                *(float4*)(pk + dcol) = make_float4(acc_k[x][4 * g4], acc_k[x][4 * g4 + 1], acc_k[x][4 * g4 + 2], acc_k[x][4 * g4 + 3]);
+                *(float4*)(pv + dcol) = make_float4(acc_v[x][4 * g4], acc_v[x][4 * g4 + 1], acc_v[x][4 * g4 + 2], acc_v[x][4 * g4 + 3]);
             }
+    }
+}
+
+// dk = dk32 (+ sk32 at the key's slot when it was ever selected), rounded to bf16; same for dv.
+__global__ __launch_bounds__(256) void abwd_merge_kernel(const float* __restrict__ dk32, const float* __restrict__ dv32,
+                                                         const float* __restrict__ sk32, const float* __restrict__ sv32,
+                                                         const int32_t* __restrict__ eslot, int H, int Gu, int n, int d4,
+                                                         uint16_t* __restrict__ dk, uint16_t* __restrict__ dv)
+{
+    const int bh = blockIdx.y;
+    const int b = bh / H, h = bh % H;
+    const int row = b * Gu + (Gu == 1 ? 0 : h);
+    const size_t total = (size_t)n * d4;  // float4 units of this head
+    for (size_t x = (size_t)blockIdx.x * 256 + threadIdx.x; x < total; x += (size_t)gridDim.x * 256) {
+        const int j = (int)(x / d4), c4 = (int)(x % d4);
+        const size_t src = ((size_t)bh * n + j) * d4 + c4;
+        float4 a = ((const float4*)dk32)[src], c = ((const float4*)dv32)[src];
+        const int slot = eslot[(size_t)row * n + j];
+        if (slot >= 0) {
+            const size_t s2 = ((size_t)bh * n + slot) * d4 + c4;
+            const float4 a2 = ((const float4*)sk32)[s2], c2 = ((const float4*)sv32)[s2];
+            a.x += a2.x; a.y += a2.y; a.z += a2.z; a.w += a2.w;
+            c.x += c2.x; c.y += c2.y; c.z += c2.z; c.w += c2.w;
+        }
+        ushort4 oa, oc;
+        oa.x = f32_to_bf16(a.x); oa.y = f32_to_bf16(a.y); oa.z = f32_to_bf16(a.z); oa.w = f32_to_bf16(a.w);
+        oc.x = f32_to_bf16(c.x); oc.y = f32_to_bf16(c.y); oc.z = f32_to_bf16(c.z); oc.w = f32_to_bf16(c.w);
+        ((ushort4*)dk)[src] = oa;
+        ((ushort4*)dv)[src] = oc;
     }
 }
 
 template <int D>
 static void launch_dkv_mfma(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                             const float* tau, const int32_t* death, const int32_t* elist, const int32_t* ecount,
-                            const float* lse, const void* dO, const float* delta, float* dk32, float* dv32, int nb,
-                            hipStream_t st)
+                            const float* lse, const void* dO, const float* delta, float* dk32, float* dv32,
+                            float* sk32, float* sv32, int nb, hipStream_t st)
 {
-    dim3 grid(2 * nb, c.B * c.H);  // window blocks, then (up to) as many blocks of selected keys
+    dim3 grid(2 * nb, c.B * c.H);  // (up to) nb blocks of selected keys, then the nb window blocks
 #define SPK_LAUNCH_KV(MODE)                                                                                         \
     hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q, (const uint16_t*)k, \
                        (const uint16_t*)v, u, tau, death, elist, ecount, lse, (const uint16_t*)dO, delta, dk32, dv32,  \
-                       c.H, c.Gu, c.n, c.w, c.softmax_scale, nb)
+                       sk32, sv32, c.H, c.Gu, c.n, c.w, c.softmax_scale, nb)
     if (c.gate_mode == 0) SPK_LAUNCH_KV(0);
     else if (c.gate_mode == 1) SPK_LAUNCH_KV(1);
     else SPK_LAUNCH_KV(2);
@@ -655,7 +701,9 @@ int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
     float* delta = (float*)(base + W.delta);
     float* dk32 = (float*)(base + W.dk32);
     float* dv32 = (float*)(base + W.dv32);
-    hipLaunchKernelGGL(abwd_zero_kernel, dim3(2048), dim3(256), 0, st, (uint4*)(base + W.dk32), (W.total - W.dk32) / 16);
+    const bool mfma = c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull;
+    if (!mfma)  // the generic kernel accumulates dk, dv with atomics
+        hipLaunchKernelGGL(abwd_zero_kernel, dim3(2048), dim3(256), 0, st, (uint4*)(base + W.dk32), (W.sk32 - W.dk32) / 16);
     launch_block_lists(c, death, lists, counts, st);
     dim3 grid(nb, c.B * c.H);
     if (c.dtype == SPARSEK_F32) {
@@ -669,26 +717,34 @@ int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
     } else {
         hipLaunchKernelGGL(abwd_delta_kernel<uint16_t>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st,
                            (const uint16_t*)o, (const uint16_t*)dO, rows, c.d, delta);
-        const bool mfma = (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull;
         if (mfma) {
             int32_t* elist = (int32_t*)(base + W.elist);
             int32_t* ecount = (int32_t*)(base + W.ecount);
-            hipLaunchKernelGGL(abwd_elist_kernel, dim3(c.B * c.Gu), dim3(1024), 0, st, death, c.n, elist, ecount);
+            int32_t* eslot = (int32_t*)(base + W.eslot);
+            float* sk32 = (float*)(base + W.sk32);
+            float* sv32 = (float*)(base + W.sv32);
+            hipLaunchKernelGGL(abwd_elist_kernel, dim3(c.B * c.Gu), dim3(1024), 0, st, death, c.n, elist, ecount, eslot);
             if (c.d == 64) {
                 launch_dq_mfma<64>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st);
-                launch_dkv_mfma<64>(c, q, k, v, u, tau, death, elist, ecount, lse, dO, delta, dk32, dv32, nb, st);
+                launch_dkv_mfma<64>(c, q, k, v, u, tau, death, elist, ecount, lse, dO, delta, dk32, dv32, sk32, sv32, nb,
+                                    st);
             } else {
                 launch_dq_mfma<128>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st);
-                launch_dkv_mfma<128>(c, q, k, v, u, tau, death, elist, ecount, lse, dO, delta, dk32, dv32, nb, st);
+                launch_dkv_mfma<128>(c, q, k, v, u, tau, death, elist, ecount, lse, dO, delta, dk32, dv32, sk32, sv32, nb,
+                                     st);
             }
+            const int d4 = c.d / 4;
+            const int gx = (int)std::min<size_t>(((size_t)c.n * d4 + 255) / 256, 1024);
+            hipLaunchKernelGGL(abwd_merge_kernel, dim3(gx, c.B * c.H), dim3(256), 0, st, dk32, dv32, sk32, sv32, eslot, c.H,
+                               c.Gu, c.n, d4, (uint16_t*)dk, (uint16_t*)dv);
         } else {
             hipLaunchKernelGGL(attn_bwd_generic_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)q,
                                (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, lse,
                                (const uint16_t*)dO, delta, (uint16_t*)dq, dk32, dv32, c.H, c.Gu, c.n, c.d, c.k, c.w,
                                c.gate_mode, c.softmax_scale, nb);
+            hipLaunchKernelGGL(abwd_convert_kernel<uint16_t>, dim3(2048), dim3(256), 0, st, dk32, dv32, (uint16_t*)dk,
+                               (uint16_t*)dv, nelem);
         }
-        hipLaunchKernelGGL(abwd_convert_kernel<uint16_t>, dim3(2048), dim3(256), 0, st, dk32, dv32, (uint16_t*)dk,
-                           (uint16_t*)dv, nelem);
     }
     return launch_status();
 }
