@@ -418,36 +418,80 @@ __device__ __forceinline__ int wave_min_i32(int x)
     return x;
 }
 
-// elist: the ever-selected keys of a score row (death_j > j) in position order; eslot[j]: where key j
-// sits in that list, -1 if it is not in it.
+// elist: the ever-selected keys of a score row (death_j > j), ordered by death_j / bw and then by position,
+// so that the 32 keys of a wave and the 128 of a block stop being attended at about the same query and the
+// span of query tiles they walk is short.  eslot[j]: where key j sits in that list, -1 if it is not in it.
+// A counting sort whose result does not depend on timing: every wave owns a contiguous range of positions
+// and its own cursor per bucket.
+constexpr int EBK = 512;
 __global__ __launch_bounds__(1024) void abwd_elist_kernel(const int32_t* __restrict__ death, int n,
                                                           int32_t* __restrict__ elist, int32_t* __restrict__ ecount,
                                                           int32_t* __restrict__ eslot)
 {
-    __shared__ int wt[16];
+    __shared__ int cur[16][EBK];
+    __shared__ int start[EBK];
     const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int32_t* dr = death + (size_t)row * n;
     int32_t* el = elist + (size_t)row * n;
-    int base = 0;
-    for (int j0 = 0; j0 < n; j0 += 1024) {
-        const int j = j0 + tid;
-        const bool sel = j < n && dr[j] > j;
-        const unsigned long long bal = __ballot(sel);
-        __syncthreads();
-        if (lane == 0) wt[wv] = __popcll(bal);
-        __syncthreads();
-        int before = 0, total = 0;
-#pragma unroll
-        for (int i = 0; i < 16; i++) {
-            if (i < wv) before += wt[i];
-            total += wt[i];
-        }
-        const int slot = base + before + __popcll(bal & ((1ull << lane) - 1ull));
-        if (sel) el[slot] = j;
-        if (j < n) eslot[(size_t)row * n + j] = sel ? slot : -1;
-        base += total;
+    int32_t* es = eslot + (size_t)row * n;
+    const int bw = max(256, (n + EBK) / EBK);  // death <= n, so death / bw < EBK
+    for (int i = tid; i < 16 * EBK; i += 1024) (&cur[0][0])[i] = 0;
+    __syncthreads();
+    const int per = ((n + 15) / 16 + 63) / 64 * 64;
+    const int j_begin = min(n, wv * per), j_end = min(n, j_begin + per);
+    for (int j0 = j_begin; j0 < j_end; j0 += 64) {
+        const int j = j0 + lane;
+        const int dj = j < j_end ? dr[j] : 0;
+        if (j < j_end && dj > j) atomicAdd(&cur[wv][dj / bw], 1);
     }
-    if (tid == 0) ecount[row] = base;
+    __syncthreads();
+    if (tid < EBK) {  // per bucket: each wave's offset inside the bucket, and the bucket's size
+        int acc = 0;
+#pragma unroll
+        for (int x = 0; x < 16; x++) {
+            const int c = cur[x][tid];
+            cur[x][tid] = acc;
+            acc += c;
+        }
+        start[tid] = acc;
+    }
+    __syncthreads();
+    if (wv == 0) {  // exclusive scan of the bucket sizes, 8 buckets per lane
+        int v[EBK / 64], sum = 0;
+#pragma unroll
+        for (int i = 0; i < EBK / 64; i++) { v[i] = start[lane * (EBK / 64) + i]; sum += v[i]; }
+        int incl = sum;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int y = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += y;
+        }
+        int ex = incl - sum;
+#pragma unroll
+        for (int i = 0; i < EBK / 64; i++) { start[lane * (EBK / 64) + i] = ex; ex += v[i]; }
+        if (lane == 63) ecount[row] = incl;
+    }
+    __syncthreads();
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int j0 = j_begin; j0 < j_end; j0 += 64) {
+        const int j = j0 + lane;
+        const int dj = j < j_end ? dr[j] : 0;
+        const bool sel = j < j_end && dj > j;
+        const int bkt = sel ? dj / bw : -1;
+        int slot = -1;
+        unsigned long long rem = __ballot(sel);
+        while (rem) {  // one turn per distinct bucket among this step's lanes
+            const int l = __ffsll((long long)rem) - 1;
+            const int bb = __shfl(bkt, l, 64);
+            const unsigned long long m = __ballot(bkt == bb);
+            const int base = start[bb] + cur[wv][bb];
+            if (bkt == bb) slot = base + __popcll(m & below);
+            if (lane == l) cur[wv][bb] += __popcll(m);
+            rem &= ~m;
+        }
+        if (sel) el[slot] = j;
+        if (j < j_end) es[j] = slot;
+    }
 }
 
 template <int D>
@@ -473,14 +517,16 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     using S = MfmaSmem<D, 64>;
     __shared__ __align__(16) DkvSmem<D> sm;
     constexpr int DS = D / 16, DB = D / 32, NX = S::NL / 4, LPR = S::RB / 16;
-    const int bh = blockIdx.y;
+    const int bh = blockIdx.x;
     const int b = bh / H, h = bh % H;
     const int row = b * Gu + (Gu == 1 ? 0 : h);
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, col = lane & 31;
-    // blocks of selected keys first: they run longest
-    const bool selected_kind = (int)blockIdx.x < nb;
-    const int kblk = selected_kind ? blockIdx.x : blockIdx.x - nb;
+    // The head is the fast grid index: workgroups go to the chip's 8 partitions in turn, so each partition
+    // keeps whole heads (the same mix of block lengths everywhere, and a head's rows in one L2).  Blocks of
+    // selected keys come first, latest deaths (longest spans) first; the short window blocks fill the tail.
+    const bool selected_kind = (int)blockIdx.y < nb;
+    const int kblk = selected_kind ? nb - 1 - blockIdx.y : blockIdx.y - nb;
     const float* ur = u + (size_t)row * n;
     const float* tr = tau + (size_t)row * n;
     const int32_t* dr = death + (size_t)row * n;
@@ -677,7 +723,7 @@ static void launch_dkv_mfma(const sparsek_cfg& c, const void* q, const void* k, 
                             const float* lse, const void* dO, const float* delta, float* dk32, float* dv32,
                             float* sk32, float* sv32, int nb, hipStream_t st)
 {
-    dim3 grid(2 * nb, c.B * c.H);  // (up to) nb blocks of selected keys, then the nb window blocks
+    dim3 grid(c.B * c.H, 2 * nb);  // per head: (up to) nb blocks of selected keys, then the nb window blocks
 #define SPK_LAUNCH_KV(MODE)                                                                                         \
     hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q, (const uint16_t*)k, \
                        (const uint16_t*)v, u, tau, death, elist, ecount, lse, (const uint16_t*)dO, delta, dk32, dv32,  \
