@@ -494,6 +494,16 @@ __global__ __launch_bounds__(1024) void abwd_elist_kernel(const int32_t* __restr
     }
 }
 
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+// two floats rounded to bf16 (nearest even), the first in the low half
+__device__ __forceinline__ unsigned pack_bf16x2(float a, float b)
+{
+    f32x2v f = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2v));
+}
+
 template <int D>
 struct DkvSmem {
     using S = MfmaSmem<D, 64>;
@@ -546,6 +556,12 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     const bool kvalid = lo <= hi;
     const int wlo = wave_min_i32(kvalid ? lo : 0x7fffffff);
     const int whi = wave_max_i32(kvalid ? hi : -1);
+    // a tile inside [wfull_lo, wfull_hi] is attended in full by every key of the wave: no interval tests there
+    const int wfull_lo = wave_max_i32(kvalid ? lo : 0x7fffffff);
+    const int wfull_hi = wave_min_i32(kvalid ? hi : -1);
+    // query i attends this lane's key iff (unsigned)(i - lo_eff) <= span (never for an empty lane)
+    const int lo_eff = kvalid ? lo : 0x7fffffff;
+    const unsigned span = kvalid ? (unsigned)(hi - lo) : 0u;
     if (lane == 0) { sm.red[0][wv] = wlo; sm.red[1][wv] = whi; }
     bf16x8 kreg[DS], vreg[DS];
 #pragma unroll
@@ -607,9 +623,120 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
         if (tid < KT) { sm.lse2[0][tid] = a; sm.del[0][tid] = bq; sm.tq[0][tid] = cq; }
         issue(0, blo);
     }
+    // One tile for this wave, as four runs of NS MFMAs:
+    //   1: S and dO.V of queries 0..31            2: the same for queries 32..63, under it the elementwise
+    //   3: dV, dK += from queries 0..31, under        work (P, dS) of queries 0..31
+    //      it the elementwise work of 32..63       4: dV, dK += from queries 32..63
+    // Every step issues one MFMA and a slice of elementwise work, fenced so that the interleave survives the
+    // scheduler; MFMA operands come from LDS through a small ring filled DEPTH steps ahead.  GATED: the keys
+    // carry soft gates (selected keys, gate modes 0 and 1); CHECK: some (query, key) pair of the tile may lie
+    // outside the key's interval.  The softmax scale of dS is applied once, to the finished dK.
+    constexpr int NS = 2 * DS, EPM = 16 / NS, DEPTH = 4;
+    static_assert(NS == 4 * DB && EPM * NS == 16, "stage lengths");
+    auto tile = [&](auto gated_c, auto check_c, int buf, int i_first) {
+        constexpr bool GATED = decltype(gated_c)::value, CHECK = decltype(check_c)::value;
+        constexpr bool GK = GATED && MODE == 0, GV = GATED && MODE != 2;
+        const f32x16 zero = {0};
+        f32x16 s0 = zero, d0 = zero, s1 = zero, d1 = zero;
+        u32x4 pb0[2], dsb0[2], pb1[2], dsb1[2];
+        const int off0 = (col % S::NL) * S::GSK + (col / S::NL) * S::RB + 16 * half;
+        const int off1 = ((32 + col) % S::NL) * S::GSK + ((32 + col) / S::NL) * S::RB + 16 * half;
+        const int rel0 = i_first + 4 * half - lo_eff;
+        // operand idx of the tile's 4 * NS MFMAs, in issue order
+        auto operand = [&](auto ic) -> bf16x8 {
+            constexpr int idx = decltype(ic)::value, run = idx / NS, m = idx % NS;
+            if constexpr (run < 2) {
+                const unsigned char* base = (m & 1) ? sm.gr[buf] : sm.qr[buf];
+                return *(const bf16x8*)(base + (run ? off1 : off0) + 32 * (m / 2));
+            } else {
+                constexpr int qb = run - 2, i2 = m / 2, g = 2 * qb + i2 / DB, x = i2 % DB;
+                return t_operand((m & 1) ? sm.qt[buf] : sm.gt[buf], g, x);
+            }
+        };
+        bf16x8 ring[DEPTH];
+        static_for<0, DEPTH>([&](auto ic) { ring[decltype(ic)::value] = operand(ic); });
+        auto refill = [&](auto ic) {
+            constexpr int idx = decltype(ic)::value;
+            if constexpr (idx + DEPTH < 4 * NS) ring[idx % DEPTH] = operand(std::integral_constant<int, idx + DEPTH>{});
+        };
+        float4 L4, D4, T4;
+        float hold_p = 0.0f, hold_s = 0.0f;
+        auto element = [&](auto qbc, auto rc, const f32x16& sacc, const f32x16& dacc, u32x4(&pb)[2], u32x4(&dsb)[2]) {
+            constexpr int qb = decltype(qbc)::value, r = decltype(rc)::value, g4 = r / 4, e = r % 4;
+            if constexpr (e == 0) {
+                const int qo = 32 * qb + 8 * g4 + 4 * half;  // first of 4 consecutive queries of the tile
+                L4 = *(const float4*)&sm.lse2[buf][qo];
+                D4 = *(const float4*)&sm.del[buf][qo];
+                if constexpr (GATED) T4 = *(const float4*)&sm.tq[buf][qo];
+            }
+            const float l2 = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
+            const float Di = e == 0 ? D4.x : e == 1 ? D4.y : e == 2 ? D4.z : D4.w;
+            float gate = 1.0f;
+            if constexpr (GATED) gate = clip01(uj - (e == 0 ? T4.x : e == 1 ? T4.y : e == 2 ? T4.z : T4.w));
+            const float qk = sacc[r], dov = dacc[r];
+            float arg = GK ? fmaf(qk, gate * c2, -l2) : fmaf(qk, c2, -l2);
+            if constexpr (CHECK) {
+                const bool valid = (unsigned)(rel0 + (32 * qb + 8 * g4 + e)) <= span;
+                arg = valid ? arg : -INFINITY;  // p = 0, and with it dS
+            }
+            const float p = __builtin_amdgcn_exp2f(arg);
+            const float pvv = GV ? p * gate : p;
+            const float tt = GV ? fmaf(gate, dov, -Di) : dov - Di;
+            const float ds = GK ? pvv * tt : p * tt;
+            if constexpr ((r & 1) == 0) {
+                hold_p = pvv;
+                hold_s = ds;
+            } else {
+                pb[r >> 3][(r & 7) >> 1] = pack_bf16x2(hold_p, pvv);
+                dsb[r >> 3][(r & 7) >> 1] = pack_bf16x2(hold_s, ds);
+            }
+        };
+        static_for<0, NS>([&](auto mc) {  // run 1
+            constexpr int m = decltype(mc)::value;
+            const bf16x8 cur = ring[m % DEPTH];
+            if constexpr (m & 1) d0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, vreg[m / 2], m < 2 ? zero : d0, 0, 0, 0);
+            else s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, kreg[m / 2], m < 2 ? zero : s0, 0, 0, 0);
+            refill(mc);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        static_for<0, NS>([&](auto mc) {  // run 2
+            constexpr int m = decltype(mc)::value;
+            const bf16x8 cur = ring[(NS + m) % DEPTH];
+            if constexpr (m & 1) d1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, vreg[m / 2], m < 2 ? zero : d1, 0, 0, 0);
+            else s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, kreg[m / 2], m < 2 ? zero : s1, 0, 0, 0);
+            refill(std::integral_constant<int, NS + m>{});
+            static_for<0, EPM>([&](auto ec) {
+                element(std::integral_constant<int, 0>{}, std::integral_constant<int, m * EPM + decltype(ec)::value>{}, s0, d0, pb0, dsb0);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        static_for<0, NS>([&](auto mc) {  // run 3
+            constexpr int m = decltype(mc)::value, i2 = m / 2, x = i2 % DB;
+            const bf16x8 cur = ring[(2 * NS + m) % DEPTH];
+            if constexpr (m & 1) acc_k[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, __builtin_bit_cast(bf16x8, dsb0[i2 / DB]), acc_k[x], 0, 0, 0);
+            else acc_v[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, __builtin_bit_cast(bf16x8, pb0[i2 / DB]), acc_v[x], 0, 0, 0);
+            refill(std::integral_constant<int, 2 * NS + m>{});
+            static_for<0, EPM>([&](auto ec) {
+                element(std::integral_constant<int, 1>{}, std::integral_constant<int, m * EPM + decltype(ec)::value>{}, s1, d1, pb1, dsb1);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        static_for<0, NS>([&](auto mc) {  // run 4
+            constexpr int m = decltype(mc)::value, i2 = m / 2, x = i2 % DB;
+            const bf16x8 cur = ring[(3 * NS + m) % DEPTH];
+            if constexpr (m & 1) acc_k[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, __builtin_bit_cast(bf16x8, dsb1[i2 / DB]), acc_k[x], 0, 0, 0);
+            else acc_v[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, __builtin_bit_cast(bf16x8, pb1[i2 / DB]), acc_v[x], 0, 0, 0);
+            refill(std::integral_constant<int, 3 * NS + m>{});
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    auto tiles = [&](auto gated_c) {
     for (int t = 0; t < ntiles; t++) {
         const int buf = t & 1;
         const int i_first = blo + t * KT;
+        // the dK / dV accumulators stay in the accumulation registers: only MFMAs touch them until the end
+#pragma unroll
+        for (int x = 0; x < DB; x++) asm volatile("" : "+a"(acc_k[x]), "+a"(acc_v[x]));
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();  // tile t landed (rows and per-query values); everybody is done with tile t-1
         float ma = 0, mb_ = 0, mc = 0;
@@ -619,60 +746,15 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
             load_meta(i_first + KT, ma, mb_, mc);
         }
         if (i_first <= whi && i_first + KT - 1 >= wlo) {  // some key of this wave is attended from this tile
-            // both query halves' S and dO.V first, so that the second half's MFMAs can run under the
-            // first half's elementwise work, and the first half's dV / dK MFMAs under the second's
-            f32x16 acc_s[2], acc_d[2];
-#pragma unroll
-            for (int qb = 0; qb < 2; qb++) {
-                const int trw = 32 * qb + col;
-                const int off = (trw % S::NL) * S::GSK + (trw / S::NL) * S::RB + 16 * half;
-#pragma unroll
-                for (int r = 0; r < 16; r++) { acc_s[qb][r] = 0.0f; acc_d[qb][r] = 0.0f; }
-#pragma unroll
-                for (int s = 0; s < DS; s++) {
-                    const bf16x8 qa = *(const bf16x8*)(sm.qr[buf] + off + 32 * s);
-                    const bf16x8 ga = *(const bf16x8*)(sm.gr[buf] + off + 32 * s);
-                    acc_s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kreg[s], acc_s[qb], 0, 0, 0);
-                    acc_d[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ga, vreg[s], acc_d[qb], 0, 0, 0);
-                }
-            }
-#pragma unroll
-            for (int qb = 0; qb < 2; qb++) {
-                bf16x8 pb[2], dsb[2];
-#pragma unroll
-                for (int g4 = 0; g4 < 4; g4++) {
-                    const int qo = 32 * qb + 8 * g4 + 4 * half;  // first of 4 consecutive queries of the tile
-                    const float4 L4 = *(const float4*)&sm.lse2[buf][qo];
-                    const float4 D4 = *(const float4*)&sm.del[buf][qo];
-                    const float4 T4 = *(const float4*)&sm.tq[buf][qo];
-#pragma unroll
-                    for (int e = 0; e < 4; e++) {
-                        const int r = 4 * g4 + e;
-                        const int i = i_first + qo + e;
-                        const float l2 = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
-                        const float Di = e == 0 ? D4.x : e == 1 ? D4.y : e == 2 ? D4.z : D4.w;
-                        const float tq = e == 0 ? T4.x : e == 1 ? T4.y : e == 2 ? T4.z : T4.w;
-                        const bool valid = (i >= lo) && (i <= hi);
-                        const float gate = selected_kind ? clip01(uj - tq) : 1.0f;
-                        const float gk = MODE == 0 ? gate : 1.0f, gv = MODE == 2 ? 1.0f : gate;
-                        const float qk = acc_s[qb][r], dov = acc_d[qb][r];
-                        const float p = __builtin_amdgcn_exp2f(fmaf(qk * gk, c2, -l2));
-                        const float pvv = p * gv;
-                        const float ds = p * fmaf(gv, dov, -Di) * (scale * gk);
-                        pb[r >> 3][r & 7] = (__bf16)(valid ? pvv : 0.0f);
-                        dsb[r >> 3][r & 7] = (__bf16)(valid ? ds : 0.0f);
-                    }
-                }
-#pragma unroll
-                for (int i2 = 0; i2 < 2 * DB; i2++) {
-                    const int g = 2 * qb + i2 / DB, x = i2 % DB;
-                    acc_v[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t_operand(sm.gt[buf], g, x), pb[i2 / DB], acc_v[x], 0, 0, 0);
-                    acc_k[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(t_operand(sm.qt[buf], g, x), dsb[i2 / DB], acc_k[x], 0, 0, 0);
-                }
-            }
+            const bool full = i_first >= wfull_lo && i_first + KT - 1 <= wfull_hi;
+            if (full) tile(gated_c, std::false_type{}, buf, i_first);
+            else tile(gated_c, std::true_type{}, buf, i_first);
         }
         if (more && tid < KT) { sm.lse2[buf ^ 1][tid] = ma; sm.del[buf ^ 1][tid] = mb_; sm.tq[buf ^ 1][tid] = mc; }
     }
+    };
+    if (selected_kind && MODE != 2) tiles(std::true_type{});
+    else tiles(std::false_type{});
     if (kreal) {
         const size_t ro = selected_kind ? ((size_t)bh * n + kidx) * D : ((size_t)bh * n + j) * D;
         float* pk = (selected_kind ? sk32 : dk32) + ro;
@@ -682,7 +764,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
 #pragma unroll
             for (int g4 = 0; g4 < 4; g4++) {
                 const int dcol = 32 * x + 8 * g4 + 4 * half;
-                *(float4*)(pk + dcol) = make_float4(acc_k[x][4 * g4], acc_k[x][4 * g4 + 1], acc_k[x][4 * g4 + 2], acc_k[x][4 * g4 + 3]);
+                *(float4*)(pk + dcol) = make_float4(scale * acc_k[x][4 * g4], scale * acc_k[x][4 * g4 + 1],
+                                                    scale * acc_k[x][4 * g4 + 2], scale * acc_k[x][4 * g4 + 3]);
                 *(float4*)(pv + dcol) = make_float4(acc_v[x][4 * g4], acc_v[x][4 * g4 + 1], acc_v[x][4 * g4 + 2], acc_v[x][4 * g4 + 3]);
             }
     }
