@@ -142,7 +142,7 @@ def decode_leg(steps=256, warm=8):
 
 def mask_bwd_leg(iters=20, warm=3):
     """Config 3: B=4, H=16, n=8192, d=128, k=w=512, bf16: forward, then the SPARSEK mask backward
-    (du of L = sum(dO * O)).  Returns the extra JSON object."""
+    (du of L = sum(dO * O)) and the attention backward (dQ, dK, dV).  Returns the extra JSON object."""
     import torch
 
     import paper_2406_16747_amd as spk
@@ -172,6 +172,10 @@ def mask_bwd_leg(iters=20, warm=3):
 
     fwd_ms = timed(lambda: spk.sparsek_attn_fwd(q, kk, v, u, tau, death, k, w, 0, 1.0))
     bwd_ms = timed(lambda: spk.sparsek_mask_bwd(q, kk, v, u, tau, death, o, lse, dO, k, w, 0, 1.0))
+    abwd_ms = timed(lambda: spk.sparsek_attn_bwd(q, kk, v, u, tau, death, o, lse, dO, k, w, 0, 1.0))
+    # five contractions per attended pair: S = Q.K^T, dO.V^T, dV += P^T.dO, dQ += dS.K, dK += dS^T.Q
+    abwd_flops = 10.0 * d * attended_pairs(n, k, w) * B * H
+    abwd_ach = abwd_flops / (abwd_ms * 1e-3) / 1e12
     # straight-through variant (gate_mode 3): forward without the gate multiplications, gradient at m = 1
     o_st, lse_st = spk.sparsek_attn_fwd(q, kk, v, u, tau, death, k, w, 3, 1.0)
     st_fwd_ms = timed(lambda: spk.sparsek_attn_fwd(q, kk, v, u, tau, death, k, w, 3, 1.0))
@@ -185,6 +189,11 @@ def mask_bwd_leg(iters=20, warm=3):
         "workload": "config 3: B=4 H=16 n=8192 d=128 k=w=512 bf16, Gu=1, gate_mode=0",
         "attn_fwd_ms": fwd_ms, "attn_fwd_tflops": fwd_flops / (fwd_ms * 1e-3) / 1e12,
         "mask_bwd_ms": bwd_ms,
+        "attn_bwd": {"ms": abwd_ms, "fwd_plus_bwd_ms": fwd_ms + abwd_ms + bwd_ms,
+                     "roofline": {"bound": "mfma", "kernel": "attn_bwd_dkv_kernel<128> + attn_bwd_dq_kernel<128> + merge",
+                                  "achieved": abwd_ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                  "frac": abwd_ach / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops": abwd_flops,
+                                  "traffic": None}},
         "straight_through": {"gate_mode": 3, "attn_fwd_ms": st_fwd_ms, "mask_bwd_ms": st_bwd_ms,
                              "mask_bwd_tflops": flops / (st_bwd_ms * 1e-3) / 1e12},
         "roofline": {"bound": "mfma", "kernel": "mask_bwd_mfma_kernel<128> + epilogue", "achieved": ach,

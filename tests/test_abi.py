@@ -78,4 +78,9 @@ def test_argument_validation_needs_no_gpu():
     assert L.sparsek_chunk_to_decode(ctypes.byref(cc), one, sb, 15, one, wb, ctypes.byref(dc), one, db, null) == -2  # < k + w
     dc.k = 9
     assert L.sparsek_chunk_to_decode(ctypes.byref(cc), one, sb, 100, one, wb, ctypes.byref(dc), one, db, null) == -1
-
+    # attention backward: 9 tensors in, 3 out, a workspace
+    assert L.sparsek_attn_bwd_workspace_bytes(ctypes.byref(cfg)) > 0
+    assert L.sparsek_attn_bwd(ctypes.byref(cfg), *([one] * 9), one, one, null, one, 1 << 30, null) == -1  # dv null
+    assert L.sparsek_attn_bwd(ctypes.byref(cfg), *([one] * 9), one, one, one, one, 8, null) == -3
+    bad = spk.SparsekCfg(B=1, H=2, Gu=1, n=16, d=64, k=4, w=4, dtype=spk.BF16, gate_mode=4, softmax_scale=1.0)
+    assert L.sparsek_attn_bwd(ctypes.byref(bad), *([one] * 9), one, one, one, one, 1 << 30, null) == -1

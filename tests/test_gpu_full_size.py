@@ -57,7 +57,7 @@ def test_config2_full(oracle):
 
 def test_config3_full_forward_and_du(oracle):
     require_gpu()
-    say("config 3 full: B=4 H=16 n=8192 d=128 k=w=512, forward + du")
+    say("config 3 full: B=4 H=16 n=8192 d=128 k=w=512, forward + du + dq, dk, dv")
     inp = synth.make(3, with_dO=True)
     k, w, n = inp["k"], inp["w"], inp["n"]
     u = dev(inp["u"])
@@ -80,6 +80,17 @@ def test_config3_full_forward_and_du(oracle):
     scale = np.abs(ref).max()
     err = np.abs(du_g[b] - ref[0]).max()
     assert scale > 0 and err <= 1e-2 * scale, (err, scale)
+    # dQ, dK, dV of the same batch element (the gates held fixed)
+    dq, dk, dv = spk.sparsek_attn_bwd(Q, K, V, u, tau, death, o, lse, dO, k, w, 0, 1.0)
+    torch.cuda.synchronize()
+    say("  oracle dq, dk, dv for batch element", b)
+    refs = oracle.attn_bwd(inp["Q32"][b:b + 1], inp["K32"][b:b + 1], inp["V32"][b:b + 1], inp["u"][b:b + 1],
+                           tau_g[b:b + 1].astype(np.float64), death_g[b:b + 1], inp["dO32"][b:b + 1], k, w, 0, 1.0)
+    for name, g, r in zip(("dq", "dk", "dv"), (dq, dk, dv), refs):
+        g = host(g[b])
+        scale = np.abs(r).max()
+        err = np.abs(g - r[0]).max()
+        assert np.isfinite(g).all() and scale > 0 and err <= 1e-2 * scale, (name, err, scale)
 
 
 def device_recipe(B, H, Gu, n, d, seed):
