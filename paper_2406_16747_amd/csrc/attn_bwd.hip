@@ -73,6 +73,28 @@ __global__ __launch_bounds__(256) void abwd_delta_kernel(const T* __restrict__ o
     if (lane == 0) delta[r] = s;
 }
 
+// The same for bf16 rows of d = 8 * LPR elements: LPR lanes per row, 16 bytes per lane.
+template <int LPR>
+__global__ __launch_bounds__(256) void abwd_delta_bf16_kernel(const uint16_t* __restrict__ o, const uint16_t* __restrict__ dO,
+                                                              size_t rows, float* __restrict__ delta)
+{
+    constexpr int RPB = 256 / LPR;  // rows per workgroup
+    const size_t r = (size_t)blockIdx.x * RPB + threadIdx.x / LPR;
+    if (r >= rows) return;  // whole groups of LPR lanes leave together
+    const size_t off = (r * LPR + threadIdx.x % LPR) * 8;
+    const uint4 a = *(const uint4*)(o + off), b = *(const uint4*)(dO + off);
+    const unsigned aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        s = fmaf(__uint_as_float(aw[i] << 16), __uint_as_float(bw[i] << 16), s);
+        s = fmaf(__uint_as_float(aw[i] & 0xffff0000u), __uint_as_float(bw[i] & 0xffff0000u), s);
+    }
+#pragma unroll
+    for (int m = LPR / 2; m > 0; m >>= 1) s += __shfl_xor(s, m, 64);
+    if (threadIdx.x % LPR == 0) delta[r] = s;
+}
+
 // fp32 accumulators -> storage type
 template <typename T>
 __global__ void abwd_convert_kernel(const float* __restrict__ a, const float* __restrict__ b, T* __restrict__ oa,
@@ -521,8 +543,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
     const int32_t* __restrict__ elist, const int32_t* __restrict__ ecount, const float* __restrict__ lse,
     const uint16_t* __restrict__ dO, const float* __restrict__ delta, float* __restrict__ dk32,
-    float* __restrict__ dv32, float* __restrict__ sk32, float* __restrict__ sv32, int H, int Gu, int n, int w,
-    float scale, int nb)
+    float* __restrict__ dv32, float* __restrict__ sk32, float* __restrict__ sv32, const int32_t* __restrict__ eslot,
+    uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int H, int Gu, int n, int w, float scale, int nb)
 {
     using S = MfmaSmem<D, 64>;
     __shared__ __align__(16) DkvSmem<D> sm;
@@ -755,43 +777,60 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     };
     if (selected_kind && MODE != 2) tiles(std::true_type{});
     else tiles(std::false_type{});
+    // A key that is never selected gets all of its gradient here: round and store it.  The other keys' two parts
+    // (window block, selected block) go to fp32 buffers and are added by the merge kernel.
     if (kreal) {
+        const bool final_here = !selected_kind && eslot[(size_t)row * n + j] < 0;
         const size_t ro = selected_kind ? ((size_t)bh * n + kidx) * D : ((size_t)bh * n + j) * D;
-        float* pk = (selected_kind ? sk32 : dk32) + ro;
-        float* pv = (selected_kind ? sv32 : dv32) + ro;
+        if (final_here) {
 #pragma unroll
-        for (int x = 0; x < DB; x++)
+            for (int x = 0; x < DB; x++)
 #pragma unroll
-            for (int g4 = 0; g4 < 4; g4++) {
-                const int dcol = 32 * x + 8 * g4 + 4 * half;
-                *(float4*)(pk + dcol) = make_float4(scale * acc_k[x][4 * g4], scale * acc_k[x][4 * g4 + 1],
-                                                    scale * acc_k[x][4 * g4 + 2], scale * acc_k[x][4 * g4 + 3]);
-                *(float4*)(pv + dcol) = make_float4(acc_v[x][4 * g4], acc_v[x][4 * g4 + 1], acc_v[x][4 * g4 + 2], acc_v[x][4 * g4 + 3]);
-            }
+                for (int g4 = 0; g4 < 4; g4++) {
+                    const int dcol = 32 * x + 8 * g4 + 4 * half;
+                    uint2 ok, ov;
+                    ok.x = pack_bf16x2(scale * acc_k[x][4 * g4], scale * acc_k[x][4 * g4 + 1]);
+                    ok.y = pack_bf16x2(scale * acc_k[x][4 * g4 + 2], scale * acc_k[x][4 * g4 + 3]);
+                    ov.x = pack_bf16x2(acc_v[x][4 * g4], acc_v[x][4 * g4 + 1]);
+                    ov.y = pack_bf16x2(acc_v[x][4 * g4 + 2], acc_v[x][4 * g4 + 3]);
+                    *(uint2*)(dk + ro + dcol) = ok;
+                    *(uint2*)(dv + ro + dcol) = ov;
+                }
+        } else {
+            float* pk = (selected_kind ? sk32 : dk32) + ro;
+            float* pv = (selected_kind ? sv32 : dv32) + ro;
+#pragma unroll
+            for (int x = 0; x < DB; x++)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; g4++) {
+                    const int dcol = 32 * x + 8 * g4 + 4 * half;
+                    *(float4*)(pk + dcol) = make_float4(scale * acc_k[x][4 * g4], scale * acc_k[x][4 * g4 + 1],
+                                                        scale * acc_k[x][4 * g4 + 2], scale * acc_k[x][4 * g4 + 3]);
+                    *(float4*)(pv + dcol) = make_float4(acc_v[x][4 * g4], acc_v[x][4 * g4 + 1], acc_v[x][4 * g4 + 2], acc_v[x][4 * g4 + 3]);
+                }
+        }
     }
 }
 
-// dk = dk32 (+ sk32 at the key's slot when it was ever selected), rounded to bf16; same for dv.
+// For every ever-selected key (list slot e, position j): dk_j = dk32_j + sk32_e rounded to bf16; same for dv.
 __global__ __launch_bounds__(256) void abwd_merge_kernel(const float* __restrict__ dk32, const float* __restrict__ dv32,
                                                          const float* __restrict__ sk32, const float* __restrict__ sv32,
-                                                         const int32_t* __restrict__ eslot, int H, int Gu, int n, int d4,
-                                                         uint16_t* __restrict__ dk, uint16_t* __restrict__ dv)
+                                                         const int32_t* __restrict__ elist, const int32_t* __restrict__ ecount,
+                                                         int H, int Gu, int n, int d4, uint16_t* __restrict__ dk,
+                                                         uint16_t* __restrict__ dv)
 {
     const int bh = blockIdx.y;
     const int b = bh / H, h = bh % H;
     const int row = b * Gu + (Gu == 1 ? 0 : h);
-    const size_t total = (size_t)n * d4;  // float4 units of this head
+    const size_t total = (size_t)ecount[row] * d4;  // float4 units of this head's list
     for (size_t x = (size_t)blockIdx.x * 256 + threadIdx.x; x < total; x += (size_t)gridDim.x * 256) {
-        const int j = (int)(x / d4), c4 = (int)(x % d4);
-        const size_t src = ((size_t)bh * n + j) * d4 + c4;
+        const int e = (int)(x / d4), c4 = (int)(x % d4);
+        const int j = elist[(size_t)row * n + e];
+        const size_t src = ((size_t)bh * n + j) * d4 + c4, s2 = ((size_t)bh * n + e) * d4 + c4;
         float4 a = ((const float4*)dk32)[src], c = ((const float4*)dv32)[src];
-        const int slot = eslot[(size_t)row * n + j];
-        if (slot >= 0) {
-            const size_t s2 = ((size_t)bh * n + slot) * d4 + c4;
-            const float4 a2 = ((const float4*)sk32)[s2], c2 = ((const float4*)sv32)[s2];
-            a.x += a2.x; a.y += a2.y; a.z += a2.z; a.w += a2.w;
-            c.x += c2.x; c.y += c2.y; c.z += c2.z; c.w += c2.w;
-        }
+        const float4 a2 = ((const float4*)sk32)[s2], c2 = ((const float4*)sv32)[s2];
+        a.x += a2.x; a.y += a2.y; a.z += a2.z; a.w += a2.w;
+        c.x += c2.x; c.y += c2.y; c.z += c2.z; c.w += c2.w;
         ushort4 oa, oc;
         oa.x = f32_to_bf16(a.x); oa.y = f32_to_bf16(a.y); oa.z = f32_to_bf16(a.z); oa.w = f32_to_bf16(a.w);
         oc.x = f32_to_bf16(c.x); oc.y = f32_to_bf16(c.y); oc.z = f32_to_bf16(c.z); oc.w = f32_to_bf16(c.w);
@@ -804,13 +843,13 @@ template <int D>
 static void launch_dkv_mfma(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                             const float* tau, const int32_t* death, const int32_t* elist, const int32_t* ecount,
                             const float* lse, const void* dO, const float* delta, float* dk32, float* dv32,
-                            float* sk32, float* sv32, int nb, hipStream_t st)
+                            float* sk32, float* sv32, const int32_t* eslot, void* dk, void* dv, int nb, hipStream_t st)
 {
     dim3 grid(c.B * c.H, 2 * nb);  // per head: (up to) nb blocks of selected keys, then the nb window blocks
 #define SPK_LAUNCH_KV(MODE)                                                                                         \
     hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q, (const uint16_t*)k, \
                        (const uint16_t*)v, u, tau, death, elist, ecount, lse, (const uint16_t*)dO, delta, dk32, dv32,  \
-                       sk32, sv32, c.H, c.Gu, c.n, c.w, c.softmax_scale, nb)
+                       sk32, sv32, eslot, (uint16_t*)dk, (uint16_t*)dv, c.H, c.Gu, c.n, c.w, c.softmax_scale, nb)
     if (c.gate_mode == 0) SPK_LAUNCH_KV(0);
     else if (c.gate_mode == 1) SPK_LAUNCH_KV(1);
     else SPK_LAUNCH_KV(2);
@@ -844,8 +883,15 @@ int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
         hipLaunchKernelGGL(abwd_convert_kernel<float>, dim3(2048), dim3(256), 0, st, dk32, dv32, (float*)dk, (float*)dv,
                            nelem);
     } else {
-        hipLaunchKernelGGL(abwd_delta_kernel<uint16_t>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st,
-                           (const uint16_t*)o, (const uint16_t*)dO, rows, c.d, delta);
+        if (c.d == 128)
+            hipLaunchKernelGGL(abwd_delta_bf16_kernel<16>, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st,
+                               (const uint16_t*)o, (const uint16_t*)dO, rows, delta);
+        else if (c.d == 64)
+            hipLaunchKernelGGL(abwd_delta_bf16_kernel<8>, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st,
+                               (const uint16_t*)o, (const uint16_t*)dO, rows, delta);
+        else
+            hipLaunchKernelGGL(abwd_delta_kernel<uint16_t>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st,
+                               (const uint16_t*)o, (const uint16_t*)dO, rows, c.d, delta);
         if (mfma) {
             int32_t* elist = (int32_t*)(base + W.elist);
             int32_t* ecount = (int32_t*)(base + W.ecount);
@@ -855,17 +901,17 @@ int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
             hipLaunchKernelGGL(abwd_elist_kernel, dim3(c.B * c.Gu), dim3(1024), 0, st, death, c.n, elist, ecount, eslot);
             if (c.d == 64) {
                 launch_dq_mfma<64>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st);
-                launch_dkv_mfma<64>(c, q, k, v, u, tau, death, elist, ecount, lse, dO, delta, dk32, dv32, sk32, sv32, nb,
-                                    st);
+                launch_dkv_mfma<64>(c, q, k, v, u, tau, death, elist, ecount, lse, dO, delta, dk32, dv32, sk32, sv32, eslot,
+                                    dk, dv, nb, st);
             } else {
                 launch_dq_mfma<128>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st);
-                launch_dkv_mfma<128>(c, q, k, v, u, tau, death, elist, ecount, lse, dO, delta, dk32, dv32, sk32, sv32, nb,
-                                     st);
+                launch_dkv_mfma<128>(c, q, k, v, u, tau, death, elist, ecount, lse, dO, delta, dk32, dv32, sk32, sv32, eslot,
+                                     dk, dv, nb, st);
             }
             const int d4 = c.d / 4;
             const int gx = (int)std::min<size_t>(((size_t)c.n * d4 + 255) / 256, 1024);
-            hipLaunchKernelGGL(abwd_merge_kernel, dim3(gx, c.B * c.H), dim3(256), 0, st, dk32, dv32, sk32, sv32, eslot, c.H,
-                               c.Gu, c.n, d4, (uint16_t*)dk, (uint16_t*)dv);
+            hipLaunchKernelGGL(abwd_merge_kernel, dim3(gx, c.B * c.H), dim3(256), 0, st, dk32, dv32, sk32, sv32, elist,
+                               ecount, c.H, c.Gu, c.n, d4, (uint16_t*)dk, (uint16_t*)dv);
         } else {
             hipLaunchKernelGGL(attn_bwd_generic_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)q,
                                (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, lse,
