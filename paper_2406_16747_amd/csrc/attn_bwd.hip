@@ -209,6 +209,16 @@ __global__ __launch_bounds__(256) void attn_bwd_generic_kernel(
 // lands in LDS twice (a second direct-to-LDS load of rows that are in cache by then); the tile is
 // single-buffered and the two workgroups of a CU cover each other's gathers.
 // ---------------------------------------------------------------------------------
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2v __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+// two floats rounded to bf16 (nearest even), the first in the low half
+__device__ __forceinline__ unsigned pack_bf16x2(float a, float b)
+{
+    f32x2v f = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2v));
+}
+
 template <int D>
 struct DqSmem {
     using S = MfmaSmem<D, 64>;
@@ -349,7 +359,10 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
                     acc_s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], acc_s, 0, 0, 0);
                     acc_d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dreg[s], acc_d, 0, 0, 0);
                 }
-                bf16x8 dsb[2];
+                // ds_ij without the softmax scale (applied once to the finished dQ); a pair that is not attended
+                // gets p = 0 through the exponent
+                u32x4 dsb[2];
+                float hold = 0.0f;
 #pragma unroll
                 for (int g4 = 0; g4 < 4; g4++) {
                     const int kb = base + 32 * mb + 8 * g4 + 4 * half;
@@ -364,17 +377,26 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
                         const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
                         // attended  <=>  j <= i <= w - 1 + death_j; inside the window the gate is 1
                         const bool valid = (Jj <= qv) && (qv <= Lj);
-                        const float gate = (qv - Jj < w) ? 1.0f : clip01(uj - tau_q);
-                        const float gk = MODE == 0 ? gate : 1.0f, gv = MODE == 2 ? 1.0f : gate;
                         const float qk = acc_s[r], dov = acc_d[r];
-                        const float p = __builtin_amdgcn_exp2f(fmaf(qk * gk, c2, -lse2));
-                        const float ds = p * fmaf(gv, dov, -Di) * (scale * gk);
-                        dsb[r >> 3][r & 7] = (__bf16)(valid ? ds : 0.0f);
+                        float ds;
+                        if (MODE == 2) {
+                            const float arg = fmaf(qk, c2, -lse2);
+                            ds = __builtin_amdgcn_exp2f(valid ? arg : -INFINITY) * (dov - Di);
+                        } else {
+                            const float gate = (qv - Jj < w) ? 1.0f : clip01(uj - tau_q);
+                            const float arg = MODE == 0 ? fmaf(qk, gate * c2, -lse2) : fmaf(qk, c2, -lse2);
+                            const float p = __builtin_amdgcn_exp2f(valid ? arg : -INFINITY);
+                            ds = p * fmaf(gate, dov, -Di);
+                            if (MODE == 0) ds *= gate;
+                        }
+                        if ((r & 1) == 0) hold = ds;
+                        else dsb[r >> 3][(r & 7) >> 1] = pack_bf16x2(hold, ds);
                     }
                 }
 #pragma unroll
                 for (int i = 0; i < 2 * DB; i++)
-                    acc_q[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt_operand(2 * mb + i / DB, i % DB), dsb[i / DB],
+                    acc_q[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt_operand(2 * mb + i / DB, i % DB),
+                                                                            __builtin_bit_cast(bf16x8, dsb[i / DB]),
                                                                             acc_q[i % DB], 0, 0, 0);
             }
         }
@@ -387,7 +409,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
             for (int g4 = 0; g4 < 4; g4++) {
                 bf16x4 pk;
 #pragma unroll
-                for (int e = 0; e < 4; e++) pk[e] = (__bf16)acc_q[x][4 * g4 + e];
+                for (int e = 0; e < 4; e++) pk[e] = (__bf16)(scale * acc_q[x][4 * g4 + e]);
                 *(bf16x4*)(orow + 32 * x + 8 * g4 + 4 * half) = pk;
             }
         }
@@ -514,16 +536,6 @@ __global__ __launch_bounds__(1024) void abwd_elist_kernel(const int32_t* __restr
         if (sel) el[slot] = j;
         if (j < j_end) es[j] = slot;
     }
-}
-
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2v __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
-// two floats rounded to bf16 (nearest even), the first in the low half
-__device__ __forceinline__ unsigned pack_bf16x2(float a, float b)
-{
-    f32x2v f = {a, b};
-    return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2v));
 }
 
 template <int D>
