@@ -60,3 +60,19 @@ def test_attn_bwd_config3_recipe_reduced(oracle):
     say("attn_bwd config 3 reduced")
     inp = synth.make(3, with_dO=True, B=1, H=2, n=2048, k=128, w=128)
     run_bwd(oracle, inp, 0)
+
+
+@pytest.mark.parametrize("n,d,k,w,Gu,gate_mode", [
+    # a top-k list that spans two metadata segments of the dQ kernel and many blocks of selected keys
+    (2600, 128, 1500, 256, 1, 0), (2600, 128, 1500, 256, 1, 1),
+    # d = 64 with one score row per head, ragged tail, window narrower than a query tile
+    (1500, 64, 300, 40, 2, 0), (1500, 64, 300, 40, 2, 3),
+    # selection only (w = 0) and window only (k = 0) on the MFMA path
+    (1100, 128, 200, 0, 1, 0), (1100, 64, 0, 300, 1, 2),
+])
+def test_attn_bwd_medium(oracle, n, d, k, w, Gu, gate_mode):
+    require_gpu()
+    say("attn_bwd medium", n, d, k, w, Gu, gate_mode)
+    inp = synth.make(3, Gu=Gu, seed=3 * n + k, with_dO=True, B=1, H=2, n=n, d=d, k=k, w=w, dtype="bf16",
+                     qk_div=float(np.sqrt(d)) / 2)
+    run_bwd(oracle, inp, gate_mode)
