@@ -201,6 +201,20 @@ int sparsek_chunk_init(const sparsek_chunk_cfg *cfg, void *state, size_t state_b
 int sparsek_chunk_prefill(const sparsek_chunk_cfg *cfg, void *state, size_t state_bytes, int32_t c,
                           const void *q, const void *k, const void *v, const float *u, void *o, void *ws,
                           size_t ws_bytes, void *stream);
+/* Backward of the chunk that the last sparsek_chunk_prefill call on `fwd_ws` processed, with the gradient of the
+ * cache stopped (training with chunk-wise recurrence, Algorithm 3): for L = sum(dO * o) over the chunk's outputs,
+ *     dq, dk, dv out [B,H,c,d]  gradients with respect to the chunk's own q, k, v (gates held fixed),
+ *     du out [B,Gu,c] fp32      gradient with respect to the chunk's own scores through the soft gates and thresholds
+ * (the retained keys of earlier chunks and their scores are constants).  Equal to the gradients of the unchunked
+ * operator for an upstream gradient that vanishes outside the chunk's rows, restricted to the chunk's positions.
+ * q, o, dO in [B,H,c,d]: the chunk's queries, the outputs the forward call returned, their upstream gradient; c as
+ * in that call.  fwd_ws: that call's workspace, untouched since (it holds the chunk's virtual sequence; read only).
+ * ws: scratch of sparsek_chunk_bwd_workspace_bytes(cfg) bytes.  bf16 with d = 64 or 128 only (UNSUPPORTED otherwise;
+ * the size query then returns 0). */
+size_t sparsek_chunk_bwd_workspace_bytes(const sparsek_chunk_cfg *cfg);
+int sparsek_chunk_bwd(const sparsek_chunk_cfg *cfg, int32_t c, const void *q, const void *o, const void *dO,
+                      const void *fwd_ws, size_t fwd_ws_bytes, void *dq, void *dk, void *dv, float *du, void *ws,
+                      size_t ws_bytes, void *stream);
 /* Hands the sequence over to the single-token decode: fills decode_state (of sparsek_decode_state_bytes(dcfg)
  * bytes) with the state after the n_consumed tokens passed so far, so that sparsek_decode_step continues exactly
  * where the chunks ended.  dcfg must agree with cfg in B, H, Gu, d, k, w and dtype.  n_consumed (the caller's count

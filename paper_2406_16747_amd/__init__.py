@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     sparsek_scores,
     ChunkState,
     sparsek_chunk_prefill,
+    sparsek_chunk_bwd,
     sparsek_chunk_status,
     sparsek_chunk_to_decode,
     sparsek_decode_init,

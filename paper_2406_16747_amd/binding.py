@@ -65,12 +65,14 @@ def lib():
         L.sparsek_scores.argtypes = [scfgp, vp, vp, vp, vp, sz, vp]
         L.sparsek_scores.restype = C.c_int
         ccfgp = C.POINTER(SparsekChunkCfg)
-        for name in ("sparsek_chunk_state_bytes", "sparsek_chunk_workspace_bytes"):
+        for name in ("sparsek_chunk_state_bytes", "sparsek_chunk_workspace_bytes", "sparsek_chunk_bwd_workspace_bytes"):
             getattr(L, name).restype = sz
             getattr(L, name).argtypes = [ccfgp]
         L.sparsek_chunk_init.argtypes = [ccfgp, vp, sz, vp]
         L.sparsek_chunk_prefill.argtypes = [ccfgp, vp, sz, i32] + [vp] * 5 + [vp, sz, vp]
         L.sparsek_chunk_status.argtypes = [ccfgp, vp, vp, vp, vp]
+        L.sparsek_chunk_bwd.argtypes = [ccfgp, i32, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, sz, vp]
+        L.sparsek_chunk_bwd.restype = C.c_int
         L.sparsek_chunk_to_decode.argtypes = [ccfgp, vp, sz, C.c_int64, vp, sz, dcfgp, vp, sz, vp]
         for name in ("sparsek_chunk_init", "sparsek_chunk_prefill", "sparsek_chunk_status", "sparsek_chunk_to_decode"):
             getattr(L, name).restype = C.c_int
@@ -243,6 +245,24 @@ def sparsek_chunk_prefill(state, q, k, v, u):
     check(lib().sparsek_chunk_prefill(C.byref(state.cfg), _ptr(state.buf), state.buf.numel(), c, _ptr(q), _ptr(k),
                                       _ptr(v), _ptr(u), _ptr(o), _ptr(state.ws), state.ws.numel(), _stream()))
     return o
+
+
+def sparsek_chunk_bwd(state, q, o, dO):
+    """Gradients (dq, dk, dv [B,H,c,d], du [B,Gu,c]) of sum(dO * o) for the chunk that the last
+    sparsek_chunk_prefill call on this state processed, the retained keys of earlier chunks held constant."""
+    torch = _torch()
+    c = q.shape[2]
+    nbytes = lib().sparsek_chunk_bwd_workspace_bytes(C.byref(state.cfg))
+    if nbytes == 0:
+        raise ValueError("sparsek_chunk_bwd: unsupported configuration (bf16 with d = 64 or 128 only)")
+    if getattr(state, "bwd_ws", None) is None or state.bwd_ws.numel() < nbytes:
+        state.bwd_ws = torch.empty(nbytes, dtype=torch.uint8, device=q.device)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    du = torch.empty((state.cfg.B, state.cfg.Gu, c), dtype=torch.float32, device=q.device)
+    check(lib().sparsek_chunk_bwd(C.byref(state.cfg), c, _ptr(q), _ptr(o), _ptr(dO), _ptr(state.ws), state.ws.numel(),
+                                  _ptr(dq), _ptr(dk), _ptr(dv), _ptr(du), _ptr(state.bwd_ws), state.bwd_ws.numel(),
+                                  _stream()))
+    return dq, dk, dv, du
 
 
 def sparsek_chunk_to_decode(state, n_consumed, decode_state):

@@ -91,13 +91,6 @@ int sparsek_attn_fwd(const sparsek_cfg* cfg, const void* q, const void* k, const
 
 }  // extern "C"
 
-// ---- attention backward (attn_bwd.hip) ----
-namespace spk {
-size_t attn_bwd_ws_bytes(const sparsek_cfg& c);
-int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
-                    const float* tau, const int32_t* death, const void* o, const float* lse, const void* dO, void* dq,
-                    void* dk, void* dv, void* ws, hipStream_t st);
-}  // namespace spk
 
 extern "C" {
 
@@ -273,6 +266,9 @@ int chunk_status(const sparsek_chunk_cfg& c, const void* state, int32_t* host_co
                  hipStream_t st);
 int launch_chunk_to_decode(const sparsek_chunk_cfg& c, void* state, void* ws, const sparsek_decode_cfg& dc,
                            void* dstate, hipStream_t st);
+size_t chunk_bwd_ws_bytes(const sparsek_chunk_cfg& c);
+int launch_chunk_bwd(const sparsek_chunk_cfg& c, int clen, const void* q, const void* o, const void* dO,
+                     const void* fwd_ws, void* dq, void* dk, void* dv, float* du, void* ws, hipStream_t st);
 }  // namespace spk
 
 namespace {
@@ -326,6 +322,26 @@ int sparsek_chunk_prefill(const sparsek_chunk_cfg* cfg, void* state, size_t stat
     if (c < 1 || c > cfg->chunk_max) return SPARSEK_ERR_INVALID_ARG;
     if (state_bytes < spk::chunk_state_bytes(*cfg) || ws_bytes < spk::chunk_ws_bytes(*cfg)) return SPARSEK_ERR_WORKSPACE;
     return spk::launch_chunk_prefill(*cfg, state, c, q, k, v, u, o, ws, (hipStream_t)stream);
+}
+
+size_t sparsek_chunk_bwd_workspace_bytes(const sparsek_chunk_cfg* cfg)
+{
+    if (check_chunk(cfg)) return 0;
+    if (cfg->dtype != SPARSEK_BF16 || (cfg->d != 64 && cfg->d != 128)) return 0;
+    return spk::chunk_bwd_ws_bytes(*cfg);
+}
+
+int sparsek_chunk_bwd(const sparsek_chunk_cfg* cfg, int32_t c, const void* q, const void* o, const void* dO,
+                      const void* fwd_ws, size_t fwd_ws_bytes, void* dq, void* dk, void* dv, float* du, void* ws,
+                      size_t ws_bytes, void* stream)
+{
+    int rc = check_chunk(cfg);
+    if (rc) return rc;
+    if (!q || !o || !dO || !fwd_ws || !dq || !dk || !dv || !du || !ws) return SPARSEK_ERR_INVALID_ARG;
+    if (c < 1 || c > cfg->chunk_max) return SPARSEK_ERR_INVALID_ARG;
+    if (cfg->dtype != SPARSEK_BF16 || (cfg->d != 64 && cfg->d != 128)) return SPARSEK_ERR_UNSUPPORTED;
+    if (fwd_ws_bytes < spk::chunk_ws_bytes(*cfg) || ws_bytes < spk::chunk_bwd_ws_bytes(*cfg)) return SPARSEK_ERR_WORKSPACE;
+    return spk::launch_chunk_bwd(*cfg, c, q, o, dO, fwd_ws, dq, dk, dv, du, ws, (hipStream_t)stream);
 }
 
 int sparsek_chunk_to_decode(const sparsek_chunk_cfg* cfg, void* state, size_t state_bytes, int64_t n_consumed,

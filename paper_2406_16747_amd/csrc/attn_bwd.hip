@@ -236,7 +236,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
     const int32_t* __restrict__ lists, const int32_t* __restrict__ counts, const float* __restrict__ lse,
     const uint16_t* __restrict__ dO, const float* __restrict__ delta, uint16_t* __restrict__ dq, int H, int Gu, int n,
-    int k, int w, float scale, int nb, int BH)
+    int k, int w, float scale, int nb, int BH, int q_begin, const int32_t* __restrict__ first_valid, int q_rows)
 {
     using S = MfmaSmem<D, 64>;
     __shared__ __align__(16) DqSmem<D> sm;
@@ -258,6 +258,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, col = lane & 31;
     const int i0 = blk * QB;
+    // queries before q_begin do not exist; q, dO, lse, delta and dq then hold q_rows rows per head from query q_begin
+    if (i0 + QB <= q_begin) return;
+    const ptrdiff_t qo = q_rows ? (ptrdiff_t)bh * q_rows - q_begin : (ptrdiff_t)bh * n;
     const unsigned char* kh = (const unsigned char*)(kk + (size_t)bh * n * D);
     const unsigned char* vh = (const unsigned char*)(v + (size_t)bh * n * D);
     const float* ur = u + (size_t)row * n;
@@ -265,7 +268,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const int32_t* dr = death + (size_t)row * n;
     const int32_t* list = lists + ((size_t)row * nb + blk) * (size_t)(k > 0 ? k : 1);
     const int cnt = counts[(size_t)row * nb + blk];
-    const int c0 = max(0, i0 - w + 1);
+    const int c0 = max(max(0, i0 - w + 1), first_valid ? first_valid[row] : 0);
     const int c_end = min(n - 1, i0 + QB - 1);
     const int nkl = (cnt + KT - 1) / KT * KT;
     const int nkc = (c_end - c0 + 1 + KT - 1) / KT * KT;
@@ -277,12 +280,12 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const bool wave_live = qa < n;
     const int qv = qi < n ? qi : -1;  // -1: no key passes "j <= query"
     const float tau_q = (qi < n && qi - w >= 0) ? tr[qi - w] : 0.0f;
-    const float lse2 = lse[(size_t)bh * n + qrow] * 1.4426950408889634f;
-    const float Di = delta[(size_t)bh * n + qrow];
+    const float lse2 = lse[qo + qrow] * 1.4426950408889634f;
+    const float Di = delta[qo + qrow];
     bf16x8 qreg[DS], dreg[DS];
 #pragma unroll
     for (int s = 0; s < DS; s++) {
-        const size_t off = ((size_t)bh * n + qrow) * D + 16 * s + 8 * half;
+        const size_t off = (size_t)(qo + qrow) * D + 16 * s + 8 * half;
         qreg[s] = *(const bf16x8*)(q + off);
         dreg[s] = *(const bf16x8*)(dO + off);
     }
@@ -402,7 +405,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
         }
     }
     if (qi < n) {
-        uint16_t* orow = dq + ((size_t)bh * n + qi) * D;
+        uint16_t* orow = dq + (size_t)(qo + qi) * D;
 #pragma unroll
         for (int x = 0; x < DB; x++) {
 #pragma unroll
@@ -419,14 +422,15 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
 template <int D>
 static void launch_dq_mfma(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                            const float* tau, const int32_t* death, const int32_t* lists, const int32_t* counts,
-                           const float* lse, const void* dO, const float* delta, void* dq, int nb, hipStream_t st)
+                           const float* lse, const void* dO, const float* delta, void* dq, int nb, hipStream_t st,
+                           int q_begin, const int32_t* first_valid, int q_rows)
 {
     const int BH = c.B * c.H;
     dim3 grid(nb * BH);
 #define SPK_LAUNCH_DQ(MODE)                                                                                        \
     hipLaunchKernelGGL((attn_bwd_dq_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q, (const uint16_t*)k, \
                        (const uint16_t*)v, u, tau, death, lists, counts, lse, (const uint16_t*)dO, delta,          \
-                       (uint16_t*)dq, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH)
+                       (uint16_t*)dq, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH, q_begin, first_valid, q_rows)
     if (c.gate_mode == 0) SPK_LAUNCH_DQ(0);
     else if (c.gate_mode == 1) SPK_LAUNCH_DQ(1);
     else SPK_LAUNCH_DQ(2);
@@ -468,7 +472,7 @@ __device__ __forceinline__ int wave_min_i32(int x)
 // A counting sort whose result does not depend on timing: every wave owns a contiguous range of positions
 // and its own cursor per bucket.
 constexpr int EBK = 512;
-__global__ __launch_bounds__(1024) void abwd_elist_kernel(const int32_t* __restrict__ death, int n,
+__global__ __launch_bounds__(1024) void abwd_elist_kernel(const int32_t* __restrict__ death, int n, int j_min,
                                                           int32_t* __restrict__ elist, int32_t* __restrict__ ecount,
                                                           int32_t* __restrict__ eslot)
 {
@@ -486,7 +490,7 @@ __global__ __launch_bounds__(1024) void abwd_elist_kernel(const int32_t* __restr
     for (int j0 = j_begin; j0 < j_end; j0 += 64) {
         const int j = j0 + lane;
         const int dj = j < j_end ? dr[j] : 0;
-        if (j < j_end && dj > j) atomicAdd(&cur[wv][dj / bw], 1);
+        if (j < j_end && dj > j && j >= j_min) atomicAdd(&cur[wv][dj / bw], 1);
     }
     __syncthreads();
     if (tid < EBK) {  // per bucket: each wave's offset inside the bucket, and the bucket's size
@@ -520,7 +524,7 @@ __global__ __launch_bounds__(1024) void abwd_elist_kernel(const int32_t* __restr
     for (int j0 = j_begin; j0 < j_end; j0 += 64) {
         const int j = j0 + lane;
         const int dj = j < j_end ? dr[j] : 0;
-        const bool sel = j < j_end && dj > j;
+        const bool sel = j < j_end && dj > j && j >= j_min;  // keys before j_min receive no gradient
         const int bkt = sel ? dj / bw : -1;
         int slot = -1;
         unsigned long long rem = __ballot(sel);
@@ -556,7 +560,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     const int32_t* __restrict__ elist, const int32_t* __restrict__ ecount, const float* __restrict__ lse,
     const uint16_t* __restrict__ dO, const float* __restrict__ delta, float* __restrict__ dk32,
     float* __restrict__ dv32, float* __restrict__ sk32, float* __restrict__ sv32, const int32_t* __restrict__ eslot,
-    uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int H, int Gu, int n, int w, float scale, int nb)
+    uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int H, int Gu, int n, int w, float scale, int nb,
+    int q_begin, int q_rows)
 {
     using S = MfmaSmem<D, 64>;
     __shared__ __align__(16) DkvSmem<D> sm;
@@ -576,6 +581,10 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     const int32_t* dr = death + (size_t)row * n;
     const int ne = selected_kind ? ecount[row] : n;
     if (kblk * 128 >= ne) return;  // no such block of selected keys
+    // Keys before q_begin receive no gradient and queries before it do not exist (q_begin is a multiple of
+    // 128); q, dO, lse, delta, dk and dv then hold q_rows rows per head from position q_begin.
+    if (!selected_kind && kblk * 128 + 128 <= q_begin) return;
+    const ptrdiff_t qo = q_rows ? (ptrdiff_t)bh * q_rows - q_begin : (ptrdiff_t)bh * n;
 
     // ---- this lane's key and the queries that attend it ----
     const int kidx = kblk * 128 + 32 * wv + col;
@@ -614,8 +623,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     const int bhi = max(max(sm.red[1][0], sm.red[1][1]), max(sm.red[1][2], sm.red[1][3]));
     const int ntiles = blo > bhi ? 0 : (bhi - blo) / KT + 1;  // (uniform) 0: nothing attends these keys
     const float c2 = scale * 1.4426950408889634f;
-    const unsigned char* qh = (const unsigned char*)(q + (size_t)bh * n * D);
-    const unsigned char* gh = (const unsigned char*)(dO + (size_t)bh * n * D);
+    const unsigned char* qh = (const unsigned char*)(q + qo * D);
+    const unsigned char* gh = (const unsigned char*)(dO + qo * D);
 
     const int r16 = lane & 15, grp2 = (lane >> 4) & 1;
     const int tcol = (16 * grp2 + 4 * (r16 & 3)) * 2;
@@ -646,8 +655,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     auto load_meta = [&](int i_first, float& a, float& bq, float& cq) {
         if (tid < KT) {
             const int i = min(i_first + tid, n - 1);
-            a = lse[(size_t)bh * n + i] * 1.4426950408889634f;
-            bq = delta[(size_t)bh * n + i];
+            a = lse[qo + i] * 1.4426950408889634f;
+            bq = delta[qo + i];
             cq = tr[max(i - w, 0)];
         }
     };
@@ -794,6 +803,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     if (kreal) {
         const bool final_here = !selected_kind && eslot[(size_t)row * n + j] < 0;
         const size_t ro = selected_kind ? ((size_t)bh * n + kidx) * D : ((size_t)bh * n + j) * D;
+        const size_t fo = (size_t)(qo + j) * D;
         if (final_here) {
 #pragma unroll
             for (int x = 0; x < DB; x++)
@@ -805,8 +815,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
                     ok.y = pack_bf16x2(scale * acc_k[x][4 * g4 + 2], scale * acc_k[x][4 * g4 + 3]);
                     ov.x = pack_bf16x2(acc_v[x][4 * g4], acc_v[x][4 * g4 + 1]);
                     ov.y = pack_bf16x2(acc_v[x][4 * g4 + 2], acc_v[x][4 * g4 + 3]);
-                    *(uint2*)(dk + ro + dcol) = ok;
-                    *(uint2*)(dv + ro + dcol) = ov;
+                    *(uint2*)(dk + fo + dcol) = ok;
+                    *(uint2*)(dv + fo + dcol) = ov;
                 }
         } else {
             float* pk = (selected_kind ? sk32 : dk32) + ro;
@@ -829,9 +839,10 @@ __global__ __launch_bounds__(256) void abwd_merge_kernel(const float* __restrict
                                                          const float* __restrict__ sk32, const float* __restrict__ sv32,
                                                          const int32_t* __restrict__ elist, const int32_t* __restrict__ ecount,
                                                          int H, int Gu, int n, int d4, uint16_t* __restrict__ dk,
-                                                         uint16_t* __restrict__ dv)
+                                                         uint16_t* __restrict__ dv, int q_begin, int q_rows)
 {
     const int bh = blockIdx.y;
+    const ptrdiff_t qo = q_rows ? (ptrdiff_t)bh * q_rows - q_begin : (ptrdiff_t)bh * n;  // rows of dk, dv
     const int b = bh / H, h = bh % H;
     const int row = b * Gu + (Gu == 1 ? 0 : h);
     const size_t total = (size_t)ecount[row] * d4;  // float4 units of this head's list
@@ -846,8 +857,9 @@ __global__ __launch_bounds__(256) void abwd_merge_kernel(const float* __restrict
         ushort4 oa, oc;
         oa.x = f32_to_bf16(a.x); oa.y = f32_to_bf16(a.y); oa.z = f32_to_bf16(a.z); oa.w = f32_to_bf16(a.w);
         oc.x = f32_to_bf16(c.x); oc.y = f32_to_bf16(c.y); oc.z = f32_to_bf16(c.z); oc.w = f32_to_bf16(c.w);
-        ((ushort4*)dk)[src] = oa;
-        ((ushort4*)dv)[src] = oc;
+        const size_t dst = (size_t)(qo + j) * d4 + c4;
+        ((ushort4*)dk)[dst] = oa;
+        ((ushort4*)dv)[dst] = oc;
     }
 }
 
@@ -855,13 +867,15 @@ template <int D>
 static void launch_dkv_mfma(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                             const float* tau, const int32_t* death, const int32_t* elist, const int32_t* ecount,
                             const float* lse, const void* dO, const float* delta, float* dk32, float* dv32,
-                            float* sk32, float* sv32, const int32_t* eslot, void* dk, void* dv, int nb, hipStream_t st)
+                            float* sk32, float* sv32, const int32_t* eslot, void* dk, void* dv, int nb, hipStream_t st,
+                            int q_begin, int q_rows)
 {
     dim3 grid(c.B * c.H, 2 * nb);  // per head: (up to) nb blocks of selected keys, then the nb window blocks
 #define SPK_LAUNCH_KV(MODE)                                                                                         \
     hipLaunchKernelGGL((attn_bwd_dkv_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q, (const uint16_t*)k, \
                        (const uint16_t*)v, u, tau, death, elist, ecount, lse, (const uint16_t*)dO, delta, dk32, dv32,  \
-                       sk32, sv32, eslot, (uint16_t*)dk, (uint16_t*)dv, c.H, c.Gu, c.n, c.w, c.softmax_scale, nb)
+                       sk32, sv32, eslot, (uint16_t*)dk, (uint16_t*)dv, c.H, c.Gu, c.n, c.w, c.softmax_scale, nb, q_begin, \
+                       q_rows)
     if (c.gate_mode == 0) SPK_LAUNCH_KV(0);
     else if (c.gate_mode == 1) SPK_LAUNCH_KV(1);
     else SPK_LAUNCH_KV(2);
@@ -870,18 +884,20 @@ static void launch_dkv_mfma(const sparsek_cfg& c, const void* q, const void* k, 
 
 int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                     const float* tau, const int32_t* death, const void* o, const float* lse, const void* dO, void* dq,
-                    void* dk, void* dv, void* ws, hipStream_t st)
+                    void* dk, void* dv, void* ws, hipStream_t st, int q_begin, const int32_t* first_valid, int q_rows)
 {
     const AbwdWs W = abwd_ws(c);
     char* base = (char*)ws;
     const int nb = (c.n + QB - 1) / QB;
-    const size_t BH = (size_t)c.B * c.H, rows = BH * c.n, nelem = rows * c.d;
+    const size_t BH = (size_t)c.B * c.H, rows = BH * (q_rows ? q_rows : c.n), nelem = rows * c.d;
     int32_t* lists = (int32_t*)(base + W.lists);
     int32_t* counts = (int32_t*)(base + W.counts);
     float* delta = (float*)(base + W.delta);
     float* dk32 = (float*)(base + W.dk32);
     float* dv32 = (float*)(base + W.dv32);
     const bool mfma = c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull;
+    if (!mfma && (q_begin != 0 || first_valid || q_rows != 0)) return SPARSEK_ERR_UNSUPPORTED;
+    if (q_begin % 128 != 0) return SPARSEK_ERR_INVALID_ARG;
     if (!mfma)  // the generic kernel accumulates dk, dv with atomics
         hipLaunchKernelGGL(abwd_zero_kernel, dim3(2048), dim3(256), 0, st, (uint4*)(base + W.dk32), (W.sk32 - W.dk32) / 16);
     launch_block_lists(c, death, lists, counts, st);
@@ -910,20 +926,23 @@ int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
             int32_t* eslot = (int32_t*)(base + W.eslot);
             float* sk32 = (float*)(base + W.sk32);
             float* sv32 = (float*)(base + W.sv32);
-            hipLaunchKernelGGL(abwd_elist_kernel, dim3(c.B * c.Gu), dim3(1024), 0, st, death, c.n, elist, ecount, eslot);
+            hipLaunchKernelGGL(abwd_elist_kernel, dim3(c.B * c.Gu), dim3(1024), 0, st, death, c.n, q_begin, elist, ecount,
+                               eslot);
             if (c.d == 64) {
-                launch_dq_mfma<64>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st);
+                launch_dq_mfma<64>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st, q_begin, first_valid,
+                                   q_rows);
                 launch_dkv_mfma<64>(c, q, k, v, u, tau, death, elist, ecount, lse, dO, delta, dk32, dv32, sk32, sv32, eslot,
-                                    dk, dv, nb, st);
+                                    dk, dv, nb, st, q_begin, q_rows);
             } else {
-                launch_dq_mfma<128>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st);
+                launch_dq_mfma<128>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st, q_begin, first_valid,
+                                    q_rows);
                 launch_dkv_mfma<128>(c, q, k, v, u, tau, death, elist, ecount, lse, dO, delta, dk32, dv32, sk32, sv32, eslot,
-                                     dk, dv, nb, st);
+                                     dk, dv, nb, st, q_begin, q_rows);
             }
             const int d4 = c.d / 4;
             const int gx = (int)std::min<size_t>(((size_t)c.n * d4 + 255) / 256, 1024);
             hipLaunchKernelGGL(abwd_merge_kernel, dim3(gx, c.B * c.H), dim3(256), 0, st, dk32, dv32, sk32, sv32, elist,
-                               ecount, c.H, c.Gu, c.n, d4, (uint16_t*)dk, (uint16_t*)dv);
+                               ecount, c.H, c.Gu, c.n, d4, (uint16_t*)dk, (uint16_t*)dv, q_begin, q_rows);
         } else {
             hipLaunchKernelGGL(attn_bwd_generic_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)q,
                                (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, lse,

@@ -221,7 +221,7 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(
         const float inv = 1.0f / l_run;
         if (lane < d) st(oh + (size_t)i * d + lane, acc0 * inv);
         if (lane + 64 < d) st(oh + (size_t)i * d + lane + 64, acc1 * inv);
-        if (lse && lane == 0) lse[(size_t)bh * n + i] = m_run + __logf(l_run);
+        if (lse && lane == 0) lse[qo + i] = m_run + __logf(l_run);
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
     }
 }
@@ -666,7 +666,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
                 *(bf16x4*)(orow + 32 * x + 8 * g4 + 4 * half) = pk;
             }
         }
-        if (lse && half == 0) lse[(size_t)bh * n + qi] = (ref.m * c2 + log2f(l_tot)) * 0.6931471805599453f;
+        if (lse && half == 0) lse[qo + qi] = (ref.m * c2 + log2f(l_tot)) * 0.6931471805599453f;
     }
 }
 

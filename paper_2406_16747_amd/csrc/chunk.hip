@@ -64,7 +64,7 @@ static sparsek_cfg virtual_cfg(const sparsek_chunk_cfg& c, int nv)
 }
 
 struct ChunkWs {
-    size_t u, tau, death, map, first, k, v, mask, attn, total;
+    size_t u, tau, death, map, first, lse, k, v, mask, attn, total;
 };
 static ChunkWs chunk_ws(const sparsek_chunk_cfg& c, int clen)
 {
@@ -79,6 +79,7 @@ static ChunkWs chunk_ws(const sparsek_chunk_cfg& c, int clen)
     W.death = off; off += align_up(rows * nv * 4, 256);
     W.map = off; off += align_up(rows * L.rcap * 4, 256);
     W.first = off; off += align_up(rows * 4, 256);
+    W.lse = off; off += align_up(BH * (size_t)clen * 4, 256);
     const size_t tens = align_up(BH * nv * c.d * esize(c.dtype), 256);
     W.k = off; off += tens;
     W.v = off; off += tens;
@@ -325,13 +326,75 @@ int launch_chunk_prefill(const sparsek_chunk_cfg& c, void* state, int clen, cons
     if (rc) return rc;
     hipLaunchKernelGGL(chunk_clear_padding_kernel, dim3((L.rcap + 255) / 256, rows), dim3(256), 0, st, count,
                        (const int32_t*)(s + L.ret_sel), L.rcap, nv, death_v);
-    rc = launch_attn_fwd(cv, q, k_v, v_v, u_v, tau_v, death_v, o, nullptr, w + W.attn, st, L.rcap, first_valid, clen);
+    rc = launch_attn_fwd(cv, q, k_v, v_v, u_v, tau_v, death_v, o, (float*)(w + W.lse), w + W.attn, st, L.rcap,
+                         first_valid, clen);
     if (rc) return rc;
     hipLaunchKernelGGL(chunk_retain_kernel, dim3(rows), dim3(1024), 0, st, count, flags, u_v, tau_v, death_v, L.rcap,
                        clen, c.w, map, ret_u, (int32_t*)(s + L.ret_sel));
     const int gr = (int)std::min<size_t>(((size_t)L.rcap * row16 + 255) / 256, 2048);
     hipLaunchKernelGGL(chunk_retain_rows_kernel, dim3(gr, BH), dim3(256), 0, st, count, map, k_v, v_v, c.H, c.Gu,
                        L.rcap, nv, row16, ret_k, ret_v);
+    return launch_status();
+}
+
+// Backward of one chunk with the cache's gradient stopped (training with chunk-wise recurrence, Algorithm 3):
+// the gradients of L = sum(dO * O_chunk) with respect to the chunk's own q, k, v and scores, the retained keys
+// being constants.  The forward call left the virtual sequence (scores, thresholds, lifetimes, K and V rows, lse)
+// in its workspace; the ordinary backward kernels run on it with the queries offset to the chunk, and only
+// keys from the chunk on receive dk, dv, du.
+struct ChunkBwdWs {
+    size_t du, attn, mask, total;
+};
+static ChunkBwdWs chunk_bwd_ws(const sparsek_chunk_cfg& c, int clen)
+{
+    const ChunkLayout L = chunk_layout(c);
+    const int nv = L.rcap + clen;
+    sparsek_cfg v = virtual_cfg(c, nv);
+    ChunkBwdWs W;
+    size_t off = 0;
+    W.du = off; off += align_up((size_t)c.B * c.Gu * nv * 4, 256);
+    W.attn = off; off += align_up(attn_bwd_ws_bytes(v), 256);
+    v.gate_mode = c.gate_mode;
+    W.mask = off; off += align_up(mask_bwd_ws_bytes(v), 256);
+    W.total = off;
+    return W;
+}
+size_t chunk_bwd_ws_bytes(const sparsek_chunk_cfg& c) { return chunk_bwd_ws(c, c.chunk_max).total; }
+
+__global__ void chunk_slice_du_kernel(const float* __restrict__ du_v, int nv, int rcap, int clen, float* __restrict__ du)
+{
+    const int row = blockIdx.y;
+    for (int x = blockIdx.x * blockDim.x + threadIdx.x; x < clen; x += gridDim.x * blockDim.x)
+        du[(size_t)row * clen + x] = du_v[(size_t)row * nv + rcap + x];
+}
+
+int launch_chunk_bwd(const sparsek_chunk_cfg& c, int clen, const void* q, const void* o, const void* dO,
+                     const void* fwd_ws, void* dq, void* dk, void* dv, float* du, void* ws, hipStream_t st)
+{
+    const ChunkLayout L = chunk_layout(c);
+    const ChunkWs W = chunk_ws(c, clen);
+    const ChunkBwdWs Bw = chunk_bwd_ws(c, clen);
+    const int rows = c.B * c.Gu;
+    const int nv = L.rcap + clen;
+    const char* w = (const char*)fwd_ws;
+    char* b = (char*)ws;
+    const float* u_v = (const float*)(w + W.u);
+    const float* tau_v = (const float*)(w + W.tau);
+    const int32_t* death_v = (const int32_t*)(w + W.death);
+    const int32_t* first_valid = (const int32_t*)(w + W.first);
+    const float* lse = (const float*)(w + W.lse);
+    const void* k_v = w + W.k;
+    const void* v_v = w + W.v;
+    sparsek_cfg cv = virtual_cfg(c, nv);  // hard gates for gate_mode 3: what the forward computed
+    int rc = launch_attn_bwd(cv, q, k_v, v_v, u_v, tau_v, death_v, o, lse, dO, dq, dk, dv, b + Bw.attn, st, L.rcap,
+                             first_valid, clen);
+    if (rc) return rc;
+    cv.gate_mode = c.gate_mode;  // the straight-through mode has its own score gradient
+    float* du_v = (float*)(b + Bw.du);
+    rc = launch_mask_bwd(cv, q, k_v, v_v, u_v, tau_v, death_v, o, lse, dO, du_v, b + Bw.mask, st, L.rcap, clen,
+                         std::max(0, L.rcap - c.w - 1));
+    if (rc) return rc;
+    hipLaunchKernelGGL(chunk_slice_du_kernel, dim3((clen + 255) / 256, rows), dim3(256), 0, st, du_v, nv, L.rcap, clen, du);
     return launch_status();
 }
 

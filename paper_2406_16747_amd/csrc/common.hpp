@@ -22,12 +22,22 @@ int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const vo
                     void* ws, hipStream_t st, int q_begin = 0, const int32_t* first_valid = nullptr,
                     int q_rows = 0);
 // (query blocks that end at or before q_begin are skipped; keys before first_valid[row] are never attended;
-//  q_rows != 0: q and o hold q_rows rows per head, the first being query q_begin, a multiple of 128; lse unused)
+//  q_rows != 0: q, o and lse hold q_rows rows per head, the first being query q_begin, a multiple of 128)
 size_t attn_fwd_ws_bytes(const sparsek_cfg& c);
 int launch_mask_bwd(const sparsek_cfg& c, const void* q, const void* k, const void* v,
                     const float* u, const float* tau, const int32_t* death, const void* o,
-                    const float* lse, const void* dO, float* du, void* ws, hipStream_t st);
+                    const float* lse, const void* dO, float* du, void* ws, hipStream_t st, int q_begin = 0,
+                    int q_rows = 0, int t_min = 0);
+// (q_begin, q_rows as in launch_attn_fwd, for q, o, dO and lse; thresholds of prefixes before t_min are not read;
+//  bf16 with d = 64 or 128 only when any of them is set)
 size_t mask_bwd_ws_bytes(const sparsek_cfg& c);
+int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
+                    const float* tau, const int32_t* death, const void* o, const float* lse, const void* dO,
+                    void* dq, void* dk, void* dv, void* ws, hipStream_t st, int q_begin = 0,
+                    const int32_t* first_valid = nullptr, int q_rows = 0);
+// (q_rows != 0: q, o, dO, lse, dq and also dk, dv hold q_rows rows per head, the first being position q_begin: only
+//  keys from q_begin on receive a gradient; keys before first_valid[row] are attended by nobody; bf16, d = 64 / 128)
+size_t attn_bwd_ws_bytes(const sparsek_cfg& c);
 
 inline int launch_status()
 {

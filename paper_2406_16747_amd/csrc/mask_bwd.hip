@@ -337,7 +337,7 @@ __global__ __launch_bounds__(256, 2) void mask_bwd_mfma_kernel(
     const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
     const int32_t* __restrict__ lists, const int32_t* __restrict__ counts, const uint16_t* __restrict__ o,
     const float* __restrict__ lse, const uint16_t* __restrict__ dO, float* __restrict__ A, float* __restrict__ C,
-    int H, int Gu, int n, int k, int w, float scale, int nb, int BH)
+    int H, int Gu, int n, int k, int w, float scale, int nb, int BH, int q_begin, int q_rows)
 {
     static_assert(RAW <= SEG, "survivors of one segment must fit the staged metadata");
     __shared__ __align__(16) MfmaSmem<D, 16> sm;
@@ -362,6 +362,10 @@ __global__ __launch_bounds__(256, 2) void mask_bwd_mfma_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, col = lane & 31;
     const int i0 = blk * QB;
+    // Queries before q_begin do not exist (a caller that attends a chunk against retained keys);
+    // q, o, dO and lse then hold q_rows rows per head, the first of them query q_begin.
+    if (i0 + QB <= q_begin) return;
+    const ptrdiff_t qo = q_rows ? (ptrdiff_t)bh * q_rows - q_begin : (ptrdiff_t)bh * n;
     // prefixes of the block's queries that carry gradient: T = i - w with T >= k (prefixes with at
     // most k entries have every gate at 1)
     const int Tmax = min(n - 1, i0 + QB - 1) - w;
@@ -390,7 +394,7 @@ __global__ __launch_bounds__(256, 2) void mask_bwd_mfma_kernel(
     // Loads complete in issue order, so this lets the candidates be classified and compacted, and
     // the first tile's gather be issued, while the rows are still on their way from HBM.
     const float tau_q = qlive ? tr[Tp] : 0.0f;
-    const float lse2 = lse[(size_t)bh * n + qrow] * 1.4426950408889634f;
+    const float lse2 = lse[qo + qrow] * 1.4426950408889634f;
     // candidates of a segment: position, death - position, score (4 per thread)
     int cj[RAW / 256], cl[RAW / 256];
     float cu[RAW / 256];
@@ -418,7 +422,7 @@ __global__ __launch_bounds__(256, 2) void mask_bwd_mfma_kernel(
     bf16x8 qreg[DS], dreg[DS], oreg[DS];
 #pragma unroll
     for (int s = 0; s < DS; s++) {
-        const size_t off = ((size_t)bh * n + qrow) * D + 16 * s + 8 * half;
+        const size_t off = (qo + qrow) * D + 16 * s + 8 * half;
         qreg[s] = *(const bf16x8*)(q + off);
         dreg[s] = *(const bf16x8*)(dO + off);
         oreg[s] = *(const bf16x8*)(o + off);
@@ -553,14 +557,14 @@ template <int D>
 static void launch_bwd_mfma(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                             const float* tau, const int32_t* death, const int32_t* lists, const int32_t* counts,
                             const void* o, const float* lse, const void* dO, float* A, float* C, int nb,
-                            hipStream_t st)
+                            hipStream_t st, int q_begin, int q_rows)
 {
     const int BH = c.B * c.H;
     dim3 grid(nb * BH);
 #define SPK_LAUNCH_B(MODE)                                                                                    \
     hipLaunchKernelGGL((mask_bwd_mfma_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q,           \
                        (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, (const uint16_t*)o, \
-                       lse, (const uint16_t*)dO, A, C, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH)
+                       lse, (const uint16_t*)dO, A, C, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH, q_begin, q_rows)
     if (c.gate_mode == 0) SPK_LAUNCH_B(0);
     else if (c.gate_mode == 3) SPK_LAUNCH_B(3);
     else SPK_LAUNCH_B(1);
@@ -743,7 +747,7 @@ __global__ __launch_bounds__(1024) void mask_bwd_scan_final_kernel(const float* 
 
 int launch_mask_bwd(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                     const float* tau, const int32_t* death, const void* o, const float* lse, const void* dO,
-                    float* du, void* ws, hipStream_t st)
+                    float* du, void* ws, hipStream_t st, int q_begin, int q_rows, int t_min)
 {
     const BwdWs W = bwd_ws(c);
     char* base = (char*)ws;
@@ -763,14 +767,19 @@ int launch_mask_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
     }
     // A, C, diff are contiguous: clear them with one fill kernel (safe under graph capture)
     hipLaunchKernelGGL(zero_kernel, dim3(512), dim3(256), 0, st, (uint32_t*)(base + W.A), (W.G - W.A) / 4);
-    hipLaunchKernelGGL(mask_bwd_ranges_kernel, dim3((c.n + 1023) / 1024, rows), dim3(1024), 0, st, u, tau, c.n, c.k,
-                       diff, ab);
+    // t_min: thresholds of earlier prefixes are not available (and no query uses them)
+    hipLaunchKernelGGL(mask_bwd_ranges_kernel, dim3((c.n + 1023) / 1024, rows), dim3(1024), 0, st, u, tau, c.n,
+                       std::max(c.k, t_min), diff, ab);
     launch_block_lists(c, death, lists, counts, st);
     dim3 grid(nb, c.B * c.H);
     if (c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull) {
-        if (c.d == 64) launch_bwd_mfma<64>(c, q, k, v, u, tau, death, lists, counts, o, lse, dO, A, C, nb, st);
-        else launch_bwd_mfma<128>(c, q, k, v, u, tau, death, lists, counts, o, lse, dO, A, C, nb, st);
-    } else if (c.dtype == SPARSEK_F32)
+        if (c.d == 64)
+            launch_bwd_mfma<64>(c, q, k, v, u, tau, death, lists, counts, o, lse, dO, A, C, nb, st, q_begin, q_rows);
+        else
+            launch_bwd_mfma<128>(c, q, k, v, u, tau, death, lists, counts, o, lse, dO, A, C, nb, st, q_begin, q_rows);
+    } else if (q_begin != 0 || q_rows != 0 || t_min != 0)
+        return SPARSEK_ERR_UNSUPPORTED;  // the offset-query form exists on the MFMA path only
+    else if (c.dtype == SPARSEK_F32)
         hipLaunchKernelGGL(mask_bwd_generic_kernel<float>, grid, dim3(256), 0, st, (const float*)q, (const float*)k,
                            (const float*)v, u, tau, death, lists, counts, (const float*)o, lse, (const float*)dO, A, C,
                            c.H, c.Gu, c.n, c.d, c.k, c.w, c.gate_mode, c.softmax_scale, nb);

@@ -84,3 +84,15 @@ def test_argument_validation_needs_no_gpu():
     assert L.sparsek_attn_bwd(ctypes.byref(cfg), *([one] * 9), one, one, one, one, 8, null) == -3
     bad = spk.SparsekCfg(B=1, H=2, Gu=1, n=16, d=64, k=4, w=4, dtype=spk.BF16, gate_mode=4, softmax_scale=1.0)
     assert L.sparsek_attn_bwd(ctypes.byref(bad), *([one] * 9), one, one, one, one, 1 << 30, null) == -1
+    # backward of a chunk (bf16, d = 64 / 128 only)
+    cc = SparsekChunkCfg(B=1, H=2, Gu=1, d=64, k=8, w=8, cand_cap=0, chunk_max=256, dtype=spk.BF16, gate_mode=0,
+                         softmax_scale=1.0)
+    wb, bb = L.sparsek_chunk_workspace_bytes(ctypes.byref(cc)), L.sparsek_chunk_bwd_workspace_bytes(ctypes.byref(cc))
+    assert bb > 0
+    assert L.sparsek_chunk_bwd(ctypes.byref(cc), 16, one, one, one, one, wb, one, one, one, null, one, bb, null) == -1
+    assert L.sparsek_chunk_bwd(ctypes.byref(cc), 0, one, one, one, one, wb, one, one, one, one, one, bb, null) == -1
+    assert L.sparsek_chunk_bwd(ctypes.byref(cc), 16, one, one, one, one, wb, one, one, one, one, one, 8, null) == -3
+    f32 = SparsekChunkCfg(B=1, H=2, Gu=1, d=64, k=8, w=8, cand_cap=0, chunk_max=256, dtype=spk.F32, gate_mode=0,
+                          softmax_scale=1.0)
+    assert L.sparsek_chunk_bwd_workspace_bytes(ctypes.byref(f32)) == 0
+    assert L.sparsek_chunk_bwd(ctypes.byref(f32), 16, one, one, one, one, 1 << 30, one, one, one, one, one, 1 << 30, null) == -2
