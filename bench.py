@@ -267,7 +267,23 @@ def chunk_leg(n=131072, c=8192):
     counts, flags = spk.sparsek_chunk_status(st)
     flops = 4.0 * d * attended_pairs(n, k, w) * B * H
     ach = flops / (ms * 1e-3) / 1e12
+    # training with chunk-wise recurrence: every chunk's forward followed by its backward (cache gradient stopped)
+    dOs = [torch.randn(B, H, c, d, device="cuda", generator=g).bfloat16() for _ in range(2)]
+    st2 = spk.ChunkState(B, H, 1, d, k, w, spk.BF16, c, 0, 1.0)
+    for i, ch in enumerate(chunks[:2]):
+        spk.sparsek_chunk_bwd(st2, ch[0], spk.sparsek_chunk_prefill(st2, *ch), dOs[i % 2])
+    st2 = spk.ChunkState(B, H, 1, d, k, w, spk.BF16, c, 0, 1.0)
+    torch.cuda.synchronize()
+    e0.record()
+    for i, ch in enumerate(chunks):
+        spk.sparsek_chunk_bwd(st2, ch[0], spk.sparsek_chunk_prefill(st2, *ch), dOs[i % 2])
+    e1.record()
+    torch.cuda.synchronize()
+    train_ms = e0.elapsed_time(e1)
     return {"workload": "B=1 H=32 n=%d d=128 k=w=1024 bf16, Gu=1, gate_mode=0, chunks of %d" % (n, c),
+            "training": {"ms_total": train_ms, "ms_per_chunk": train_ms / len(chunks),
+                         "tokens_per_s": n / (train_ms * 1e-3), "what": "sparsek_chunk_prefill + sparsek_chunk_bwd per chunk",
+                         "bwd_workspace_bytes": int(st2.bwd_ws.numel())},
             "ms_total": ms, "ms_per_chunk": ms / len(chunks), "tokens_per_s": n / (ms * 1e-3),
             "retained_entries": int(counts.max()), "overflow": bool(flags.any()),
             "state_bytes": int(st.buf.numel()), "workspace_bytes": int(st.ws.numel()),

@@ -194,3 +194,55 @@ def test_chunked_prefill_at_bench_shape(oracle):
             ref = np.abs(o_r).max()
             assert err <= 1e-2 and err <= ref * 2.0 ** -7 + 1e-6, (h, a, err, ref)
 
+
+
+def test_chunk_training_at_bench_shape(oracle):
+    """Forward + backward of the second of two 8192-token chunks at the bench's head shape (H=32 d=128
+    k=w=1024): dq, dk, dv of two heads and du against the oracle's full-sequence backward with the
+    upstream gradient masked to that chunk (du sums over all heads, so it is checked on a run with the
+    two heads alone)."""
+    require_gpu()
+    say("chunk training at the bench shape: H=32 (then 2) n=16384 d=128 k=w=1024, chunks of 8192")
+    B, H, n, d, k, w, c = 1, 32, 16384, 128, 1024, 1024, 8192
+    g = torch.Generator(device="cuda")
+    g.manual_seed(2304)
+    div = math.sqrt(d)
+    q, kk, v = ((torch.randn(B, H, n, d, device="cuda", generator=g) / div).bfloat16() for _ in range(3))
+    dO = torch.randn(B, H, n, d, device="cuda", generator=g).bfloat16()
+    u = torch.randn(B, 1, n, device="cuda", generator=g)
+    heads = [5, 28]
+
+    def run(hsel):
+        qs, ks, vs, ds = (x[:, hsel].contiguous() for x in (q, kk, v, dO))
+        st = spk.ChunkState(B, len(hsel), 1, d, k, w, spk.BF16, c, 0, 1.0)
+        res = None
+        for p in range(0, n, c):
+            qc = qs[:, :, p:p + c].contiguous()
+            o = spk.sparsek_chunk_prefill(st, qc, ks[:, :, p:p + c].contiguous(), vs[:, :, p:p + c].contiguous(),
+                                          u[:, :, p:p + c].contiguous())
+            res = spk.sparsek_chunk_bwd(st, qc, o, ds[:, :, p:p + c].contiguous())
+        torch.cuda.synchronize()
+        return [host(x) for x in res]
+
+    full = run(list(range(H)))   # the launch shape bench.py times
+    two = run(heads)             # du of the two heads alone
+    sl = slice(c, n)
+    q32, k32, v32 = (host(x[:, heads]) for x in (q, kk, v))
+    dO_m = host(dO[:, heads])
+    dO_m[:, :, :c] = 0.0
+    u_np = host(u)
+    tau64, death = oracle.mask_all(u_np, k)
+    say("  oracle backward of 2 heads over 16384 positions")
+    rq, rk, rv = oracle.attn_bwd(q32, k32, v32, u_np, tau64, death, dO_m, k, w, 0, 1.0)
+    ru, _ = oracle.mask_bwd(q32, k32, v32, u_np, tau64, death, dO_m, k, w, 0, 1.0)
+    for name, gi, r in (("dq", 0, rq), ("dk", 1, rk), ("dv", 2, rv)):
+        r = r[:, :, sl]
+        scale = np.abs(r).max()
+        for got in (full[gi][:, heads], two[gi]):
+            err = np.abs(got - r).max()
+            assert np.isfinite(got).all() and scale > 0 and err <= 1e-2 * scale, (name, err, scale)
+    r = ru[:, :, sl]
+    scale = np.abs(r).max()
+    err = np.abs(two[3] - r).max()
+    assert scale > 0 and err <= 1e-2 * scale, ("du", err, scale)
+    assert np.isfinite(full[3]).all()
