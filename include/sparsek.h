@@ -119,6 +119,14 @@ int sparsek_attn_bwd(const sparsek_cfg *cfg, const void *q, const void *k, const
                      const float *tau, const int32_t *death, const void *o, const float *lse, const void *dO,
                      void *dq, void *dk, void *dv, void *ws, size_t ws_bytes, void *stream);
 
+/* The whole backward of the operator in one call: dq, dk, dv as sparsek_attn_bwd and du as sparsek_mask_bwd
+ * (same arguments, same results; the two parts are enqueued back to back on the stream).
+ * ws: scratch of at least sparsek_bwd_workspace_bytes(cfg) bytes. */
+size_t sparsek_bwd_workspace_bytes(const sparsek_cfg *cfg);
+int sparsek_bwd(const sparsek_cfg *cfg, const void *q, const void *k, const void *v, const float *u,
+                const float *tau, const int32_t *death, const void *o, const float *lse, const void *dO,
+                void *dq, void *dk, void *dv, float *du, void *ws, size_t ws_bytes, void *stream);
+
 /* ---- importance scores (Sec. 3.2 scoring network with position slope; Sec. 3.5 score normalisation) ----
  * u out [B,n] fp32, one row per sequence (the single score group of the paper; feed it to sparsek_mask with Gu = 1):
  *     raw_t = x_t . w + t * slope        (t counted from 0),

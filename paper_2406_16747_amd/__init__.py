@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     sparsek_attn_fwd,
     sparsek_mask_bwd,
     sparsek_attn_bwd,
+    sparsek_bwd,
     sparsek_scores,
     ChunkState,
     sparsek_chunk_prefill,

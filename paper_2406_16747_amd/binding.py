@@ -59,6 +59,10 @@ def lib():
         L.sparsek_mask_bwd.argtypes = [cfgp] + [vp] * 10 + [vp, sz, vp]
         L.sparsek_attn_bwd.argtypes = [cfgp] + [vp] * 12 + [vp, sz, vp]
         L.sparsek_attn_bwd.restype = C.c_int
+        L.sparsek_bwd.argtypes = [cfgp] + [vp] * 13 + [vp, sz, vp]
+        L.sparsek_bwd.restype = C.c_int
+        L.sparsek_bwd_workspace_bytes.restype = sz
+        L.sparsek_bwd_workspace_bytes.argtypes = [cfgp]
         scfgp = C.POINTER(SparsekScoresCfg)
         L.sparsek_scores_workspace_bytes.restype = sz
         L.sparsek_scores_workspace_bytes.argtypes = [scfgp]
@@ -203,6 +207,19 @@ def sparsek_attn_bwd(q, k, v, u, tau, death, o, lse, dO, k_sel, w, gate_mode=0, 
     check(lib().sparsek_attn_bwd(C.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(u), _ptr(tau), _ptr(death), _ptr(o),
                                  _ptr(lse), _ptr(dO), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(), _stream()))
     return dq, dk, dv
+
+
+def sparsek_bwd(q, k, v, u, tau, death, o, lse, dO, k_sel, w, gate_mode=0, scale=1.0, ws=None):
+    """The whole backward in one call: (dq, dk, dv, du)."""
+    torch = _torch()
+    cfg = _attn_cfg(q, u, k_sel, w, gate_mode, scale)
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    du = torch.empty_like(u)
+    if ws is None:
+        ws = _ws(lib().sparsek_bwd_workspace_bytes(C.byref(cfg)), q.device)
+    check(lib().sparsek_bwd(C.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(u), _ptr(tau), _ptr(death), _ptr(o), _ptr(lse),
+                            _ptr(dO), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(du), _ptr(ws), ws.numel(), _stream()))
+    return dq, dk, dv, du
 
 
 def sparsek_scores(x, w, slope=0.0, norm=False, norm_eps=1e-5, ws=None):

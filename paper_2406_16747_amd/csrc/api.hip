@@ -206,6 +206,29 @@ int sparsek_mask_bwd(const sparsek_cfg* cfg, const void* q, const void* k, const
     return launch_mask_bwd(*cfg, q, k, v, u, tau, death, o, lse, dO, du, ws, (hipStream_t)stream);
 }
 
+size_t sparsek_bwd_workspace_bytes(const sparsek_cfg* cfg)
+{
+    if (check_attn(cfg)) return 0;
+    return align_up(spk::attn_bwd_ws_bytes(*cfg), 256) + mask_bwd_ws_bytes(*cfg);
+}
+
+int sparsek_bwd(const sparsek_cfg* cfg, const void* q, const void* k, const void* v, const float* u, const float* tau,
+                const int32_t* death, const void* o, const float* lse, const void* dO, void* dq, void* dk, void* dv,
+                float* du, void* ws, size_t ws_bytes, void* stream)
+{
+    int rc = check_attn(cfg);
+    if (rc) return rc;
+    if (!q || !k || !v || !u || !tau || !death || !o || !lse || !dO || !dq || !dk || !dv || !du || !ws)
+        return SPARSEK_ERR_INVALID_ARG;
+    if (ws_bytes < sparsek_bwd_workspace_bytes(cfg)) return SPARSEK_ERR_WORKSPACE;
+    sparsek_cfg c = *cfg;
+    if (c.gate_mode == 3) c.gate_mode = 2;  // the straight-through forward has no gates on q, k, v
+    rc = spk::launch_attn_bwd(c, q, k, v, u, tau, death, o, lse, dO, dq, dk, dv, ws, (hipStream_t)stream);
+    if (rc) return rc;
+    return launch_mask_bwd(*cfg, q, k, v, u, tau, death, o, lse, dO, du,
+                           (char*)ws + align_up(spk::attn_bwd_ws_bytes(*cfg), 256), (hipStream_t)stream);
+}
+
 size_t sparsek_decode_state_bytes(const sparsek_decode_cfg* cfg)
 {
     if (check_decode(cfg)) return 0;

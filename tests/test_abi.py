@@ -96,3 +96,7 @@ def test_argument_validation_needs_no_gpu():
                           softmax_scale=1.0)
     assert L.sparsek_chunk_bwd_workspace_bytes(ctypes.byref(f32)) == 0
     assert L.sparsek_chunk_bwd(ctypes.byref(f32), 16, one, one, one, one, 1 << 30, one, one, one, one, one, 1 << 30, null) == -2
+    # the one-call backward
+    assert L.sparsek_bwd_workspace_bytes(ctypes.byref(cfg)) > L.sparsek_attn_bwd_workspace_bytes(ctypes.byref(cfg))
+    assert L.sparsek_bwd(ctypes.byref(cfg), *([one] * 9), one, one, one, null, one, 1 << 30, null) == -1  # du null
+    assert L.sparsek_bwd(ctypes.byref(cfg), *([one] * 9), one, one, one, one, one, 8, null) == -3

@@ -76,3 +76,24 @@ def test_attn_bwd_medium(oracle, n, d, k, w, Gu, gate_mode):
     inp = synth.make(3, Gu=Gu, seed=3 * n + k, with_dO=True, B=1, H=2, n=n, d=d, k=k, w=w, dtype="bf16",
                      qk_div=float(np.sqrt(d)) / 2)
     run_bwd(oracle, inp, gate_mode)
+
+
+@pytest.mark.parametrize("gate_mode", [0, 1, 3])
+def test_one_call_backward_equals_the_two_parts(gate_mode):
+    """sparsek_bwd = sparsek_attn_bwd + sparsek_mask_bwd, bit for bit (dq, dk, dv; du accumulates with atomics
+    across heads, so it is compared to rounding)."""
+    require_gpu()
+    say("one-call backward", gate_mode)
+    inp = synth.make(3, seed=77, with_dO=True, B=2, H=2, n=700, d=64, k=40, w=30, dtype="bf16", qk_div=2.0)
+    u = dev(inp["u"])
+    Q, K, V, dO = (dev(inp[x], True) for x in ("Q", "K", "V", "dO"))
+    tau, death = spk.sparsek_mask(u, 40)
+    o, lse = spk.sparsek_attn_fwd(Q, K, V, u, tau, death, 40, 30, gate_mode, 1.0)
+    dq, dk, dv = spk.sparsek_attn_bwd(Q, K, V, u, tau, death, o, lse, dO, 40, 30, gate_mode, 1.0)
+    du = spk.sparsek_mask_bwd(Q, K, V, u, tau, death, o, lse, dO, 40, 30, gate_mode, 1.0)
+    dq2, dk2, dv2, du2 = spk.sparsek_bwd(Q, K, V, u, tau, death, o, lse, dO, 40, 30, gate_mode, 1.0)
+    torch.cuda.synchronize()
+    for a, b in ((dq, dq2), (dk, dk2), (dv, dv2)):
+        assert torch.equal(a, b)
+    scale = float(du.abs().max())
+    assert scale > 0 and float((du - du2).abs().max()) <= 1e-5 * scale
