@@ -446,12 +446,14 @@ static void launch_dq_mfma(const sparsek_cfg& c, const void* q, const void* k, c
 // Because a key is attended on one contiguous range of queries, two kinds of key blocks cover all
 // pairs with one interval test per pair:
 //   window blocks    128 consecutive positions, queries j <= i <= j + w - 1, gate 1;
-//   selected blocks  128 ever-selected keys (death_j > j, compacted in position order), queries
+//   selected blocks  128 ever-selected keys (death_j > j, listed by death, see abwd_elist_kernel), queries
 //                    j + w <= i <= death_j + w - 1, gate clip(u_j - tau_{i-w}).
-// Every key belongs to exactly one window block and at most one selected block, so both kinds
-// store their fp32 result without atomics: window blocks into dk32 / dv32 [B,H,n,d] (every element,
-// zeros included), selected blocks into sk32 / sv32 at the key's slot of the compacted list; the
-// final pass adds the two and rounds to the storage type.
+// Every key belongs to exactly one window block and at most one selected block, so nothing needs an
+// atomic: a window block stores the final dk, dv rows of the keys that are never selected, and its
+// fp32 part of the others into dk32 / dv32 by position; a selected block stores into sk32 / sv32 at
+// the key's slot of the list; abwd_merge_kernel adds the two parts and rounds.
+// With q_rows != 0 the queries are offset (a chunk attending retained keys): q, dO, lse, delta, dk, dv
+// hold q_rows rows per head from position q_begin, and only keys from q_begin on are processed.
 // ---------------------------------------------------------------------------------
 __device__ __forceinline__ int wave_max_i32(int x)
 {
