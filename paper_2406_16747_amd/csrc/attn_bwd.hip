@@ -897,7 +897,9 @@ int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
     float* delta = (float*)(base + W.delta);
     float* dk32 = (float*)(base + W.dk32);
     float* dv32 = (float*)(base + W.dv32);
-    const bool mfma = c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull;
+    // (the dK/dV kernel puts 2 * nb key blocks on the grid's y axis)
+    const bool mfma = c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull &&
+                      2 * nb <= 65535;
     if (!mfma && (q_begin != 0 || first_valid || q_rows != 0)) return SPARSEK_ERR_UNSUPPORTED;
     if (q_begin % 128 != 0) return SPARSEK_ERR_INVALID_ARG;
     if (!mfma)  // the generic kernel accumulates dk, dv with atomics
