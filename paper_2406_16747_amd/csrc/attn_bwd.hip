@@ -16,7 +16,7 @@ void launch_block_lists(const sparsek_cfg& c, const int32_t* death, int32_t* lis
 size_t block_lists_bytes(const sparsek_cfg& c, size_t* counts_offset);
 
 struct AbwdWs {
-    size_t lists, counts, delta, elist, ecount, eslot, dk32, dv32, sk32, sv32, total;
+    size_t lists, counts, delta, lse2, elist, ecount, eslot, dk32, dv32, sk32, sv32, total;
 };
 static AbwdWs abwd_ws(const sparsek_cfg& c)
 {
@@ -28,6 +28,7 @@ static AbwdWs abwd_ws(const sparsek_cfg& c)
     W.counts = coff;
     size_t off = align_up(lb, 256);
     W.delta = off; off += align_up(BH * c.n * 4, 256);
+    W.lse2 = off; off += align_up(BH * c.n * 4, 256);
     W.elist = off; off += align_up((size_t)c.B * c.Gu * c.n * 4, 256);
     W.ecount = off; off += align_up((size_t)c.B * c.Gu * 4, 256);
     W.eslot = off; off += align_up((size_t)c.B * c.Gu * c.n * 4, 256);
@@ -73,10 +74,12 @@ __global__ __launch_bounds__(256) void abwd_delta_kernel(const T* __restrict__ o
     if (lane == 0) delta[r] = s;
 }
 
-// The same for bf16 rows of d = 8 * LPR elements: LPR lanes per row, 16 bytes per lane.
+// The same for bf16 rows of d = 8 * LPR elements: LPR lanes per row, 16 bytes per lane.  Also writes
+// lse2 = lse * log2(e), the form the exponent of the dK/dV kernel subtracts.
 template <int LPR>
 __global__ __launch_bounds__(256) void abwd_delta_bf16_kernel(const uint16_t* __restrict__ o, const uint16_t* __restrict__ dO,
-                                                              size_t rows, float* __restrict__ delta)
+                                                              size_t rows, float* __restrict__ delta,
+                                                              const float* __restrict__ lse, float* __restrict__ lse2)
 {
     constexpr int RPB = 256 / LPR;  // rows per workgroup
     const size_t r = (size_t)blockIdx.x * RPB + threadIdx.x / LPR;
@@ -92,7 +95,10 @@ __global__ __launch_bounds__(256) void abwd_delta_bf16_kernel(const uint16_t* __
     }
 #pragma unroll
     for (int m = LPR / 2; m > 0; m >>= 1) s += __shfl_xor(s, m, 64);
-    if (threadIdx.x % LPR == 0) delta[r] = s;
+    if (threadIdx.x % LPR == 0) {
+        delta[r] = s;
+        lse2[r] = lse[r] * 1.4426950408889634f;
+    }
 }
 
 // fp32 accumulators -> storage type
@@ -551,7 +557,6 @@ struct DkvSmem {
     unsigned char qt[2][S::NL * S::GSV];   // ... for transposing reads
     unsigned char gr[2][S::NL * S::GSK];   // dO rows, row reads
     unsigned char gt[2][S::NL * S::GSV];   // dO rows, transposing reads
-    float lse2[2][KT], del[2][KT], tq[2][KT];  // per query of the tile: lse * log2(e), D_i, tau_{i-w}
     int red[2][4];
 };
 
@@ -559,7 +564,7 @@ template <int D, int MODE>
 __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ kk, const uint16_t* __restrict__ v,
     const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
-    const int32_t* __restrict__ elist, const int32_t* __restrict__ ecount, const float* __restrict__ lse,
+    const int32_t* __restrict__ elist, const int32_t* __restrict__ ecount, const float* __restrict__ lse2s,
     const uint16_t* __restrict__ dO, const float* __restrict__ delta, float* __restrict__ dk32,
     float* __restrict__ dv32, float* __restrict__ sk32, float* __restrict__ sv32, const int32_t* __restrict__ eslot,
     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int H, int Gu, int n, int w, float scale, int nb,
@@ -567,6 +572,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
 {
     using S = MfmaSmem<D, 64>;
     __shared__ __align__(16) DkvSmem<D> sm;
+    // per query of a tile: lse * log2(e), D_i, tau_{i-w} (and a fourth row that only keeps the loads branch-free)
+    __shared__ __align__(16) float meta[2][4][KT];
     constexpr int DS = D / 16, DB = D / 32, NX = S::NL / 4, LPR = S::RB / 16;
     const int bh = blockIdx.x;
     const int b = bh / H, h = bh % H;
@@ -648,24 +655,24 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
             const int L = wv * NX + x;
             const int rr = min(i_first + L + S::NL * (lane / LPR), n - 1);  // tile row L + NL * jrow
             const uint32_t off = (uint32_t)rr * (uint32_t)S::RB + 16u * (uint32_t)c;
-            __builtin_amdgcn_global_load_lds((glb_void_t*)(qh + off), (lds_void_t*)&sm.qr[buf][L * S::GSK], 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((glb_void_t*)(qh + off), (lds_void_t*)&sm.qt[buf][L * S::GSV], 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((glb_void_t*)(gh + off), (lds_void_t*)&sm.gr[buf][L * S::GSK], 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((glb_void_t*)(gh + off), (lds_void_t*)&sm.gt[buf][L * S::GSV], 16, 0, 0);
+            async_load_lds16(qh, off, &sm.qr[buf][L * S::GSK]);
+            async_load_lds16(qh, off, &sm.qt[buf][L * S::GSV]);
+            async_load_lds16(gh, off, &sm.gr[buf][L * S::GSK]);
+            async_load_lds16(gh, off, &sm.gt[buf][L * S::GSV]);
         }
     };
-    auto load_meta = [&](int i_first, float& a, float& bq, float& cq) {
-        if (tid < KT) {
-            const int i = min(i_first + tid, n - 1);
-            a = lse[qo + i] * 1.4426950408889634f;
-            bq = delta[qo + i];
-            cq = tr[max(i - w, 0)];
-        }
+    // the tile's per-query values: waves 0, 1, 2 load one row each (wave 3 a copy of tau into the spare row)
+    const float* msrc = wv == 0 ? lse2s + qo : wv == 1 ? delta + qo : tr;
+    auto issue_meta = [&](int buf, int i_first) {
+        const int i = min(i_first + lane, n - 1);
+        async_load_lds4(msrc, 4u * (uint32_t)(wv >= 2 ? max(i - w, 0) : i), &meta[buf][wv][0]);
     };
+    // The K / V fragments must have arrived before the first untracked load is issued: the compiler's own
+    // wait for them would otherwise sit at their first use, inside the loop, and count the prefetches too.
+#pragma unroll
+    for (int s = 0; s < DS; s++) asm volatile("" ::"v"(kreg[s]), "v"(vreg[s]));
     if (ntiles > 0) {
-        float a = 0, bq = 0, cq = 0;
-        load_meta(blo, a, bq, cq);
-        if (tid < KT) { sm.lse2[0][tid] = a; sm.del[0][tid] = bq; sm.tq[0][tid] = cq; }
+        issue_meta(0, blo);
         issue(0, blo);
     }
     // One tile for this wave, as four runs of NS MFMAs:
@@ -678,6 +685,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     // outside the key's interval.  The softmax scale of dS is applied once, to the finished dK.
     constexpr int NS = 2 * DS, EPM = 16 / NS, DEPTH = 4;
     static_assert(NS == 4 * DB && EPM * NS == 16, "stage lengths");
+    const unsigned char* mbase = (const unsigned char*)&meta[0][0][0];
     auto tile = [&](auto gated_c, auto check_c, int buf, int i_first) {
         constexpr bool GATED = decltype(gated_c)::value, CHECK = decltype(check_c)::value;
         constexpr bool GK = GATED && MODE == 0, GV = GATED && MODE != 2;
@@ -710,9 +718,10 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
             constexpr int qb = decltype(qbc)::value, r = decltype(rc)::value, g4 = r / 4, e = r % 4;
             if constexpr (e == 0) {
                 const int qo = 32 * qb + 8 * g4 + 4 * half;  // first of 4 consecutive queries of the tile
-                L4 = *(const float4*)&sm.lse2[buf][qo];
-                D4 = *(const float4*)&sm.del[buf][qo];
-                if constexpr (GATED) T4 = *(const float4*)&sm.tq[buf][qo];
+                const unsigned char* mp = mbase + (buf * 4 * KT + qo) * 4;
+                L4 = *(const float4*)(mp);
+                D4 = *(const float4*)(mp + KT * 4);
+                if constexpr (GATED) T4 = *(const float4*)(mp + 2 * KT * 4);
             }
             const float l2 = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
             const float Di = e == 0 ? D4.x : e == 1 ? D4.y : e == 2 ? D4.z : D4.w;
@@ -784,18 +793,15 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
         for (int x = 0; x < DB; x++) asm volatile("" : "+a"(acc_k[x]), "+a"(acc_v[x]));
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();  // tile t landed (rows and per-query values); everybody is done with tile t-1
-        float ma = 0, mb_ = 0, mc = 0;
-        const bool more = t + 1 < ntiles;
-        if (more) {
+        if (t + 1 < ntiles) {
+            issue_meta(buf ^ 1, i_first + KT);
             issue(buf ^ 1, i_first + KT);
-            load_meta(i_first + KT, ma, mb_, mc);
         }
         if (i_first <= whi && i_first + KT - 1 >= wlo) {  // some key of this wave is attended from this tile
             const bool full = i_first >= wfull_lo && i_first + KT - 1 <= wfull_hi;
             if (full) tile(gated_c, std::false_type{}, buf, i_first);
             else tile(gated_c, std::true_type{}, buf, i_first);
         }
-        if (more && tid < KT) { sm.lse2[buf ^ 1][tid] = ma; sm.del[buf ^ 1][tid] = mb_; sm.tq[buf ^ 1][tid] = mc; }
     }
     };
     if (selected_kind && MODE != 2) tiles(std::true_type{});
@@ -895,6 +901,7 @@ int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
     int32_t* lists = (int32_t*)(base + W.lists);
     int32_t* counts = (int32_t*)(base + W.counts);
     float* delta = (float*)(base + W.delta);
+    float* lse2 = (float*)(base + W.lse2);
     float* dk32 = (float*)(base + W.dk32);
     float* dv32 = (float*)(base + W.dv32);
     // (the dK/dV kernel puts 2 * nb key blocks on the grid's y axis)
@@ -917,10 +924,10 @@ int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
     } else {
         if (c.d == 128)
             hipLaunchKernelGGL(abwd_delta_bf16_kernel<16>, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, st,
-                               (const uint16_t*)o, (const uint16_t*)dO, rows, delta);
+                               (const uint16_t*)o, (const uint16_t*)dO, rows, delta, lse, lse2);
         else if (c.d == 64)
             hipLaunchKernelGGL(abwd_delta_bf16_kernel<8>, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st,
-                               (const uint16_t*)o, (const uint16_t*)dO, rows, delta);
+                               (const uint16_t*)o, (const uint16_t*)dO, rows, delta, lse, lse2);
         else
             hipLaunchKernelGGL(abwd_delta_kernel<uint16_t>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st,
                                (const uint16_t*)o, (const uint16_t*)dO, rows, c.d, delta);
@@ -935,12 +942,12 @@ int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
             if (c.d == 64) {
                 launch_dq_mfma<64>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st, q_begin, first_valid,
                                    q_rows);
-                launch_dkv_mfma<64>(c, q, k, v, u, tau, death, elist, ecount, lse, dO, delta, dk32, dv32, sk32, sv32, eslot,
+                launch_dkv_mfma<64>(c, q, k, v, u, tau, death, elist, ecount, lse2, dO, delta, dk32, dv32, sk32, sv32, eslot,
                                     dk, dv, nb, st, q_begin, q_rows);
             } else {
                 launch_dq_mfma<128>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st, q_begin, first_valid,
                                     q_rows);
-                launch_dkv_mfma<128>(c, q, k, v, u, tau, death, elist, ecount, lse, dO, delta, dk32, dv32, sk32, sv32, eslot,
+                launch_dkv_mfma<128>(c, q, k, v, u, tau, death, elist, ecount, lse2, dO, delta, dk32, dv32, sk32, sv32, eslot,
                                      dk, dv, nb, st, q_begin, q_rows);
             }
             const int d4 = c.d / 4;

@@ -15,6 +15,30 @@ typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void lds_void_t;
 typedef __attribute__((address_space(1))) const void glb_void_t;
 
+// The 4-byte form of async_load_lds16 below: lane l's word at gbase + voff lands at lds_dst + 4 * l.
+__device__ __forceinline__ void async_load_lds4(const void* gbase, uint32_t voff, const void* lds_dst)
+{
+    const uint32_t m0v = (uint32_t)(uintptr_t)(lds_void_t*)lds_dst;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :
+                 : "s"(m0v), "v"(voff), "s"(gbase)
+                 : "memory", "m0");
+}
+
+// A 16-byte-per-lane direct-to-LDS load that the compiler does not track: lane l's 16 bytes at gbase + voff land
+// at lds_dst + 16 * l (gbase and lds_dst uniform over the wave).  The compiler makes the first LDS read that
+// follows a tracked direct-to-LDS load wait for all such loads (it cannot tell that the read goes to another
+// buffer), which would put the whole memory latency of a prefetch in front of the next operand read.  The
+// caller waits itself: s_waitcnt vmcnt(0) before the barrier that publishes the tile.
+__device__ __forceinline__ void async_load_lds16(const void* gbase, uint32_t voff, const void* lds_dst)
+{
+    const uint32_t m0v = (uint32_t)(uintptr_t)(lds_void_t*)lds_dst;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(m0v), "v"(voff), "s"(gbase)
+                 : "memory", "m0");
+}
+
 constexpr int KT = 64;     // keys per tile
 constexpr int SEG = 1088;  // keys whose metadata is staged in LDS at a time (17 tiles)
 
