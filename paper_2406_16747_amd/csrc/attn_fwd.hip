@@ -636,6 +636,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
         const int ntiles = seg_n / KT;
         const int T0 = seg0 / KT;                 // global number of the segment's first tile
         const int jbase0 = c0 + (seg0 - nkl);     // position of local tile 0 if it were contiguous
+        // The tile gathers are direct-to-LDS loads that the compiler does not track.  Everything it does track
+        // (the Q fragments, the metadata above) is waited for here, ahead of the first of them: left to their
+        // first use inside the tile loop, those waits would count the prefetched tile too and drain it early.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int s = 0; s < DS; s++) asm volatile("" ::"v"(qreg[s]));
         issue_tile_loads<D, 64>(sm, 0, sm.jpos, kh, vh, wv, lane);
         int t = 0;
 #define SPK_RUN(KIND, bound)                                                                                   \

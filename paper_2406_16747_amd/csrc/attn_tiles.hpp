@@ -96,8 +96,8 @@ __device__ __forceinline__ void tile_load_step(MfmaSmem<D, VPAD>& sm, int buf, c
     const int c = lane % LPR;
     const int L = wv * (S::NL / 4) + x;
     const uint32_t off = (uint32_t)rows.j[x] * (uint32_t)S::RB + 16u * (uint32_t)c;
-    __builtin_amdgcn_global_load_lds((glb_void_t*)((const unsigned char*)kh + off), (lds_void_t*)&sm.kb[buf][L * S::GSK], 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((glb_void_t*)((const unsigned char*)vh + off), (lds_void_t*)&sm.vb[buf][L * S::GSV], 16, 0, 0);
+    async_load_lds16(kh, off, &sm.kb[buf][L * S::GSK]);
+    async_load_lds16(vh, off, &sm.vb[buf][L * S::GSV]);
 }
 
 template <int D, int VPAD>
