@@ -97,3 +97,23 @@ def test_one_call_backward_equals_the_two_parts(gate_mode):
         assert torch.equal(a, b)
     scale = float(du.abs().max())
     assert scale > 0 and float((du - du2).abs().max()) <= 1e-5 * scale
+
+
+def test_one_call_backward_fp32_generic_path(oracle):
+    """sparsek_bwd on the generic (fp32) kernels against the oracle's two gradients."""
+    require_gpu()
+    say("one-call backward fp32")
+    inp = synth.make(3, seed=91, with_dO=True, B=1, H=2, n=300, d=32, k=24, w=20, dtype="fp32", qk_div=2.0)
+    u = dev(inp["u"])
+    Q, K, V, dO = (dev(inp[x], False) for x in ("Q", "K", "V", "dO"))
+    tau, death = spk.sparsek_mask(u, 24)
+    o, lse = spk.sparsek_attn_fwd(Q, K, V, u, tau, death, 24, 20, 0, inp["scale"])
+    got = [host(x) for x in spk.sparsek_bwd(Q, K, V, u, tau, death, o, lse, dO, 24, 20, 0, inp["scale"])]
+    tau64 = host(tau).astype(np.float64)
+    ref = list(oracle.attn_bwd(inp["Q32"], inp["K32"], inp["V32"], inp["u"], tau64, host(death), inp["dO32"], 24, 20, 0,
+                               inp["scale"]))
+    ref.append(oracle.mask_bwd(inp["Q32"], inp["K32"], inp["V32"], inp["u"], tau64, host(death), inp["dO32"], 24, 20, 0,
+                               inp["scale"])[0])
+    for name, g, r in zip(("dq", "dk", "dv", "du"), got, ref):
+        scale = np.abs(r).max()
+        assert scale > 0 and np.abs(g - r).max() <= 2e-4 * scale, (name, np.abs(g - r).max(), scale)

@@ -63,6 +63,8 @@ def run_case(oracle, inp, chunks, gate_mode):
     (800, 64, 40, 0, 1, [200, 200, 400], 0),
     (700, 64, 24, 30, 1, [350, 350], 3),
     (600, 128, 16, 20, 1, [128, 472], 2),
+    (900, 128, 40, 50, 2, [77, 500, 323], 0),
+    (520, 64, 600, 8, 1, [260, 260], 0),
 ])
 def test_chunk_bwd_equals_masked_full_backward(oracle, n, d, k, w, Gu, chunks, gate_mode):
     require_gpu()
