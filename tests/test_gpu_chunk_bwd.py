@@ -48,7 +48,9 @@ def run_case(oracle, inp, chunks, gate_mode):
             scale = np.abs(r).max() if name == "du" else max(np.abs(r).max(), 1e-3 * common)
             err = np.abs(g - r).max()
             if name == "du" and scale == 0.0:
-                assert err == 0.0, (name, ci, err)
+                # no soft gate in reach of this chunk's queries: the exact gradient is zero; the kernel forms it as
+                # a difference of fp64 prefix sums, which may leave rounding noise of the order 1e-16 of their size
+                assert err <= 1e-12 * common, (name, ci, err)
                 continue
             assert err <= 1e-2 * scale + 1e-30, (name, ci, err, scale, np.unravel_index(np.abs(g - r).argmax(), g.shape))
         pos += c
