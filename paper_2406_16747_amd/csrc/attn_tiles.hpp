@@ -30,6 +30,9 @@ __device__ __forceinline__ void async_load_lds4(const void* gbase, uint32_t voff
 // follows a tracked direct-to-LDS load wait for all such loads (it cannot tell that the read goes to another
 // buffer), which would put the whole memory latency of a prefetch in front of the next operand read.  The
 // caller waits itself: s_waitcnt vmcnt(0) before the barrier that publishes the tile.
+// The LDS base goes through M0, which the compiler reserves for itself and does not treat as clobbered by an asm
+// statement: a kernel that uses these loads must give the compiler no reason to keep a value of its own in M0 across
+// them (the builtin form of the same load, indirect register indexing).  The kernels here use one form or the other.
 __device__ __forceinline__ void async_load_lds16(const void* gbase, uint32_t voff, const void* lds_dst)
 {
     const uint32_t m0v = (uint32_t)(uintptr_t)(lds_void_t*)lds_dst;
