@@ -458,7 +458,7 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
     static_for<0, 2 * NS>([&](auto nc) {
         constexpr int n = decltype(nc)::value;
         const bf16x8 cur = ring[n % DEPTH];
-        if (n < NS) sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qreg[n], sA, 0, 0, 0);
+        if constexpr (n < NS) sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qreg[n], sA, 0, 0, 0);
         else sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, qreg[n - NS], sB, 0, 0, 0);
         if (n + DEPTH < NSLOT) ring[n % DEPTH] = operand(n + DEPTH);
         // the gather of the next tile rides on the S_A slots, whose issue is otherwise idle
