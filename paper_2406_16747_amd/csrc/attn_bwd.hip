@@ -474,6 +474,8 @@ __device__ __forceinline__ int wave_min_i32(int x)
     return x;
 }
 
+__device__ __forceinline__ int b_row(int bh, int H, int Gu) { return (bh / H) * Gu + (Gu == 1 ? 0 : bh % H); }
+
 // elist: the ever-selected keys of a score row (death_j > j), ordered by death_j / bw and then by position,
 // so that the 32 keys of a wave and the 128 of a block stop being attended at about the same query and the
 // span of query tiles they walk is short.  eslot[j]: where key j sits in that list, -1 if it is not in it.
@@ -584,7 +586,11 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     // keeps whole heads (the same mix of block lengths everywhere, and a head's rows in one L2).  Blocks of
     // selected keys come first, latest deaths (longest spans) first; the short window blocks fill the tail.
     const bool selected_kind = (int)blockIdx.y < nb;
-    const int kblk = selected_kind ? nb - 1 - blockIdx.y : blockIdx.y - nb;
+    int kblk = blockIdx.y - nb;
+    if (selected_kind) {  // y = 0 is the list's last block; the workgroups beyond the list come after it and leave at once
+        const int ne_blocks = (ecount[b_row(blockIdx.x, H, Gu)] + 127) / 128;
+        kblk = (int)blockIdx.y < ne_blocks ? ne_blocks - 1 - (int)blockIdx.y : nb;
+    }
     const float* ur = u + (size_t)row * n;
     const float* tr = tau + (size_t)row * n;
     const int32_t* dr = death + (size_t)row * n;
