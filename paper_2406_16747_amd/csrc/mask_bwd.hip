@@ -194,6 +194,11 @@ __device__ __forceinline__ float bwd_pair(float qk, float dov, int Jj, int Lj, f
 // index c >> 1, which the even one adds to the tile's sums in LDS.
 __device__ __forceinline__ void bwd_column_sums(float (&gv)[16], float* colsum, int mb, int lane, int half)
 {
+    // The lane's target address is recomputed here on purpose (the empty asm hides that it is loop-invariant):
+    // hoisted, it was one of the values the register allocator parked in scratch memory, and a reload inside
+    // the tile loop waits for every outstanding memory operation, the prefetched tile included.
+    asm volatile("" : "+v"(lane));
+    half = lane >> 5;
     const int c31 = lane & 31;
 #pragma unroll
     for (int r = 0; r < 8; r++) {
