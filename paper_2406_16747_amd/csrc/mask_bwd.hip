@@ -261,6 +261,9 @@ __device__ __forceinline__ void bwd_step(MfmaSmem<D, 16>& sm, float* colsum_prev
     constexpr int EPM = 16 / NM;   // pairs of elementwise work per slot
     constexpr int DEPTH = 2;
     static_assert(EPM * NM == 16 && (4 % EPM) == 0, "head dim 64 or 128");
+    // Per-lane LDS addresses (metadata groups, operand rows) are formed again in every step: as loop-invariant
+    // values they were spilled, and a reload inside the tile loop waits for the prefetched tile as well.
+    asm volatile("" : "+v"(half), "+v"(col));
     const unsigned char* kbuf = sm.kb[buf];
     const unsigned char* vbuf = sm.vb[buf];
     const float c2 = scale * 1.4426950408889634f;
