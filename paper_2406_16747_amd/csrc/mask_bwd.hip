@@ -260,6 +260,7 @@ __device__ __forceinline__ void bwd_step(MfmaSmem<D, 16>& sm, float* colsum_prev
     constexpr int NM = 2 * DS;     // MFMA slots per key half: K and V fragments alternate
     constexpr int EPM = 16 / NM;   // pairs of elementwise work per slot
     constexpr int DEPTH = 2;
+    static_assert(NM % DEPTH == 0, "the ring runs on from phase A into phase B");
     static_assert(EPM * NM == 16 && (4 % EPM) == 0, "head dim 64 or 128");
     // Per-lane LDS addresses (metadata groups, operand rows) are formed again in every step: as loop-invariant
     // values they were spilled, and a reload inside the tile loop waits for the prefetched tile as well.
