@@ -37,7 +37,7 @@ extern "C" {
 
 #define SPARSEK_OK 0
 #define SPARSEK_ERR_INVALID_ARG (-1)    /* null pointer, n<1, k<0, w<0, k+w<1, Gu not in {1,H}, bad range */
-#define SPARSEK_ERR_UNSUPPORTED (-2)    /* head dim / dtype / size outside what the kernels handle */
+#define SPARSEK_ERR_UNSUPPORTED (-2)    /* head dim / dtype / size outside what the kernels handle (n, k, w > 2^28; decode k, w > 2^24) */
 #define SPARSEK_ERR_WORKSPACE (-3)      /* workspace or state buffer smaller than the *_bytes query says */
 #define SPARSEK_ERR_LAUNCH (-5)         /* the HIP runtime refused a launch */
 
@@ -73,6 +73,11 @@ const char *sparsek_strerror(int code);
 size_t sparsek_mask_workspace_bytes(const sparsek_cfg *cfg);
 int sparsek_mask(const sparsek_cfg *cfg, const float *u, float *tau, int32_t *death, void *ws,
                  size_t ws_bytes, void *stream);
+/* Copies the status word that the last sparsek_mask call on `ws` (same cfg) left there to *host_flag (host memory)
+ * and synchronises the stream.  0: every threshold is the exact root.  bit 0: a threshold solve stopped at its
+ * iteration cap (the bracket-and-bisect safeguard ran out; not observed on finite scores -- that threshold is then
+ * the last iterate and may miss the 1e-5 bar).  The word is cleared at the start of every sparsek_mask call. */
+int sparsek_mask_status(const sparsek_cfg *cfg, const void *ws, size_t ws_bytes, int32_t *host_flag, void *stream);
 
 /* ---- stage 2, explicit form (verification aid; O((t_end-t_begin)*k) memory) ----
  * For every prefix t in [t_begin, t_end): idx [B,Gu,t_end-t_begin,k] int32 = positions of the

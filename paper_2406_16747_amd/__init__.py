@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     lib_path,
     check,
     sparsek_mask,
+    sparsek_mask_workspace,
+    sparsek_mask_status,
     sparsek_materialize,
     sparsek_attn_fwd,
     sparsek_mask_bwd,

@@ -54,6 +54,8 @@ def lib():
             getattr(L, name).restype = sz
             getattr(L, name).argtypes = [cfgp]
         L.sparsek_mask.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
+        L.sparsek_mask_status.argtypes = [cfgp, vp, sz, vp, vp]
+        L.sparsek_mask_status.restype = C.c_int
         L.sparsek_materialize.argtypes = [cfgp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.sparsek_attn_fwd.argtypes = [cfgp] + [vp] * 8 + [vp, sz, vp]
         L.sparsek_mask_bwd.argtypes = [cfgp] + [vp] * 10 + [vp, sz, vp]
@@ -131,18 +133,34 @@ def _ws(nbytes, device):
     return _torch().empty(max(int(nbytes), 256), dtype=_torch().uint8, device=device)
 
 
-def sparsek_mask(u, k):
+def _mask_cfg(u, k):
+    B, Gu, n = u.shape
+    return SparsekCfg(B=B, H=Gu, Gu=Gu, n=n, d=64, k=int(k), w=1, dtype=F32, gate_mode=0, softmax_scale=1.0)
+
+
+def sparsek_mask(u, k, ws=None):
     """u [B,Gu,n] fp32 -> (tau [B,Gu,n] fp32, death [B,Gu,n] int32)."""
     torch = _torch()
     _need(u, torch.float32, "u")
-    B, Gu, n = u.shape
-    cfg = SparsekCfg(B=B, H=Gu, Gu=Gu, n=n, d=64, k=int(k), w=1, dtype=F32, gate_mode=0, softmax_scale=1.0)
+    cfg = _mask_cfg(u, k)
     tau = torch.empty_like(u)
     death = torch.empty(u.shape, dtype=torch.int32, device=u.device)
-    nbytes = lib().sparsek_mask_workspace_bytes(C.byref(cfg))
-    ws = _ws(nbytes, u.device)
+    if ws is None:
+        ws = _ws(lib().sparsek_mask_workspace_bytes(C.byref(cfg)), u.device)
     check(lib().sparsek_mask(C.byref(cfg), _ptr(u), _ptr(tau), _ptr(death), _ptr(ws), ws.numel(), _stream()))
     return tau, death
+
+
+def sparsek_mask_workspace(u, k):
+    """A workspace for sparsek_mask(u, k, ws=...), to be read back with sparsek_mask_status."""
+    return _ws(lib().sparsek_mask_workspace_bytes(C.byref(_mask_cfg(u, k))), u.device)
+
+
+def sparsek_mask_status(u, k, ws):
+    """Status word of the last sparsek_mask(u, k, ws=ws) call (0 = every threshold solve converged).  Synchronises."""
+    flag = C.c_int32(-1)
+    check(lib().sparsek_mask_status(C.byref(_mask_cfg(u, k)), _ptr(ws), ws.numel(), C.byref(flag), _stream()))
+    return int(flag.value)
 
 
 def sparsek_materialize(u, tau, death, k, t_begin, t_end, with_gate=True):

@@ -8,11 +8,14 @@ namespace {
 int check_common(const sparsek_cfg* c)
 {
     if (!c) return SPARSEK_ERR_INVALID_ARG;
-    if (c->B < 1 || c->H < 1 || c->n < 1 || c->k < 0 || c->w < 0 || c->k + c->w < 1)
+    if (c->B < 1 || c->H < 1 || c->n < 1 || c->k < 0 || c->w < 0 || (long long)c->k + c->w < 1)
         return SPARSEK_ERR_INVALID_ARG;
     if (c->Gu != 1 && c->Gu != c->H) return SPARSEK_ERR_INVALID_ARG;
     if ((long long)c->B * c->H > 65535) return SPARSEK_ERR_UNSUPPORTED;
     if ((long long)c->n > (1 << 28)) return SPARSEK_ERR_UNSUPPORTED;
+    // k and w beyond n mean the same as n; larger values are refused rather than clamped so that sums such as
+    // k + w and w - 1 + death[j] stay far from the int32 range everywhere
+    if (c->k > (1 << 28) || c->w > (1 << 28)) return SPARSEK_ERR_UNSUPPORTED;
     return SPARSEK_OK;
 }
 
@@ -57,6 +60,15 @@ int sparsek_mask(const sparsek_cfg* cfg, const float* u, float* tau, int32_t* de
     if (!u || !tau || !death || !ws) return SPARSEK_ERR_INVALID_ARG;
     if (ws_bytes < mask_ws_bytes(*cfg)) return SPARSEK_ERR_WORKSPACE;
     return launch_mask(*cfg, u, tau, death, ws, (hipStream_t)stream);
+}
+
+int sparsek_mask_status(const sparsek_cfg* cfg, const void* ws, size_t ws_bytes, int32_t* host_flag, void* stream)
+{
+    int rc = check_common(cfg);
+    if (rc) return rc;
+    if (!ws || !host_flag) return SPARSEK_ERR_INVALID_ARG;
+    if (ws_bytes < mask_ws_bytes(*cfg)) return SPARSEK_ERR_WORKSPACE;
+    return mask_status(*cfg, ws, host_flag, (hipStream_t)stream);
 }
 
 int sparsek_materialize(const sparsek_cfg* cfg, const float* u, const float* tau, const int32_t* death,
@@ -174,11 +186,13 @@ namespace {
 int check_decode(const sparsek_decode_cfg* c)
 {
     if (!c) return SPARSEK_ERR_INVALID_ARG;
-    if (c->B < 1 || c->H < 1 || c->k < 0 || c->w < 0 || c->k + c->w < 1 || c->cand_cap < 0)
+    if (c->B < 1 || c->H < 1 || c->k < 0 || c->w < 0 || (long long)c->k + c->w < 1 || c->cand_cap < 0)
         return SPARSEK_ERR_INVALID_ARG;
     if (c->Gu != 1 && c->Gu != c->H) return SPARSEK_ERR_INVALID_ARG;
     if (c->gate_mode < 0 || c->gate_mode > 3) return SPARSEK_ERR_INVALID_ARG;
     if (c->dtype != SPARSEK_F32 && c->dtype != SPARSEK_BF16) return SPARSEK_ERR_UNSUPPORTED;
+    // the state holds k + w slots per head and cand_cap (default 4k) scores per row: sizes are computed in int
+    if (c->k > (1 << 24) || c->w > (1 << 24) || c->cand_cap > (1 << 26)) return SPARSEK_ERR_UNSUPPORTED;
     if (c->d < 8 || c->d > 128 || (c->d % 8) != 0) return SPARSEK_ERR_UNSUPPORTED;
     if ((long long)c->B * c->H > (1 << 24)) return SPARSEK_ERR_UNSUPPORTED;
     if (!(c->softmax_scale > 0.0f) || !(c->softmax_scale < INFINITY)) return SPARSEK_ERR_INVALID_ARG;
@@ -298,7 +312,7 @@ namespace {
 int check_chunk(const sparsek_chunk_cfg* c)
 {
     if (!c) return SPARSEK_ERR_INVALID_ARG;
-    if (c->B < 1 || c->H < 1 || c->k < 0 || c->w < 0 || c->k + c->w < 1 || c->cand_cap < 0 || c->chunk_max < 1)
+    if (c->B < 1 || c->H < 1 || c->k < 0 || c->w < 0 || (long long)c->k + c->w < 1 || c->cand_cap < 0 || c->chunk_max < 1)
         return SPARSEK_ERR_INVALID_ARG;
     if (c->Gu != 1 && c->Gu != c->H) return SPARSEK_ERR_INVALID_ARG;
     if (c->gate_mode < 0 || c->gate_mode > 3) return SPARSEK_ERR_INVALID_ARG;

@@ -15,6 +15,8 @@ namespace spk {
 int launch_mask(const sparsek_cfg& c, const float* u, float* tau, int32_t* death, void* ws,
                 hipStream_t st, int t_begin = 0);
 size_t mask_ws_bytes(const sparsek_cfg& c);
+// copies the status word that the last launch_mask on `ws` left (bit 0: a threshold solve hit its iteration cap) and waits
+int mask_status(const sparsek_cfg& c, const void* ws, int32_t* host_flag, hipStream_t st);
 int launch_materialize(const sparsek_cfg& c, const float* u, const float* tau, const int32_t* death,
                        int t_begin, int t_end, int32_t* idx, float* gate, hipStream_t st);
 int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const void* v,

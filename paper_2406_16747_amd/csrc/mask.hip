@@ -83,7 +83,7 @@ __global__ __launch_bounds__(NT_COARSE) void mask_coarse_kernel(const float* __r
                                                                  float* __restrict__ lo_out,
                                                                  float* __restrict__ tau,
                                                                  int32_t* __restrict__ death, int n,
-                                                                 int k, int nsuper)
+                                                                 int k, int nsuper, int* __restrict__ status)
 {
     __shared__ double red[NT_COARSE / 64][NPROBE + 1];
     __shared__ double ftot[NPROBE];
@@ -93,6 +93,8 @@ __global__ __launch_bounds__(NT_COARSE) void mask_coarse_kernel(const float* __r
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const float* ur = u + (size_t)row * n;
     int32_t* dr = death + (size_t)row * n;
+    // the call's status word starts at 0; the chunk kernel, which sets bits in it, runs after this one on the stream
+    if (s == 0 && row == 0 && tid == 0) *status = 0;
     if (k > 0)
         for (int i = s * SUPER + tid; i < min(n, (s + 1) * SUPER); i += NT_COARSE) dr[i] = n;
     const int L = s * SUPER;
@@ -1067,7 +1069,7 @@ int launch_mask(const sparsek_cfg& c, const float* u, float* tau, int32_t* death
     float* lo = (float*)ws;
     int* status = (int*)((char*)ws + align_up((size_t)rows * nsuper * sizeof(float), 256));
     hipLaunchKernelGGL(mask_coarse_kernel, dim3(c.k == 0 ? 1 : nsuper, rows), dim3(NT_COARSE), 0, st, u, lo, tau,
-                       death, c.n, c.k, nsuper);
+                       death, c.n, c.k, nsuper, status);
     if (c.k == 0) return launch_status();
     if (c.k < c.n) {
         const int nchunks = (c.n + CHUNK - 1) / CHUNK;
@@ -1075,6 +1077,15 @@ int launch_mask(const sparsek_cfg& c, const float* u, float* tau, int32_t* death
                            c.n, c.k, nsuper, status, t_begin);
     }
     return launch_status();
+}
+
+int mask_status(const sparsek_cfg& c, const void* ws, int32_t* host_flag, hipStream_t st)
+{
+    const size_t rows = (size_t)c.B * c.Gu, nsuper = ((size_t)c.n + SUPER - 1) / SUPER;
+    const int* status = (const int*)((const char*)ws + align_up(rows * nsuper * sizeof(float), 256));
+    if (hipMemcpyAsync(host_flag, status, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return SPARSEK_ERR_LAUNCH;
+    return hipStreamSynchronize(st) == hipSuccess ? SPARSEK_OK : SPARSEK_ERR_LAUNCH;
 }
 
 int launch_materialize(const sparsek_cfg& c, const float* u, const float* tau, const int32_t* death,

@@ -30,8 +30,17 @@ def test_argument_validation_needs_no_gpu():
     L = spk.lib()
     cfg = spk.SparsekCfg(B=1, H=2, Gu=1, n=16, d=64, k=4, w=4, dtype=spk.BF16, gate_mode=0, softmax_scale=1.0)
     null = ctypes.c_void_p(0)
+    one_ = ctypes.c_void_p(256)  # never dereferenced: validation fails first
     assert L.sparsek_mask(ctypes.byref(cfg), null, null, null, null, 0, null) == -1
     assert L.sparsek_mask_workspace_bytes(ctypes.byref(cfg)) > 0
+    flag = ctypes.c_int32(7)
+    assert L.sparsek_mask_status(ctypes.byref(cfg), null, 1 << 20, ctypes.byref(flag), null) == -1
+    assert L.sparsek_mask_status(ctypes.byref(cfg), one_, 8, ctypes.byref(flag), null) == -3
+    # k or w far beyond any sequence length are refused, not wrapped around
+    for kw in ((2 ** 31 - 1, 4), (4, 2 ** 31 - 1), (2 ** 31 - 1, 2 ** 31 - 1)):
+        big = spk.SparsekCfg(B=1, H=2, Gu=1, n=16, d=64, k=kw[0], w=kw[1], dtype=spk.BF16, gate_mode=0, softmax_scale=1.0)
+        assert L.sparsek_mask_workspace_bytes(ctypes.byref(big)) == 0
+        assert L.sparsek_attn_fwd(ctypes.byref(big), *([one_] * 8), one_, 1 << 20, null) == -2
     bad = spk.SparsekCfg(B=1, H=2, Gu=3, n=16, d=64, k=4, w=4, dtype=spk.BF16, gate_mode=0, softmax_scale=1.0)
     assert L.sparsek_mask_workspace_bytes(ctypes.byref(bad)) == 0
     one = ctypes.c_void_p(256)  # never dereferenced: validation fails first

@@ -36,8 +36,10 @@ def scores(kind, rng, rows, n):
 def check_rows(oracle, u, k, sample_t=None):
     rows, n = u.shape
     ud = dev(u.reshape(rows, 1, n))
-    tau_g, death_g = spk.sparsek_mask(ud, k)
-    torch.cuda.synchronize()
+    ws = spk.sparsek_mask_workspace(ud, k)
+    ws.fill_(0xFF)  # the call itself must clear its status word
+    tau_g, death_g = spk.sparsek_mask(ud, k, ws=ws)
+    assert spk.sparsek_mask_status(ud, k, ws) == 0  # every threshold solve converged
     tau_g, death_g = host(tau_g).reshape(rows, n), host(death_g).reshape(rows, n)
     for r in range(rows):
         tau_r, us, ws = oracle.tau_prefixes(u[r], k)
