@@ -40,6 +40,7 @@ extern "C" {
 #define SPARSEK_ERR_UNSUPPORTED (-2)    /* head dim / dtype / size outside what the kernels handle (n, k, w > 2^28; decode k, w > 2^24) */
 #define SPARSEK_ERR_WORKSPACE (-3)      /* workspace or state buffer smaller than the *_bytes query says */
 #define SPARSEK_ERR_LAUNCH (-5)         /* the HIP runtime refused a launch */
+#define SPARSEK_ERR_TOO_LARGE (-6)      /* sparsek_mask_static: the problem needs more scratch than the built-in array holds */
 
 #define SPARSEK_F32 0
 #define SPARSEK_BF16 1
@@ -78,6 +79,19 @@ int sparsek_mask(const sparsek_cfg *cfg, const float *u, float *tau, int32_t *de
  * iteration cap (the bracket-and-bisect safeguard ran out; not observed on finite scores -- that threshold is then
  * the last iterate and may miss the 1e-5 bar).  The word is cleared at the start of every sparsek_mask call. */
 int sparsek_mask_status(const sparsek_cfg *cfg, const void *ws, size_t ws_bytes, int32_t *host_flag, void *stream);
+
+/* ---- stages 1+2 without a workspace, for callers that cannot allocate ----
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc: same inputs, outputs,
+ * kernels and results as sparsek_mask, but the scratch (one fp32 lower bound per 2048 positions of every score row,
+ * and the status word) lives in a 64 KiB device array built into the library, which each GPU holds until the process
+ * ends.  The call allocates and frees nothing.  The current device must be the one that owns u, tau and death.
+ * Limit: sparsek_mask_workspace_bytes(cfg) = B*Gu*ceil(n/2048)*4 (rounded up to 256) + 256 must not exceed
+ * SPARSEK_MASK_STATIC_MAX_BYTES, e.g. 32 rows of 1 M scores;
+ * beyond it nothing is enqueued and SPARSEK_ERR_TOO_LARGE is returned.  All calls on one GPU share the array: calls
+ * that may overlap (different streams, or threads) race and must be ordered by the caller.  The status word of this
+ * variant is not readable. */
+#define SPARSEK_MASK_STATIC_MAX_BYTES 65536
+int sparsek_mask_static(const sparsek_cfg *cfg, const float *u, float *tau, int32_t *death, void *stream);
 
 /* ---- stage 2, explicit form (verification aid; O((t_end-t_begin)*k) memory) ----
  * For every prefix t in [t_begin, t_end): idx [B,Gu,t_end-t_begin,k] int32 = positions of the

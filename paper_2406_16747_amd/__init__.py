@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     sparsek_mask,
     sparsek_mask_workspace,
     sparsek_mask_status,
+    sparsek_mask_static,
     sparsek_materialize,
     sparsek_attn_fwd,
     sparsek_mask_bwd,

@@ -56,6 +56,8 @@ def lib():
         L.sparsek_mask.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
         L.sparsek_mask_status.argtypes = [cfgp, vp, sz, vp, vp]
         L.sparsek_mask_status.restype = C.c_int
+        L.sparsek_mask_static.argtypes = [cfgp, vp, vp, vp, vp]
+        L.sparsek_mask_static.restype = C.c_int
         L.sparsek_materialize.argtypes = [cfgp, vp, vp, vp, i32, i32, vp, vp, vp]
         L.sparsek_attn_fwd.argtypes = [cfgp] + [vp] * 8 + [vp, sz, vp]
         L.sparsek_mask_bwd.argtypes = [cfgp] + [vp] * 10 + [vp, sz, vp]
@@ -148,6 +150,21 @@ def sparsek_mask(u, k, ws=None):
     if ws is None:
         ws = _ws(lib().sparsek_mask_workspace_bytes(C.byref(cfg)), u.device)
     check(lib().sparsek_mask(C.byref(cfg), _ptr(u), _ptr(tau), _ptr(death), _ptr(ws), ws.numel(), _stream()))
+    return tau, death
+
+
+def sparsek_mask_static(u, k, tau=None, death=None):
+    """sparsek_mask without a workspace (the library's built-in scratch array); tau, death may be preallocated."""
+    torch = _torch()
+    _need(u, torch.float32, "u")
+    cfg = _mask_cfg(u, k)
+    if tau is None:
+        tau = torch.empty_like(u)
+    if death is None:
+        death = torch.empty(u.shape, dtype=torch.int32, device=u.device)
+    _need(tau, torch.float32, "tau")
+    _need(death, torch.int32, "death")
+    check(lib().sparsek_mask_static(C.byref(cfg), _ptr(u), _ptr(tau), _ptr(death), _stream()))
     return tau, death
 
 

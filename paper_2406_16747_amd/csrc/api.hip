@@ -42,6 +42,7 @@ const char* sparsek_strerror(int code)
         case SPARSEK_ERR_UNSUPPORTED: return "unsupported shape or dtype";
         case SPARSEK_ERR_WORKSPACE: return "workspace or state buffer too small";
         case SPARSEK_ERR_LAUNCH: return "HIP launch failed";
+        case SPARSEK_ERR_TOO_LARGE: return "problem larger than the built-in scratch array of sparsek_mask_static";
         default: return "unknown error";
     }
 }
