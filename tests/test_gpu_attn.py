@@ -75,7 +75,7 @@ def test_config1_fp32(oracle, gate_mode):
     (1000, 128, 70, 150, 1, "bf16"), (900, 64, 100, 192, 1, "bf16"), (2600, 128, 1500, 256, 1, "bf16"),
     (1500, 64, 300, 64, 1, "bf16"),
 ])
-@pytest.mark.parametrize("gate_mode", [0, 1])
+@pytest.mark.parametrize("gate_mode", [0, 1, 2, 3])
 def test_small_shapes(oracle, n, d, k, w, Gu, dtype, gate_mode):
     require_gpu()
     say("attn small", n, d, k, w, Gu, dtype, gate_mode)

@@ -1,8 +1,8 @@
 """GPU parity of sparsek_attn_bwd (gradients with respect to q, k, v) against the CPU oracle.
 
 Bars: |g - ref| <= 1e-2 max|ref| per tensor for bf16 storage (outputs are rounded to bf16, the
-stored bf16 O enters D = dO.O with relative error 2^-9), <= 2e-4 max|ref| for fp32.  The gates are
-functions of (u, tau): the oracle is fed the GPU's fp32 thresholds, checked to 1e-5 elsewhere.
+stored bf16 O enters D = dO.O with relative error 2^-9), <= 2e-4 max|ref| for fp32.  The reference
+is computed from the oracle's own thresholds (rounded to fp32, the precision the kernels keep them in) and lifetimes.
 """
 import numpy as np
 import pytest
@@ -10,7 +10,7 @@ import torch
 
 import paper_2406_16747_amd as spk
 from paper_2406_16747_amd import synth
-from gpu_util import dev, host, require_gpu, say
+from gpu_util import check_mask_against, dev, host, kink_keys, oracle_mask32, require_gpu, say
 
 pytestmark = pytest.mark.gpu
 
@@ -25,7 +25,9 @@ def run_bwd(oracle, inp, gate_mode, heads=None):
     dq, dk, dv = spk.sparsek_attn_bwd(Q, K, V, u, tau, death, o, lse, dO, k, w, gate_mode, inp["scale"])
     torch.cuda.synchronize()
     got = [host(x) for x in (dq, dk, dv)]
-    ref = oracle.attn_bwd(inp["Q32"], inp["K32"], inp["V32"], inp["u"], host(tau).astype(np.float64), host(death),
+    tau_r, death_r = oracle_mask32(oracle, inp["u"], k)
+    check_mask_against(host(tau), host(death), tau_r, death_r)
+    ref = oracle.attn_bwd(inp["Q32"], inp["K32"], inp["V32"], inp["u"], tau_r, death_r,
                           inp["dO32"], k, w, gate_mode, inp["scale"])
     worst = 0.0
     common = max(np.abs(r).max() for r in ref)
@@ -79,9 +81,9 @@ def test_attn_bwd_medium(oracle, n, d, k, w, Gu, gate_mode):
 
 
 @pytest.mark.parametrize("gate_mode", [0, 1, 3])
-def test_one_call_backward_equals_the_two_parts(gate_mode):
+def test_one_call_backward_equals_the_two_parts(oracle, gate_mode):
     """sparsek_bwd = sparsek_attn_bwd + sparsek_mask_bwd, bit for bit (dq, dk, dv; du accumulates with atomics
-    across heads, so it is compared to rounding)."""
+    across heads, so it is compared to rounding), and all four gradients of the one call against the oracle."""
     require_gpu()
     say("one-call backward", gate_mode)
     inp = synth.make(3, seed=77, with_dO=True, B=2, H=2, n=700, d=64, k=40, w=30, dtype="bf16", qk_div=2.0)
@@ -97,6 +99,18 @@ def test_one_call_backward_equals_the_two_parts(gate_mode):
         assert torch.equal(a, b)
     scale = float(du.abs().max())
     assert scale > 0 and float((du - du2).abs().max()) <= 1e-5 * scale
+    tau_r, death_r = oracle_mask32(oracle, inp["u"], 40)
+    check_mask_against(host(tau), host(death), tau_r, death_r)
+    kink = kink_keys(inp["u"], tau_r, host(tau))
+    assert kink.sum() <= 4
+    args = (inp["Q32"], inp["K32"], inp["V32"], inp["u"], tau_r, death_r, inp["dO32"], 40, 30, gate_mode, 1.0)
+    ref = list(oracle.attn_bwd(*args)) + [oracle.mask_bwd(*args)[0]]
+    for name, g, r in zip(("dq", "dk", "dv", "du"), (dq2, dk2, dv2, du2), ref):
+        rs = np.abs(r).max()
+        diff = np.abs(host(g) - r)
+        if name == "du":
+            diff = diff[~kink]
+        assert rs > 0 and diff.max() <= 1e-2 * rs, (name, diff.max(), rs)
 
 
 def test_one_call_backward_fp32_generic_path(oracle):
@@ -109,10 +123,12 @@ def test_one_call_backward_fp32_generic_path(oracle):
     tau, death = spk.sparsek_mask(u, 24)
     o, lse = spk.sparsek_attn_fwd(Q, K, V, u, tau, death, 24, 20, 0, inp["scale"])
     got = [host(x) for x in spk.sparsek_bwd(Q, K, V, u, tau, death, o, lse, dO, 24, 20, 0, inp["scale"])]
-    tau64 = host(tau).astype(np.float64)
-    ref = list(oracle.attn_bwd(inp["Q32"], inp["K32"], inp["V32"], inp["u"], tau64, host(death), inp["dO32"], 24, 20, 0,
+    tau_r, death_r = oracle_mask32(oracle, inp["u"], 24)
+    check_mask_against(host(tau), host(death), tau_r, death_r)
+    assert not kink_keys(inp["u"], tau_r, host(tau)).any()
+    ref = list(oracle.attn_bwd(inp["Q32"], inp["K32"], inp["V32"], inp["u"], tau_r, death_r, inp["dO32"], 24, 20, 0,
                                inp["scale"]))
-    ref.append(oracle.mask_bwd(inp["Q32"], inp["K32"], inp["V32"], inp["u"], tau64, host(death), inp["dO32"], 24, 20, 0,
+    ref.append(oracle.mask_bwd(inp["Q32"], inp["K32"], inp["V32"], inp["u"], tau_r, death_r, inp["dO32"], 24, 20, 0,
                                inp["scale"])[0])
     for name, g, r in zip(("dq", "dk", "dv", "du"), got, ref):
         scale = np.abs(r).max()

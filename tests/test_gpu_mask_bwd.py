@@ -1,8 +1,10 @@
 """GPU parity of sparsek_mask_bwd (gradient w.r.t. the scores) against the CPU oracle.
 
-The membership of a key in the strictly fractional set S* is decided from tau; so that both
-sides decide it on the same numbers the oracle is fed the GPU's fp32 thresholds (already
-checked against the oracle's own to 1e-5 elsewhere).  Bars: |du - ref| <= 1e-2 max|ref| for
+The reference is computed from the oracle's own thresholds and lifetimes (nothing of the GPU's
+enters it); the thresholds are rounded to fp32, the precision the kernels keep them in, because
+the membership of a key in the strictly fractional set S* is decided from them.  Keys whose
+membership could differ where the two sides' fp32 thresholds differ are listed (almost always
+none), must be few, and are held to a looser bar.  Bars: |du - ref| <= 1e-2 max|ref| for
 bf16 tensors (the stored bf16 output O enters dO.O with relative error 2^-9), 2e-4 max|ref|
 for fp32.  The sum of du over a row must vanish (rows of the SPARSEK Jacobian sum to 0).
 """
@@ -12,7 +14,7 @@ import torch
 
 import paper_2406_16747_amd as spk
 from paper_2406_16747_amd import synth
-from gpu_util import dev, host, require_gpu, say
+from gpu_util import check_mask_against, dev, host, kink_keys, oracle_mask32, require_gpu, say
 
 pytestmark = pytest.mark.gpu
 
@@ -28,13 +30,18 @@ def run_bwd(oracle, inp, gate_mode, heads_all=True):
     torch.cuda.synchronize()
     du = host(du)
     assert np.isfinite(du).all()
-    tau64 = host(tau).astype(np.float64)
-    ref, _ = oracle.mask_bwd(inp["Q32"], inp["K32"], inp["V32"], inp["u"], tau64, host(death), inp["dO32"], k, w,
+    tau_r, death_r = oracle_mask32(oracle, inp["u"], k)
+    check_mask_against(host(tau), host(death), tau_r, death_r)
+    ref, _ = oracle.mask_bwd(inp["Q32"], inp["K32"], inp["V32"], inp["u"], tau_r, death_r, inp["dO32"], k, w,
                              gate_mode, 1.0)
+    kink = kink_keys(inp["u"], tau_r, host(tau))
+    assert kink.sum() <= 4, kink.sum()
     scale = np.abs(ref).max()
-    err = np.abs(du - ref).max()
+    diff = np.abs(du - ref)
+    err = diff[~kink].max()
     tol = (1e-2 if bf16 else 2e-4) * scale
     assert err <= tol + 1e-30, (err, scale)
+    assert diff.max() <= 0.2 * scale + 1e-30
     if scale > 0:
         assert np.abs(du.sum(-1)).max() <= 1e-3 * scale * np.sqrt(n)
     return err / max(scale, 1e-30), scale
