@@ -30,7 +30,17 @@ size_t block_lists_bytes(const sparsek_cfg& c, size_t* counts_offset)
     return lists + counts;
 }
 
-size_t attn_fwd_ws_bytes(const sparsek_cfg& c) { return block_lists_bytes(c, nullptr); }
+// The MFMA forward kernel reads a second form of the lists: per (row, block) three parallel arrays of KP entries --
+// position, lifetime death[j] and score u[j] of every listed key -- so that it stages a segment of metadata with
+// plain copies (no gather by position).  Entries from the list length up to the next multiple of the tile size are
+// padding (position 0, lifetime INT_MIN: attended by nobody, score 0).
+static inline size_t ext_stride(const sparsek_cfg& c) { return align_up((size_t)(c.k > 0 ? c.k : 1), KT); }
+static inline size_t ext_array_bytes(const sparsek_cfg& c)
+{
+    return align_up((size_t)c.B * c.Gu * nblocks(c.n) * ext_stride(c) * sizeof(int32_t), 256);
+}
+
+size_t attn_fwd_ws_bytes(const sparsek_cfg& c) { return block_lists_bytes(c, nullptr) + 3 * ext_array_bytes(c); }
 
 // ---------------------------------------------------------------------------------
 // Per (row, block): the positions of the top-k of prefix T0 = blk*QB - w, in two partitions:
@@ -38,13 +48,18 @@ size_t attn_fwd_ws_bytes(const sparsek_cfg& c) { return block_lists_bytes(c, nul
 // then, filled from the back, the keys that expire inside the block.  Only the tiles of the
 // second partition need a per-pair validity test.  Each of the 16 waves owns a slice of
 // [0, T0]: one counting pass, one barrier, one placement pass.
+// With xpos != nullptr the same lists are also written in the extended form described above.
 // ---------------------------------------------------------------------------------
 constexpr int BL_WAVES = 16;   // waves per workgroup of block_lists_kernel
 constexpr int BL_UNROLL = 8;   // loads in flight per lane
 
 __global__ __launch_bounds__(64 * BL_WAVES) void block_lists_kernel(const int32_t* __restrict__ death, int n, int k,
                                                                      int w, int nb, int32_t* __restrict__ lists,
-                                                                     int32_t* __restrict__ counts)
+                                                                     int32_t* __restrict__ counts,
+                                                                     const float* __restrict__ u,
+                                                                     int32_t* __restrict__ xpos,
+                                                                     int32_t* __restrict__ xdeath,
+                                                                     float* __restrict__ xu, int KP)
 {
     __shared__ int wstay[BL_WAVES], wgo[BL_WAVES];
     const int blk = blockIdx.x, row = blockIdx.y;
@@ -59,6 +74,8 @@ __global__ __launch_bounds__(64 * BL_WAVES) void block_lists_kernel(const int32_
         return;
     }
     const int32_t* dr = death + (size_t)row * n;
+    const float* ur = u ? u + (size_t)row * n : nullptr;
+    const size_t xo = ((size_t)row * nb + blk) * (size_t)KP;
     const int len = T0 + 1;
     constexpr int STEP = 64 * BL_UNROLL;
     const int per = ((len + BL_WAVES - 1) / BL_WAVES + STEP - 1) / STEP * STEP;
@@ -101,13 +118,19 @@ __global__ __launch_bounds__(64 * BL_WAVES) void block_lists_kernel(const int32_
             const int j = j0 + 64 * e + lane;
             const bool stay = dj[e] >= stay_from, go = dj[e] > T0 && dj[e] < stay_from;
             const unsigned long long bs = __ballot(stay), bg = __ballot(go);
+            int o = -1;
             if (stay) {
-                const int o = os + __popcll(bs & below);
-                if (o < cnt) lo[o] = j;
+                o = os + __popcll(bs & below);
+                if (o >= cnt) o = -1;
             }
-            if (go) {
-                const int o = cnt - 1 - (og + __popcll(bg & below));
-                if (o >= 0) lo[o] = j;
+            if (go) o = cnt - 1 - (og + __popcll(bg & below));
+            if (o >= 0) {
+                lo[o] = j;
+                if (xpos) {
+                    xpos[xo + o] = j;
+                    xdeath[xo + o] = dj[e];
+                    xu[xo + o] = ur[j];
+                }
             }
             os += __popcll(bs);
             og += __popcll(bg);
@@ -116,6 +139,15 @@ __global__ __launch_bounds__(64 * BL_WAVES) void block_lists_kernel(const int32_
     if (tid == 0) {
         counts[(size_t)row * nb + blk] = cnt;
         counts[((size_t)gridDim.y + row) * nb + blk] = min(cnt, tot_s);
+    }
+    if (xpos) {
+        // padding up to the tile boundary above min(k, T0 + 1), the length the forward kernel lays its tiles out for
+        const int padded = (min(k, len) + KT - 1) / KT * KT;
+        for (int o = cnt + tid; o < padded; o += 64 * BL_WAVES) {
+            xpos[xo + o] = 0;
+            xdeath[xo + o] = INT32_MIN;
+            xu[xo + o] = 0.0f;
+        }
     }
 }
 
@@ -248,6 +280,19 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(
 // with one MFMA followed by a slice of the softmax work, the slices fenced with sched_barrier
 // so that the compiler keeps the order.
 // ---------------------------------------------------------------------------------
+// Metadata (position, lifetime, score of every key of the block's key set) is staged in segments of TPS tiles, double
+// buffered: while the tiles of one segment run, the next segment is copied into the other buffer.
+constexpr int TPS = 9;
+constexpr int SEGN = TPS * KT;
+
+template <int D>
+struct FwdSmem : MfmaTileBufs<D, 64> {
+    int32_t jpos[2][SEGN];    // key position
+    int32_t jdeath[2][SEGN];  // death[j]: the key is attended by query i while i <= w - 1 + death[j]; INT_MIN = padding
+    float ju[2][SEGN];        // key score
+};
+static_assert(sizeof(FwdSmem<128>) <= 80 * 1024, "two workgroups per CU");
+
 // Tile kinds.  Along a block's key set they come in runs (per wave), so the tile loop is a
 // sequence of loops, one per kind, and each loop body is straight-line code:
 //   LIST       selected keys that stay selected for every query of the block: gates, no mask
@@ -297,7 +342,7 @@ struct HalfState {
 };
 
 template <int MODE, int KIND>
-__device__ __forceinline__ void load_meta(HalfState& h, const int32_t* jlast, const float* ju, int hf, int half)
+__device__ __forceinline__ void load_meta(HalfState& h, const float* ju, int hf, int half)
 {
     using TT = TileTraits<MODE, KIND>;
 #pragma unroll
@@ -316,8 +361,8 @@ __device__ __forceinline__ void load_meta(HalfState& h, const int32_t* jlast, co
 // keeps the rescale of the output accumulator a rare event).  U = 4..7: exponentials, row sum,
 // value gate and bf16 packing of key group U - 4.
 template <int MODE, int KIND, int U>
-__device__ __forceinline__ void softmax_slice(HalfState& h, f32x16& sv, const int32_t* jlast, int half, int hf,
-                                              int qi, int dqh, int dqw, float tau_q, float c2, SoftRef& ref)
+__device__ __forceinline__ void softmax_slice(HalfState& h, f32x16& sv, const int32_t* jdeath, int half, int hf,
+                                              int qw, int dqh, int dqw, float tau_q, float c2, SoftRef& ref)
 {
     using TT = TileTraits<MODE, KIND>;
     constexpr float LAZY_LOG2 = 8.0f;
@@ -327,7 +372,7 @@ __device__ __forceinline__ void softmax_slice(HalfState& h, f32x16& sv, const in
         // lifetimes are read where they are used (only the few masked tile kinds need them):
         // holding them across the tile costs more registers than the kernel has
         int4 L4 = make_int4(0, 0, 0, 0);
-        if (TT::MASKL) L4 = *(const int4*)&jlast[32 * hf + 8 * g4 + 4 * half];
+        if (TT::MASKL) L4 = *(const int4*)&jdeath[32 * hf + 8 * g4 + 4 * half];
         const int ll[4] = {L4.x, L4.y, L4.z, L4.w};
 #pragma unroll
         for (int e = 0; e < 4; e++) {
@@ -342,8 +387,9 @@ __device__ __forceinline__ void softmax_slice(HalfState& h, f32x16& sv, const in
                 gg[e] = g;
                 if (TT::KGATE) s2 *= g;
             }
-            if (TT::MASKL && TT::MASKC) s2 = (cst <= dqh && qi <= ll[e]) ? s2 : -INFINITY;
-            else if (TT::MASKL) s2 = (qi <= ll[e]) ? s2 : -INFINITY;
+            // key j is attended by query i while i <= w - 1 + death[j], i.e. qw = i - (w - 1) <= death[j]
+            if (TT::MASKL && TT::MASKC) s2 = (cst <= dqh && qw <= ll[e]) ? s2 : -INFINITY;
+            else if (TT::MASKL) s2 = (qw <= ll[e]) ? s2 : -INFINITY;
             else if (TT::MASKC) s2 = (cst <= dqh) ? s2 : -INFINITY;
             sv[r] = s2;
             h.tmax = fmaxf(h.tmax, s2);
@@ -382,12 +428,12 @@ __device__ __forceinline__ void softmax_slice(HalfState& h, f32x16& sv, const in
 }
 
 template <int MODE, int KIND, int U0, int U1>
-__device__ __forceinline__ void softmax_slices(HalfState& h, f32x16& sv, const int32_t* jlast, int half, int hf,
-                                               int qi, int dqh, int dqw, float tau_q, float c2, SoftRef& ref)
+__device__ __forceinline__ void softmax_slices(HalfState& h, f32x16& sv, const int32_t* jdeath, int half, int hf,
+                                               int qw, int dqh, int dqw, float tau_q, float c2, SoftRef& ref)
 {
     if constexpr (U0 < U1) {
-        softmax_slice<MODE, KIND, U0>(h, sv, jlast, half, hf, qi, dqh, dqw, tau_q, c2, ref);
-        softmax_slices<MODE, KIND, U0 + 1, U1>(h, sv, jlast, half, hf, qi, dqh, dqw, tau_q, c2, ref);
+        softmax_slice<MODE, KIND, U0>(h, sv, jdeath, half, hf, qw, dqh, dqw, tau_q, c2, ref);
+        softmax_slices<MODE, KIND, U0 + 1, U1>(h, sv, jdeath, half, hf, qw, dqh, dqw, tau_q, c2, ref);
     }
 }
 
@@ -395,13 +441,14 @@ __device__ __forceinline__ void softmax_slices(HalfState& h, f32x16& sv, const i
 // sequence of MFMA slots (S_A, S_B, PV_A, PV_B); the LDS operand of slot n is requested DEPTH
 // slots earlier into a small register ring, so that no MFMA waits for a read it has just issued.
 template <int D, int MODE, int KIND>
-__device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, int jbase, bool more,
+__device__ __forceinline__ void tile_body(FwdSmem<D>& sm, int buf, const int32_t* jdeath, const float* ju,
+                                          const int32_t* jp_next, int jbase, bool more,
                                           const uint16_t* kh, const uint16_t* vh, int wv, int col, int half,
                                           int lane, int qi, int w, float tau_q, float c2,
                                           const bf16x8 (&qreg)[D / 16], f32x16 (&acc_o)[D / 32], SoftRef& ref,
                                           float& l_run)
 {
-    using S = MfmaSmem<D>;
+    using S = FwdSmem<D>;
     constexpr int NS = D / 16;      // MFMAs per half of S^T
     constexpr int DB = D / 32;      // 32-row blocks of O^T
     constexpr int NP = 2 * DB;      // MFMAs per half of O^T += V^T.P^T
@@ -413,8 +460,7 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
     static_assert(NX <= NS, "one gather step per S_A slot");
     const unsigned char* kbuf = sm.kb[buf];
     const unsigned char* vbuf = sm.vb[buf];
-    const int32_t* jlast = sm.jlast + base;
-    const float* ju = sm.ju + base;
+    const int qw = qi - (w - 1);
     const int dqh = qi - jbase - 4 * half;  // contiguous tiles: key number cst + 4*half sits dqh - cst behind the query
     const int dqw = dqh - w;                // in the window  <=>  cst > dqw
     const unsigned char* krA = kbuf + (col % S::NL) * S::GSK + (col / S::NL) * S::RB + 16 * half;
@@ -451,8 +497,8 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
 #pragma unroll
     for (int n = 0; n < DEPTH; n++) ring[n] = operand(n);
     TileRows<D, 64> rows;
-    if (more) rows = tile_rows<D, 64>(sm.jpos + base + KT, wv, lane);
-    load_meta<MODE, KIND>(A, jlast, ju, 0, half);
+    if (more) rows = tile_rows<D, 64>(jp_next, wv, lane);
+    load_meta<MODE, KIND>(A, ju, 0, half);
     __builtin_amdgcn_sched_barrier(0);
     // ---- S_A, then S_B with softmax(A) ----
     static_for<0, 2 * NS>([&](auto nc) {
@@ -466,8 +512,8 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
         if (n < NX && more) tile_load_step<D, 64>(sm, buf ^ 1, rows, n, kh, vh, wv, lane);
         if (n >= NS) {
             constexpr int s = n >= NS ? n - NS : 0;
-            softmax_slices<MODE, KIND, US * s, US * (s + 1)>(A, sA, jlast, half, 0, qi, dqh, dqw, tau_q, c2, ref);
-            if (US * (s + 1) == 4) load_meta<MODE, KIND>(B, jlast, ju, 1, half);
+            softmax_slices<MODE, KIND, US * s, US * (s + 1)>(A, sA, jdeath, half, 0, qw, dqh, dqw, tau_q, c2, ref);
+            if (US * (s + 1) == 4) load_meta<MODE, KIND>(B, ju, 1, half);
         }
         __builtin_amdgcn_sched_barrier(0);
     });
@@ -482,7 +528,7 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
         const bf16x8 cur = ring[n % DEPTH];
         acc_o[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur, A.pb[i / DB], acc_o[i % DB], 0, 0, 0);
         if (n + DEPTH < NSLOT) ring[n % DEPTH] = operand(n + DEPTH);
-        softmax_slices<MODE, KIND, UP * i, UP * (i + 1)>(B, sB, jlast, half, 1, qi, dqh, dqw, tau_q, c2, ref);
+        softmax_slices<MODE, KIND, UP * i, UP * (i + 1)>(B, sB, jdeath, half, 1, qw, dqh, dqw, tau_q, c2, ref);
         __builtin_amdgcn_sched_barrier(0);
     });
     asm volatile("" ::"v"(B.pb[0]), "v"(B.pb[1]), "v"(B.psum));
@@ -498,24 +544,76 @@ __device__ __forceinline__ void tile_body(MfmaSmem<D>& sm, int buf, int base, in
     });
 }
 
-// The tiles [t, t_end) of the current segment, all of one kind.
+// What a wave needs to stage a segment of metadata (see FwdSmem).
+struct StageSrc {
+    const int32_t* xpos;    // extended list of this (row, block): positions, lifetimes, scores
+    const int32_t* xdeath;
+    const float* xu;
+    const int32_t* dr;      // lifetimes and scores of the score row, for the contiguous keys
+    const float* ur;
+    int nkl, c0, c_end, nt; // list part in keys (whole tiles), first and last contiguous key, tiles in all
+};
+
+// Segment sg of the block's key set (tiles sg*TPS .. ) goes to metadata buffer sg & 1.  Each wave copies the tiles
+// wv, wv + 4, ...: plain copies that land in LDS without passing through registers and that the compiler does not
+// track (the per-tile s_waitcnt vmcnt(0) + barrier publishes them).  A tile lies entirely in the list part or
+// entirely in the contiguous part.
+template <int D>
+__device__ __forceinline__ void stage_meta(FwdSmem<D>& sm, const StageSrc& src, int sg, int wv, int lane)
+{
+    const int mb = sg & 1;
+    const int t_end = min(TPS, src.nt - sg * TPS);
+    for (int lt = wv; lt < t_end; lt += 4) {
+        const int E0 = (sg * TPS + lt) * KT;
+        int32_t* dp = sm.jpos[mb] + lt * KT;
+        int32_t* dd = sm.jdeath[mb] + lt * KT;
+        float* du = sm.ju[mb] + lt * KT;
+        if (E0 < src.nkl) {
+            const uint32_t off = 4u * (uint32_t)(E0 + lane);
+            async_load_lds4(src.xpos, off, dp);
+            async_load_lds4(src.xdeath, off, dd);
+            async_load_lds4(src.xu, off, du);
+        } else {
+            const int j = src.c0 + (E0 - src.nkl) + lane;
+            const bool real = j <= src.c_end;
+            dp[lane] = real ? j : 0;
+            if (real) {
+                async_load_lds4(src.dr, 4u * (uint32_t)j, dd);
+                async_load_lds4(src.ur, 4u * (uint32_t)j, du);
+            } else {   // beyond the block's last key: always behind the causal test; any finite value will do
+                dd[lane] = INT32_MIN;
+                du[lane] = 0.0f;
+            }
+        }
+    }
+}
+
+// The tiles [T, T_end) of the block's key set, all of one kind.  T counts the block's tiles; tile T uses K/V buffer
+// T & 1 and the metadata of segment T / TPS.
 template <int D, int MODE, int KIND>
-__device__ __forceinline__ void run_tiles(MfmaSmem<D>& sm, int& t, int t_end, int ntiles, int jbase0,
+__device__ __forceinline__ void run_tiles(FwdSmem<D>& sm, const StageSrc& src, int& T, int T_end, int jbase0,
                                           const uint16_t* kh, const uint16_t* vh, int wv, int col, int half,
                                           int lane, int qi, int w, float tau_q, float c2,
                                           const bf16x8 (&qreg)[D / 16], f32x16 (&acc_o)[D / 32], SoftRef& ref,
                                           float& l_run)
 {
-    for (; t < t_end; t++) {
-        // tile t has landed (this wave's part: vmcnt; the other waves' parts: barrier); the
-        // barrier also says that everybody is done with tile t-1, whose buffer is refilled next
+    for (; T < T_end; T++) {
+        // tile T has landed (this wave's part: vmcnt; the other waves' parts: barrier); the
+        // barrier also says that everybody is done with tile T-1, whose buffer is refilled next
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        const int sg = T / TPS, lt = T - sg * TPS;
+        // first tile of a segment: everybody has left the segment before, so its metadata buffer takes the next one
+        if (lt == 0 && (sg + 1) * TPS < src.nt) stage_meta<D>(sm, src, sg + 1, wv, lane);
+        const int sgn = (T + 1) / TPS;
+        const int32_t* jp_next = sm.jpos[sgn & 1] + (T + 1 - sgn * TPS) * KT;
+        const bool more = T + 1 < src.nt;
         if (KIND != TILE_SKIP)
-            tile_body<D, MODE, KIND>(sm, t & 1, t * KT, jbase0 + t * KT, t + 1 < ntiles, kh, vh, wv, col, half, lane,
-                                     qi, w, tau_q, c2, qreg, acc_o, ref, l_run);
-        else if (t + 1 < ntiles)
-            issue_tile_loads<D, 64>(sm, (t + 1) & 1, sm.jpos + (t + 1) * KT, kh, vh, wv, lane);
+            tile_body<D, MODE, KIND>(sm, T & 1, sm.jdeath[sg & 1] + lt * KT, sm.ju[sg & 1] + lt * KT, jp_next,
+                                     jbase0 + T * KT, more, kh, vh, wv, col, half, lane, qi, w, tau_q, c2, qreg,
+                                     acc_o, ref, l_run);
+        else if (more)
+            issue_tile_loads<D, 64>(sm, (T + 1) & 1, jp_next, kh, vh, wv, lane);
     }
 }
 
@@ -523,13 +621,16 @@ template <int D, int MODE>
 __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ kk, const uint16_t* __restrict__ v,
     const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
-    const int32_t* __restrict__ lists, const int32_t* __restrict__ counts, uint16_t* __restrict__ o,
+    const int32_t* __restrict__ xpos, const int32_t* __restrict__ xdeath, const float* __restrict__ xu, int KP,
+    const int32_t* __restrict__ counts, uint16_t* __restrict__ o,
     float* __restrict__ lse, int H, int Gu, int n, int k, int w, float scale, int nb, int BH, int nrows,
     int q_begin, const int32_t* __restrict__ first_valid, int q_rows)
 {
-    __shared__ __align__(16) MfmaSmem<D> sm;
+    __shared__ __align__(16) FwdSmem<D> sm;
     constexpr int DS = D / 16;   // MFMA k-steps over the head dim
     constexpr int DB = D / 32;   // 32-row blocks of O^T
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, col = lane & 31;
 
     // ---- block -> (head, query block): heads are dealt to the 8 XCDs so that one head's
     // blocks share an L2; late (long) blocks go first
@@ -547,8 +648,6 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     }
     const int b = bh / H, h = bh % H;
     const int row = b * Gu + (Gu == 1 ? 0 : h);
-    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int half = lane >> 5, col = lane & 31;
     const int i0 = blk * QB;
     if (i0 + QB <= q_begin) return;  // queries before q_begin are not wanted (chunked prefill)
     // q and o hold q_rows rows per head starting at query q_begin (0: all n rows)
@@ -556,18 +655,31 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     const uint16_t* qh = q + qo * D;
     const uint16_t* kh = kk + (size_t)bh * n * D;
     const uint16_t* vh = v + (size_t)bh * n * D;
-    const float* ur = u + (size_t)row * n;
     const float* tr = tau + (size_t)row * n;
-    const int32_t* dr = death + (size_t)row * n;
-    const int32_t* list = lists + ((size_t)row * nb + blk) * (size_t)(k > 0 ? k : 1);
-    const int cnt = counts[(size_t)row * nb + blk];
     const int nstay = counts[(size_t)nrows * nb + (size_t)row * nb + blk];
     // keys before first_valid[row] (padding of a chunked prefill) are attended by nobody
     const int c0 = max(max(0, i0 - w + 1), first_valid ? first_valid[row] : 0);
     const int c_end = min(n - 1, i0 + QB - 1);
-    const int nkl = (cnt + KT - 1) / KT * KT;                // list part, padded to whole tiles
-    const int nkc = (c_end - c0 + 1 + KT - 1) / KT * KT;     // contiguous part, padded
-    const int nk_total = nkl + nkc;
+    // The list part is laid out for min(k, T0 + 1) keys, the length of a complete top-k list (known without a load);
+    // a shorter list (lifetimes cleared by a chunked prefill) ends in padding that nobody attends.
+    const int T0 = i0 - w;
+    const int nkl = (T0 >= 0 && k > 0) ? (min(k, T0 + 1) + KT - 1) / KT * KT : 0;   // list part, whole tiles
+    const int nkc = max(0, (c_end - c0 + 1 + KT - 1) / KT * KT);                    // contiguous part, padded
+    const int NT = (nkl + nkc) / KT;
+
+    StageSrc src;
+    {
+        const size_t xo = ((size_t)row * nb + blk) * (size_t)KP;
+        src.xpos = xpos + xo;
+        src.xdeath = xdeath + xo;
+        src.xu = xu + xo;
+        src.dr = death + (size_t)row * n;
+        src.ur = u + (size_t)row * n;
+        src.nkl = nkl;
+        src.c0 = c0;
+        src.c_end = c_end;
+        src.nt = NT;
+    }
 
     // ---- this wave's queries ----
     const int qa = i0 + 32 * wv;          // first query of the wave
@@ -580,8 +692,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
 #pragma unroll
     for (int s = 0; s < DS; s++)
         qreg[s] = *(const bf16x8*)(qh + (size_t)qrow * D + 16 * s + 8 * half);
+    // the first segment of metadata: its copies need nothing that is loaded above, so they fly together
+    stage_meta<D>(sm, src, 0, wv, lane);
 
-    // ---- the runs of tile kinds for this wave, as global tile numbers (all wave-uniform) ----
+    // ---- the runs of tile kinds for this wave, as tile numbers (all wave-uniform) ----
     //   [0,b0) LIST  [b0,b1) LIST_MASK  [b1,b2) EDGE or CONT  [b2,b3) FAST  [b3,b4) DIAG  [b4,..) SKIP
     int b0 = 0, b1 = 0, b2 = 0, b3 = 0, b4 = 0;
     bool narrow = false;
@@ -613,47 +727,27 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     float l_run = 0.0f;
     const float c2 = scale * 1.4426950408889634f;
 
-    for (int seg0 = 0; seg0 < nk_total; seg0 += SEG) {
-        const int seg_n = min(SEG, nk_total - seg0);
-        __syncthreads();  // previous segment fully consumed (metadata and both tile buffers)
-        for (int e = tid; e < seg_n; e += 256) {
-            const int E = seg0 + e;
-            int j = 0;
-            bool real;
-            if (E < nkl) {
-                real = E < cnt;
-                if (real) j = list[E];
-            } else {
-                j = c0 + (E - nkl);
-                real = j <= c_end;
-                if (!real) j = 0;
-            }
-            sm.jpos[e] = j;
-            sm.jlast[e] = real ? (w - 1 + dr[j]) : -1;
-            sm.ju[e] = real ? ur[j] : 0.0f;
-        }
-        __syncthreads();
-        const int ntiles = seg_n / KT;
-        const int T0 = seg0 / KT;                 // global number of the segment's first tile
-        const int jbase0 = c0 + (seg0 - nkl);     // position of local tile 0 if it were contiguous
-        // The tile gathers are direct-to-LDS loads that the compiler does not track.  Everything it does track
-        // (the Q fragments, the metadata above) is waited for here, ahead of the first of them: left to their
-        // first use inside the tile loop, those waits would count the prefetched tile too and drain it early.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // The metadata copies and the tile gathers are direct-to-LDS loads that the compiler does not track.  Everything
+    // it does track (the Q fragments, tau, the counts) is waited for here, ahead of the first gather: left to their
+    // first use inside the tile loop, those waits would count the prefetched tile too and drain it early.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-        for (int s = 0; s < DS; s++) asm volatile("" ::"v"(qreg[s]));
-        issue_tile_loads<D, 64>(sm, 0, sm.jpos, kh, vh, wv, lane);
-        int t = 0;
-#define SPK_RUN(KIND, bound)                                                                                   \
-    run_tiles<D, MODE, KIND>(sm, t, min(ntiles, (bound) - T0), ntiles, jbase0, kh, vh, wv, col, half, lane, qi, \
-                             w, tau_q, c2, qreg, acc_o, ref, l_run)
+    for (int s = 0; s < DS; s++) asm volatile("" ::"v"(qreg[s]));
+    __syncthreads();  // segment 0 of the metadata is in place
+    if (NT > 0) issue_tile_loads<D, 64>(sm, 0, sm.jpos[0], kh, vh, wv, lane);
+    {
+        const int jbase0 = c0 - nkl;     // position of tile 0's first key if the whole key set were contiguous
+        int T = 0;
+#define SPK_RUN(KIND, bound)                                                                                     \
+    run_tiles<D, MODE, KIND>(sm, src, T, min(NT, (bound)), jbase0, kh, vh, wv, col, half, lane, qi, w, tau_q, c2, \
+                             qreg, acc_o, ref, l_run)
         SPK_RUN(TILE_LIST, b0);
         SPK_RUN(TILE_LIST_MASK, b1);
         if (narrow) SPK_RUN(TILE_CONT, b2);
         else SPK_RUN(TILE_EDGE, b2);
         SPK_RUN(TILE_FAST, b3);
         SPK_RUN(TILE_DIAG, b4);
-        SPK_RUN(TILE_SKIP, T0 + ntiles);
+        SPK_RUN(TILE_SKIP, NT);
 #undef SPK_RUN
     }
 
@@ -676,30 +770,44 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     }
 }
 
+struct ExtLists {
+    int32_t* pos;
+    int32_t* death;
+    float* u;
+    int KP;
+};
+
 template <int D>
 static void launch_mfma(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
-                        const float* tau, const int32_t* death, const int32_t* lists, const int32_t* counts,
+                        const float* tau, const int32_t* death, const ExtLists& x, const int32_t* counts,
                         void* o, float* lse, int nb, int q_begin, const int32_t* first_valid,
                         int q_rows, hipStream_t st)
 {
     const int BH = c.B * c.H;
     dim3 grid(nb * BH);
-#define SPK_LAUNCH(MODE)                                                                                   \
-    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q,        \
-                       (const uint16_t*)k, (const uint16_t*)v, u, tau, death, lists, counts, (uint16_t*)o, \
-                       lse, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH, c.B * c.Gu, q_begin, first_valid, q_rows)
+#define SPK_LAUNCH(MODE)                                                                                          \
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q,               \
+                       (const uint16_t*)k, (const uint16_t*)v, u, tau, death, (const int32_t*)x.pos,              \
+                       (const int32_t*)x.death, (const float*)x.u, x.KP, counts, (uint16_t*)o, lse, c.H, c.Gu,    \
+                       c.n, c.k, c.w, c.softmax_scale, nb, BH, c.B * c.Gu, q_begin, first_valid, q_rows)
     if (c.gate_mode == 0) SPK_LAUNCH(0);
     else if (c.gate_mode == 1) SPK_LAUNCH(1);
     else SPK_LAUNCH(2);
 #undef SPK_LAUNCH
 }
 
-void launch_block_lists(const sparsek_cfg& c, const int32_t* death, int32_t* lists, int32_t* counts,
-                        hipStream_t st)
+static void launch_block_lists_ext(const sparsek_cfg& c, const int32_t* death, int32_t* lists, int32_t* counts,
+                                   const float* u, const ExtLists& x, hipStream_t st)
 {
     const int nb = nblocks(c.n);
     hipLaunchKernelGGL(block_lists_kernel, dim3(nb, c.B * c.Gu), dim3(64 * BL_WAVES), 0, st, death, c.n, c.k, c.w, nb,
-                       lists, counts);
+                       lists, counts, u, x.pos, x.death, x.u, x.KP);
+}
+
+void launch_block_lists(const sparsek_cfg& c, const int32_t* death, int32_t* lists, int32_t* counts,
+                        hipStream_t st)
+{
+    launch_block_lists_ext(c, death, lists, counts, nullptr, ExtLists{nullptr, nullptr, nullptr, 0}, st);
 }
 
 int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
@@ -708,15 +816,22 @@ int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const vo
 {
     const int nb = nblocks(c.n);
     size_t coff = 0;
-    block_lists_bytes(c, &coff);
+    const size_t lb = block_lists_bytes(c, &coff);
     int32_t* lists = (int32_t*)ws;
     int32_t* counts = (int32_t*)((char*)ws + coff);
-    launch_block_lists(c, death, lists, counts, st);
     if (c.dtype == SPARSEK_BF16 && (c.d == 64 || c.d == 128) && (uint64_t)c.n * c.d * 2 <= 0xFFFFFFFFull) {
-        if (c.d == 64) launch_mfma<64>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, q_begin, first_valid, q_rows, st);
-        else launch_mfma<128>(c, q, k, v, u, tau, death, lists, counts, o, lse, nb, q_begin, first_valid, q_rows, st);
+        const size_t xb = ext_array_bytes(c);
+        ExtLists x;
+        x.pos = (int32_t*)((char*)ws + lb);
+        x.death = (int32_t*)((char*)ws + lb + xb);
+        x.u = (float*)((char*)ws + lb + 2 * xb);
+        x.KP = (int)ext_stride(c);
+        launch_block_lists_ext(c, death, lists, counts, u, x, st);
+        if (c.d == 64) launch_mfma<64>(c, q, k, v, u, tau, death, x, counts, o, lse, nb, q_begin, first_valid, q_rows, st);
+        else launch_mfma<128>(c, q, k, v, u, tau, death, x, counts, o, lse, nb, q_begin, first_valid, q_rows, st);
         return launch_status();
     }
+    launch_block_lists(c, death, lists, counts, st);
     dim3 grid(nb, c.B * c.H);
     if (c.dtype == SPARSEK_F32) {
         hipLaunchKernelGGL(attn_fwd_generic_kernel<float>, grid, dim3(256), 0, st, (const float*)q,

@@ -45,8 +45,9 @@ __device__ __forceinline__ void async_load_lds16(const void* gbase, uint32_t vof
 constexpr int KT = 64;     // keys per tile
 constexpr int SEG = 1088;  // keys whose metadata is staged in LDS at a time (17 tiles)
 
+// The double-buffered K and V tiles of a workgroup.
 template <int D, int VPAD = 64>
-struct MfmaSmem {
+struct MfmaTileBufs {
     static constexpr int RB = D * 2;        // bytes per K/V row
     static constexpr int RPL = 1024 / RB;   // rows per wave-load
     static constexpr int NL = KT / RPL;     // wave-loads (row groups) per tile and tensor
@@ -54,10 +55,14 @@ struct MfmaSmem {
     static constexpr int GSV = 1024 + VPAD; // group stride of the V buffer (64: transposing reads, 16: row reads)
     unsigned char kb[2][NL * GSK];
     unsigned char vb[2][NL * GSV];
+};
+
+// Tiles plus the metadata of one segment of keys, staged by the workgroup before the segment's tile loop.
+template <int D, int VPAD = 64>
+struct MfmaSmem : MfmaTileBufs<D, VPAD> {
     int32_t jpos[SEG];        // key position
     int32_t jlast[SEG];       // last query that attends the key: w - 1 + death[j]; -1 = padding
     float ju[SEG];            // key score
-    int32_t tile_lmin[SEG / KT];
 };
 
 // The gather of one tile (64 rows of K and of V) into buffer `buf`, as NL/4 steps per wave:
@@ -66,13 +71,13 @@ struct MfmaSmem {
 // (the host checks n * RB < 2^32), so every load is a uniform base plus one v_lshl_add_u32.
 template <int D, int VPAD>
 struct TileRows {
-    int32_t j[MfmaSmem<D, VPAD>::NL / 4];
+    int32_t j[MfmaTileBufs<D, VPAD>::NL / 4];
 };
 
 template <int D, int VPAD>
 __device__ __forceinline__ TileRows<D, VPAD> tile_rows(const int32_t* jp, int wv, int lane)
 {
-    using S = MfmaSmem<D, VPAD>;
+    using S = MfmaTileBufs<D, VPAD>;
     constexpr int LPR = S::RB / 16;  // lanes per row
     constexpr int NX = S::NL / 4;
     const int jrow = lane / LPR;
@@ -90,11 +95,11 @@ __device__ __forceinline__ TileRows<D, VPAD> tile_rows(const int32_t* jp, int wv
 }
 
 template <int D, int VPAD>
-__device__ __forceinline__ void tile_load_step(MfmaSmem<D, VPAD>& sm, int buf, const TileRows<D, VPAD>& rows, int x,
+__device__ __forceinline__ void tile_load_step(MfmaTileBufs<D, VPAD>& sm, int buf, const TileRows<D, VPAD>& rows, int x,
                                                const uint16_t* __restrict__ kh, const uint16_t* __restrict__ vh,
                                                int wv, int lane)
 {
-    using S = MfmaSmem<D, VPAD>;
+    using S = MfmaTileBufs<D, VPAD>;
     constexpr int LPR = S::RB / 16;
     const int c = lane % LPR;
     const int L = wv * (S::NL / 4) + x;
@@ -104,13 +109,13 @@ __device__ __forceinline__ void tile_load_step(MfmaSmem<D, VPAD>& sm, int buf, c
 }
 
 template <int D, int VPAD>
-__device__ __forceinline__ void issue_tile_loads(MfmaSmem<D, VPAD>& sm, int buf, const int32_t* jp,
+__device__ __forceinline__ void issue_tile_loads(MfmaTileBufs<D, VPAD>& sm, int buf, const int32_t* jp,
                                                  const uint16_t* __restrict__ kh, const uint16_t* __restrict__ vh,
                                                  int wv, int lane)
 {
     const TileRows<D, VPAD> rows = tile_rows<D, VPAD>(jp, wv, lane);
 #pragma unroll
-    for (int x = 0; x < MfmaSmem<D, VPAD>::NL / 4; x++) tile_load_step<D, VPAD>(sm, buf, rows, x, kh, vh, wv, lane);
+    for (int x = 0; x < MfmaTileBufs<D, VPAD>::NL / 4; x++) tile_load_step<D, VPAD>(sm, buf, rows, x, kh, vh, wv, lane);
 }
 
 // Compile-time loop: f(integral_constant<int, I>) for I = 0 .. N-1.
