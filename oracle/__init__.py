@@ -18,6 +18,8 @@ from .ref import (  # noqa: F401
     attn_bwd,
     mask_all,
     decode_bydef,
+    tau_incremental,
+    decode_incremental,
     max_threads,
     scores,
 )

@@ -206,6 +206,31 @@ def decode_bydef(q_steps, K_hist, V_hist, u_hist, n_ctx, k, w, gate_mode, scale)
     return o
 
 
+def tau_incremental(u_row, k):
+    """tau_t of every causal prefix by the incremental two-heap evaluation of Sec. 3.3."""
+    u_row = _f32(u_row)
+    n = u_row.shape[0]
+    tau = np.empty(n, np.float64)
+    rc = _L().orc_tau_incremental(_p(u_row), n, int(k), _p(tau))
+    assert rc == 0
+    return tau
+
+
+def decode_incremental(q_steps, K_hist, V_hist, u_hist, n_ctx, k, w, gate_mode, scale):
+    """Decode of one head with constant work per token (incremental threshold, top-k as a heap of k keys,
+    attention over k + w keys).  Same arguments and result as decode_bydef; also returns the seconds spent in
+    the steps alone."""
+    q_steps, K_hist, V_hist, u_hist = _f32(q_steps), _f32(K_hist), _f32(V_hist), _f32(u_hist)
+    steps, d = q_steps.shape
+    assert K_hist.shape[0] == n_ctx + steps and u_hist.shape[0] == n_ctx + steps
+    o = np.empty((steps, d), np.float64)
+    sec = C.c_double(0.0)
+    rc = _L().orc_decode_incremental(_p(q_steps), _p(K_hist), _p(V_hist), _p(u_hist), int(n_ctx), int(steps), int(d),
+                                     int(k), int(w), int(gate_mode), C.c_double(scale), _p(o), C.byref(sec))
+    assert rc == 0
+    return o, sec.value
+
+
 def scores(X, w, slope=0.0, norm=False, norm_eps=1e-5):
     """Importance scores u [B,n] fp64 from hidden states X [B,n,D] and the scorer w [D]:
     X.w plus the position slope, optionally timestep-normalised (Sec. 3.2 / Sec. 3.5)."""

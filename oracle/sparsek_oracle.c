@@ -552,6 +552,209 @@ int orc_scores(const float *X, const float *w, int B, int n, int D, double slope
     return rc;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Incremental evaluation (Sec. 3.3, the step-by-step algorithm with two      */
+/* min-heaps) and a decode loop built on it                                   */
+/* ------------------------------------------------------------------------- */
+
+/* a binary min-heap of doubles that also keeps the sum of its entries */
+typedef struct {
+    double *a;
+    int n, cap;
+    double sum;
+} orc_heap;
+
+static int heap_init(orc_heap *h, int cap)
+{
+    h->a = (double *)malloc(sizeof(double) * (size_t)(cap > 0 ? cap : 1));
+    h->n = 0;
+    h->cap = cap;
+    h->sum = 0.0;
+    return h->a ? 0 : -1;
+}
+
+static void heap_push(orc_heap *h, double x)
+{
+    int i = h->n++;
+    h->a[i] = x;
+    h->sum += x;
+    while (i > 0) {
+        int p = (i - 1) / 2;
+        if (h->a[p] <= h->a[i]) break;
+        double t = h->a[p]; h->a[p] = h->a[i]; h->a[i] = t;
+        i = p;
+    }
+}
+
+static double heap_pop(orc_heap *h)
+{
+    double top = h->a[0];
+    h->sum -= top;
+    h->a[0] = h->a[--h->n];
+    int i = 0;
+    for (;;) {
+        int l = 2 * i + 1, r = l + 1, m = i;
+        if (l < h->n && h->a[l] < h->a[m]) m = l;
+        if (r < h->n && h->a[r] < h->a[m]) m = r;
+        if (m == i) break;
+        double t = h->a[m]; h->a[m] = h->a[i]; h->a[i] = t;
+        i = m;
+    }
+    return top;
+}
+
+/* State of the incremental evaluation: S holds every score above the threshold, F every score at least one above
+ * it (F is a subset of S, as in the algorithm's input line); m counts the prefix. */
+typedef struct {
+    orc_heap S, F;
+    int m, k;
+    double tau, zmin, zmax;
+} orc_incr;
+
+/* One step of the algorithm: score z joins the prefix.  The threshold never decreases when a score is added, so
+ * scores that left S or F never come back.  z enters the heaps it belongs to under the old threshold; then the pair
+ * (u, w) = (|F|, |S|) walks downwards one breakpoint at a time: on the current linear piece the threshold is the
+ * solution equation of Sec. 3.3; it is the answer if it satisfies the order conditions z_(w) > tau and
+ * z_(u) >= tau + 1, i.e. lies below the nearest breakpoint (min(S), where a score drops out of the support, or
+ * min(F) - 1, where a score turns fractional); otherwise that score leaves its heap and the next pair is tried.
+ * A prefix of at most k scores selects everything (tau = min - 1); on a flat piece (w == u == k) the threshold is
+ * the upper end of the level set, min(F) - 1. */
+static double incr_step(orc_incr *st, double z)
+{
+    st->m++;
+    if (st->m == 1 || z < st->zmin) st->zmin = z;
+    if (st->m == 1 || z > st->zmax) st->zmax = z;
+    if (st->k == 0) { st->tau = st->zmax; return st->tau; }
+    if (st->m <= st->k) {           /* everything selected, every gate 1: all scores sit in both heaps */
+        heap_push(&st->S, z);
+        heap_push(&st->F, z);
+        st->tau = st->zmin - 1.0;
+        return st->tau;
+    }
+    if (z >= st->tau + 1.0) heap_push(&st->F, z);
+    if (z > st->tau) heap_push(&st->S, z);
+    for (;;) {
+        const int u = st->F.n, w = st->S.n;
+        if (w == u) {               /* no fractional score: f = u on this piece */
+            if (u > st->k) { heap_pop(&st->F); continue; }   /* the threshold lies higher: min(F) turns fractional */
+            st->tau = st->F.a[0] - 1.0;                       /* u == k: upper end of the level set */
+            break;
+        }
+        double tau = ((st->S.sum - st->F.sum) + (double)u - (double)st->k) / (double)(w - u);
+        if (tau < st->tau) tau = st->tau;                     /* rounding only: the threshold is monotone */
+        if (tau < st->S.a[0] && (u == 0 || tau + 1.0 <= st->F.a[0])) { st->tau = tau; break; }
+        if (u > 0 && st->F.a[0] - 1.0 <= st->S.a[0]) heap_pop(&st->F);
+        else heap_pop(&st->S);
+    }
+    return st->tau;
+}
+
+/* tau of every prefix of a score row by the incremental algorithm (compare orc_tau_prefixes, which re-sorts). */
+int orc_tau_incremental(const float *u, int n, int k, double *tau)
+{
+    if (n < 1 || k < 0) return -1;
+    orc_incr st;
+    memset(&st, 0, sizeof st);
+    st.k = k;
+    if (heap_init(&st.S, n) || heap_init(&st.F, n)) return -1;
+    for (int t = 0; t < n; t++) tau[t] = incr_step(&st, (double)u[t]);
+    free(st.S.a);
+    free(st.F.a);
+    return 0;
+}
+
+/* Decode of one head with constant work per token: positions 0..n_ctx-1 are consumed first (only their scores
+ * matter), then every step t = n_ctx .. n_ctx+steps-1 appends one position: the key leaving the window (position
+ * T = t - w) joins the SPARSEK prefix -- incremental threshold as above; the hard top-k as a min-heap of the k
+ * selected keys in the selection order, where a newcomer replaces the weakest only with a strictly larger score --
+ * and the new query attends the selected keys (gates from the current threshold) and the window.
+ * q_steps [steps,d]; K, V [n_ctx+steps,d]; u [n_ctx+steps]; o [steps,d].  seconds (may be NULL) receives the time
+ * spent in the steps alone, without the context. */
+typedef struct {
+    double z;
+    int j;
+} orc_selkey;
+
+static int sel_weaker(const orc_selkey *a, const orc_selkey *b)   /* a comes after b in the selection order */
+{
+    return a->z < b->z || (a->z == b->z && a->j > b->j);
+}
+
+static double now_seconds(void)
+{
+#ifdef _OPENMP
+    return omp_get_wtime();
+#else
+    return 0.0;
+#endif
+}
+
+int orc_decode_incremental(const float *q_steps, const float *K, const float *V, const float *u, int n_ctx,
+                           int steps, int d, int k, int w, int gate_mode, double scale, double *o,
+                           double *seconds)
+{
+    if (n_ctx < 0 || steps < 1 || k < 0 || w < 0 || k + w < 1) return -1;
+    const int n = n_ctx + steps;
+    orc_incr st;
+    memset(&st, 0, sizeof st);
+    st.k = k;
+    orc_selkey *sel = (orc_selkey *)malloc(sizeof(orc_selkey) * (size_t)(k > 0 ? k : 1));   /* min-heap: weakest on top */
+    int nsel = 0;
+    int *keys = (int *)malloc(sizeof(int) * (size_t)(k + w + 1));
+    double *gates = (double *)malloc(sizeof(double) * (size_t)(k + w + 1));
+    if (heap_init(&st.S, n) || heap_init(&st.F, n) || !sel || !keys || !gates) return -1;
+    double t0 = 0.0;
+    for (int t = 0; t < n; t++) {
+        if (t == n_ctx) t0 = now_seconds();
+        const int T = t - w;            /* the position that joins the prefix at this step */
+        if (T >= 0) {
+            incr_step(&st, (double)u[T]);
+            if (k > 0) {
+                orc_selkey nk = {(double)u[T], T};
+                if (nsel < k) {
+                    int i = nsel++;
+                    sel[i] = nk;
+                    while (i > 0 && sel_weaker(&sel[i], &sel[(i - 1) / 2])) {
+                        orc_selkey x = sel[i]; sel[i] = sel[(i - 1) / 2]; sel[(i - 1) / 2] = x;
+                        i = (i - 1) / 2;
+                    }
+                } else if (sel_weaker(&sel[0], &nk)) {   /* strictly larger score: equal scores keep the older key */
+                    sel[0] = nk;
+                    int i = 0;
+                    for (;;) {
+                        int l = 2 * i + 1, r = l + 1, m = i;
+                        if (l < nsel && sel_weaker(&sel[l], &sel[m])) m = l;
+                        if (r < nsel && sel_weaker(&sel[r], &sel[m])) m = r;
+                        if (m == i) break;
+                        orc_selkey x = sel[i]; sel[i] = sel[m]; sel[m] = x;
+                        i = m;
+                    }
+                }
+            }
+        }
+        if (t < n_ctx) continue;
+        int nk = 0;
+        if (T >= 0)
+            for (int a = 0; a < nsel; a++) {
+                keys[nk] = sel[a].j;
+                gates[nk] = clip01(sel[a].z - st.tau);
+                nk++;
+            }
+        int lo = t - w + 1;
+        if (lo < 0) lo = 0;
+        for (int j = lo; j <= t; j++) { keys[nk] = j; gates[nk] = 1.0; nk++; }
+        attend_list(q_steps + (size_t)(t - n_ctx) * d, K, V, d, keys, gates, nk, gate_mode, scale,
+                    o + (size_t)(t - n_ctx) * d, NULL, NULL, NULL);
+    }
+    if (seconds) *seconds = now_seconds() - t0;
+    free(st.S.a);
+    free(st.F.a);
+    free(sel);
+    free(keys);
+    free(gates);
+    return 0;
+}
+
 int orc_max_threads(void)
 {
 #ifdef _OPENMP

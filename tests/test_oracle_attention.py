@@ -378,3 +378,23 @@ def test_qkv_gradients_dense_limit_against_autograd(oracle):
     np.testing.assert_allclose(dK[0, 0], tk.grad.numpy(), rtol=1e-9, atol=1e-11)
     np.testing.assert_allclose(dV[0, 0], tv.grad.numpy(), rtol=1e-9, atol=1e-11)
 
+
+
+@pytest.mark.parametrize("k,w,mode", [(20, 10, 0), (5, 0, 1), (0, 8, 2), (600, 3, 0), (16, 16, 3), (1, 1, 0)])
+def test_incremental_decode_equals_decode_by_definition(oracle, k, w, mode):
+    """The constant-work decode loop (incremental threshold, heap of the k selected keys, attention over k + w
+    keys) against the definition: row t of the attention over the whole history.  Scores on a coarse grid, so the
+    tie rule of the selection (an equal newcomer does not evict) is exercised."""
+    rng = np.random.default_rng(100 * k + w)
+    n_ctx, steps, d = 500, 40, 16
+    n = n_ctx + steps
+    K, V = (rng.standard_normal((n, d)).astype(np.float32) for _ in range(2))
+    u = (np.round(rng.standard_normal(n) * 3) / 3).astype(np.float32)
+    q = rng.standard_normal((steps, d)).astype(np.float32)
+    want = oracle.decode_bydef(q, K, V, u, n_ctx, k, w, mode, 0.3)
+    got, _ = oracle.decode_incremental(q, K, V, u, n_ctx, k, w, mode, 0.3)
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-10)
+    # from an empty context as well
+    want = oracle.decode_bydef(q, K[:steps], V[:steps], u[:steps], 0, k, w, mode, 0.3)
+    got, _ = oracle.decode_incremental(q, K[:steps], V[:steps], u[:steps], 0, k, w, mode, 0.3)
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-10)

@@ -221,3 +221,25 @@ def test_death_edge_cases(oracle):
     u = np.array([0, 1, 2, 3, 4], np.float32)
     assert oracle.death(u, 2).tolist() == [2, 3, 4, 5, 5]
     assert oracle.death(u, 9).tolist() == [5] * 5
+
+
+def _score_rows(rng, n):
+    yield "normal", rng.standard_normal(n).astype(np.float32)
+    yield "ties", (np.round(rng.standard_normal(n) * 4) / 4).astype(np.float32)
+    yield "equal", np.full(n, 0.5, np.float32)
+    yield "rising", (np.arange(n) * 0.01).astype(np.float32)
+    yield "falling", (-np.arange(n) * 0.3).astype(np.float32)
+    yield "wide", (rng.standard_normal(n) * 50).astype(np.float32)
+    yield "drift", (rng.standard_normal(n) + 0.5 * np.sin(np.arange(n) / 256)).astype(np.float32)
+
+
+@pytest.mark.parametrize("n,k", [(300, 7), (1000, 64), (50, 60), (200, 0), (64, 1), (2000, 200)])
+def test_incremental_two_heap_evaluation_equals_the_sort_based_one(oracle, n, k):
+    """The step-by-step evaluation of Sec. 3.3 (two min-heaps with their sums, one breakpoint per step of the
+    (u, w) walk) must give the threshold of the re-sorting routine on every prefix, including ties, flat
+    segments (wide), prefixes of at most k scores and k = 0."""
+    rng = np.random.default_rng(n + k)
+    for name, u in _score_rows(rng, n):
+        want = oracle.tau_prefixes(u, k)[0]
+        got = oracle.tau_incremental(u, k)
+        np.testing.assert_allclose(got, want, rtol=0, atol=1e-9 * max(1.0, np.abs(want).max()), err_msg=name)
