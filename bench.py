@@ -6,7 +6,12 @@ sparsek_mask (thresholds + lifetimes) followed by sparsek_attn_fwd, at the
 Llama-7B-shaped long-context configuration (B=1, H=32, n=32768, d=128, k=w=1024, bf16).
 Inputs are resident in HBM before the timed region.  Prints one JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-bwd] [--no-decode] [--no-scores] [--no-chunk] [--only LEG]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-prefill-configs] [--no-bwd]
+                    [--no-decode] [--no-scores] [--no-chunk] [--only LEG]
+
+Besides the headline (config 4) the line carries one object per further leg: the prefill of configs 1-3, the
+backward at config 3, the score pipeline, the chunk-wise recurrent prefill and the decode of config 5, each with
+its roofline object and, where the oracle covers it, a cpu_baseline.
 """
 import argparse
 import json
@@ -21,6 +26,31 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2516.6  # 256 CUs x 2.4 GHz x 4096 flop/clk, dense
 HBM_PEAK_GBS = 8000.0
+
+
+FP32_VECTOR_PEAK_TFLOPS = 157.3  # 256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 flop x 2.4 GHz
+
+
+def stats(samples):
+    """mean / median / min of per-iteration times (ms)."""
+    xs = sorted(samples)
+    return {"mean": sum(xs) / len(xs), "median": xs[len(xs) // 2], "min": xs[0], "n": len(xs)}
+
+
+def timed(fn, iters=20, warm=3):
+    """Per-iteration device times (ms) of fn from HIP events on the launch stream."""
+    import torch
+
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return [a.elapsed_time(b) for a, b in ev]
 
 
 def attended_pairs(n, k, w):
@@ -78,18 +108,151 @@ def cpu_baseline(cfg, q, k, v, u, rows_per_head=16384):
     sample_pairs = len(heads) * sum(min(i + 1, w) + min(kk, max(i - w + 1, 0)) for i in range(a, e))
     total_pairs = cfg["B"] * H * attended_pairs(n, kk, w)
     t_full = t_mask * cfg["B"] * cfg["Gu"] + t_attn * total_pairs / sample_pairs
+    # one thread: a shorter span of one head
+    e1 = a + max(rows_per_head // 8, 64)
+    t0 = time.perf_counter()
+    oracle.attn_rows(qs[0], ks[0], vs[0], u0, tau, death, kk, w, 0, 1.0, a, e1)
+    t_one = time.perf_counter() - t0
+    one_pairs = sum(min(i + 1, w) + min(kk, max(i - w + 1, 0)) for i in range(a, e1))
+    t_full_one = t_mask * cfg["B"] * cfg["Gu"] + t_one * total_pairs / one_pairs
     return {
         "value": cfg["B"] * n / t_full,
         "unit": "tokens/s",
         "cores": cores,
         "kind": "oracle",
-        "sample": "tau+lifetimes of the full score row (%.1f s) and query rows %d..%d of %d heads "
-                  "(%.1f s), attention time scaled by attended pairs to all %d heads x %d rows"
-                  % (t_mask, a, e - 1, len(heads), t_attn, H, n),
+        "single_thread_value": cfg["B"] * n / t_full_one,
+        "sample": "tau+lifetimes of the full score row (%.1f s, one thread) and query rows %d..%d of %d heads "
+                  "(%.1f s), attention time scaled by attended pairs to all %d heads x %d rows; single thread: "
+                  "rows %d..%d of one head (%.1f s), scaled the same way"
+                  % (t_mask, a, e - 1, len(heads), t_attn, H, n, a, e1 - 1, t_one),
     }
 
 
-def decode_leg(steps=256, warm=8):
+def prefill_leg(config, iters=20, warm=3, with_cpu=True):
+    """Configs 1-3 as the headline is measured: one step = sparsek_mask + sparsek_attn_fwd on the configuration's
+    own recipe (drawn on the host: the CPU oracle gets the identical bytes).  Config 2 is bound by HBM (d = 64,
+    small k + w), config 3 by the matrix cores, config 1 (fp32, one head) runs the vector-ALU kernel and is
+    launch-bound.  The oracle is timed in full on all host threads, and on one thread on a slice of heads."""
+    import numpy as np
+    import torch
+
+    import paper_2406_16747_amd as spk
+    from paper_2406_16747_amd import synth
+
+    inp = synth.make(config)
+    B, H, n, d, k, w, Gu = (inp[x] for x in ("B", "H", "n", "d", "k", "w", "Gu"))
+    bf16 = inp["dtype"] == "bf16"
+    u = torch.from_numpy(inp["u"]).cuda()
+    q, kk, v = (synth.to_device(inp[x], inp["dtype"]) for x in ("Q", "K", "V"))
+    tau, death = spk.sparsek_mask(u, k)
+    mask_ms = stats(timed(lambda: spk.sparsek_mask(u, k), iters, warm))
+    attn_ms = stats(timed(lambda: spk.sparsek_attn_fwd(q, kk, v, u, tau, death, k, w, 0, 1.0), iters, warm))
+
+    def step():
+        t, dth = spk.sparsek_mask(u, k)
+        spk.sparsek_attn_fwd(q, kk, v, u, t, dth, k, w, 0, 1.0)
+
+    step_ms = stats(timed(step, iters, warm))
+    pairs = attended_pairs(n, k, w) * B * H
+    flops = 4.0 * d * pairs
+    nbytes = 4.0 * B * H * n * d * (2 if bf16 else 4) + B * H * n * 4 + 3.0 * B * Gu * n * 4
+    t_attn = attn_ms["mean"] * 1e-3
+    if config == 2:
+        roof = {"bound": "hbm", "achieved": nbytes / t_attn / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "algorithmic_bytes": nbytes, "mfma_tflops": flops / t_attn / 1e12,
+                "traffic": read_traffic("attn_fwd_mfma_config2_counters.txt")}
+    elif config == 3:
+        roof = {"bound": "mfma", "achieved": flops / t_attn / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "algorithmic_flops": flops, "traffic": read_traffic("attn_fwd_mfma_config3_counters.txt")}
+    else:
+        roof = {"bound": "alu", "achieved": flops / t_attn / 1e12, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "algorithmic_flops": flops, "traffic": None,
+                "note": "31 MFLOP in all: the two launches are latency-bound; microseconds are the figure to read"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["kernel"] = ("attn_fwd_mfma_kernel<%d> (+ block_lists_kernel, inside the timed call)" % d) if bf16 else \
+        "attn_fwd_generic_kernel<float> (+ block_lists_kernel, inside the timed call)"
+    roof["ms_per_launch"] = attn_ms["mean"]
+    out = {
+        "workload": "config %d: prefill fwd, B=%d H=%d n=%d d=%d k=%d w=%d %s, Gu=%d, gate_mode=0, mask+select+attention "
+                    "per step" % (config, B, H, n, d, k, w, inp["dtype"], Gu),
+        "ms_per_step": step_ms, "mask_ms": mask_ms, "attn_ms": attn_ms,
+        "tokens_per_s": B * n / (step_ms["mean"] * 1e-3), "us_per_step": step_ms["mean"] * 1e3,
+        "roofline": roof,
+    }
+    if with_cpu:
+        import oracle
+
+        oracle.build()
+        cores = min(os.cpu_count() or 1, 16)
+        t0 = time.perf_counter()
+        tau_r, death_r = oracle.mask_all(inp["u"], k)
+        t_mask = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.attn_fwd(inp["Q32"], inp["K32"], inp["V32"], inp["u"], tau_r, death_r, k, w, 0, 1.0, nthreads=cores)
+        t_all = time.perf_counter() - t0
+        hs = min(H, 2)  # one thread: the first heads of batch element 0, scaled by the head count
+        t0 = time.perf_counter()
+        oracle.attn_fwd(inp["Q32"][:1, :hs], inp["K32"][:1, :hs], inp["V32"][:1, :hs], inp["u"][:1, :1] if Gu == 1
+                        else inp["u"][:1, :hs], tau_r[:1, :1] if Gu == 1 else tau_r[:1, :hs],
+                        death_r[:1, :1] if Gu == 1 else death_r[:1, :hs], k, w, 0, 1.0, nthreads=1)
+        t_one = (time.perf_counter() - t0) * (B * H / hs)
+        out["cpu_baseline"] = {
+            "value": B * n / (t_mask + t_all), "unit": "tokens/s", "cores": min(cores, B * H), "kind": "oracle",
+            "single_thread_value": B * n / (t_mask + t_one),
+            "sample": "the whole configuration: tau+lifetimes of all %d score rows (%.2f s, one thread), attention of "
+                      "all %d heads on %d threads (%.2f s); single thread: %d head(s) (%.2f s scaled by %d/%d)"
+                      % (B * Gu, t_mask, B * H, min(cores, B * H), t_all, hs, t_one, B * H, hs),
+        }
+    return out
+
+
+def decode_cpu_baseline(hist, qs, ks, vs, us, n_ctx, k, w, B, H, steps):
+    """The oracle beside the decode leg.  (a) decode by definition (every step recomputes thresholds and lifetimes
+    of the whole history) on a slice of heads; (b) the incremental loop of Sec. 3.3 (two heaps; attention over k + w
+    keys), steps only, the context already consumed -- what a CPU implementation of the method would run.  Both
+    scaled linearly from the slice to all B*H heads (heads are independent)."""
+    import numpy as np
+
+    import oracle
+
+    oracle.build()
+    cores = min(os.cpu_count() or 1, 16)
+    heads = sorted(hist)[:cores]
+
+    def pack(bh):
+        b, h = bh
+        Kh, Vh, uh = hist[bh]
+        return (qs[:, b, h].float().cpu().numpy(), np.concatenate([Kh, ks[:, b, h].float().cpu().numpy()]),
+                np.concatenate([Vh, vs[:, b, h].float().cpu().numpy()]), np.concatenate([uh, us[:, b, 0].cpu().numpy()]))
+
+    data = [pack(bh) for bh in heads]
+    nd = min(len(data), 4)
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=nd) as ex:
+        list(ex.map(lambda a: oracle.decode_bydef(a[0], a[1], a[2], a[3], n_ctx, k, w, 0, 1.0), data[:nd]))
+    t_def = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=len(data)) as ex:
+        secs = [r[1] for r in ex.map(lambda a: oracle.decode_incremental(a[0], a[1], a[2], a[3], n_ctx, k, w, 0, 1.0),
+                                     data)]
+    t_inc_wall = time.perf_counter() - t0
+    # per-head seconds of the steps alone, run len(data) at a time
+    t_inc_steps = max(secs)
+    one = oracle.decode_incremental(*data[0], n_ctx, k, w, 0, 1.0)[1]
+    return {
+        "value": B * steps / (t_def * (B * H / nd)), "unit": "tokens/s", "cores": nd, "kind": "oracle",
+        "incremental": {"value": B * steps / (t_inc_steps * (B * H / len(data))), "unit": "tokens/s",
+                        "cores": len(data), "single_thread_value": B * steps / (one * B * H),
+                        "what": "orc_decode_incremental: two-heap threshold + heap of the k selected keys + attention "
+                                "over k+w keys, time of the %d steps alone" % steps},
+        "sample": "decode by definition of %d heads on %d threads (%.1f s, all %d steps incl. thresholds and lifetimes "
+                  "of the 33 K history), scaled by %d/%d; incremental: %d heads on %d threads (%.2f s wall incl. "
+                  "consuming the context, %.3f s for the steps), scaled by %d/%d"
+                  % (nd, nd, t_def, steps, B * H, nd, len(data), len(data), t_inc_wall, t_inc_steps, B * H, len(data)),
+    }
+
+
+def decode_leg(steps=256, warm=8, with_cpu=True):
     """Config 5: B=64, H=32, d=128, k=w=1024, context 32768 already consumed, one token per
     sequence per step, `steps` consecutive steps.  Returns the extra JSON object."""
     import torch
@@ -106,6 +269,11 @@ def decode_leg(steps=256, warm=8):
         K[b] = (torch.randn(H, n_ctx, d, device="cuda", generator=g) / div).bfloat16()
         V[b] = (torch.randn(H, n_ctx, d, device="cuda", generator=g) / div).bfloat16()
     u = torch.randn(B, Gu, n_ctx, device="cuda", generator=g)
+    hist = {}
+    if with_cpu:  # histories of a few heads for the CPU baselines, before K and V are dropped
+        for i in range(16):
+            b, h = (i * 4) % B, (i * 2 + 1) % H
+            hist[(b, h)] = (K[b, h].float().cpu().numpy(), V[b, h].float().cpu().numpy(), u[b, 0].cpu().numpy())
     tau, death = spk.sparsek_mask(u, k)
     state = spk.DecodeState(B, H, Gu, d, k, w, torch.bfloat16)
     spk.sparsek_decode_load(state, K, V, u, tau, death)
@@ -118,26 +286,32 @@ def decode_leg(steps=256, warm=8):
     for s in range(warm):
         spk.sparsek_decode_step(state, qs[s], ks[s], vs[s], us[s], out=o)
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     t0 = time.perf_counter()
-    e0.record()
     for s in range(warm, tot):
+        ev[s - warm][0].record()
         spk.sparsek_decode_step(state, qs[s], ks[s], vs[s], us[s], out=o)
-    e1.record()
+        ev[s - warm][1].record()
     torch.cuda.synchronize()
     wall_us = (time.perf_counter() - t0) / steps * 1e6
-    dev_us = e0.elapsed_time(e1) / steps * 1e3
+    per_step = stats([a.elapsed_time(b) * 1e3 for a, b in ev])
+    dev_us = ev[0][0].elapsed_time(ev[-1][1]) / steps * 1e3
     bytes_step = B * H * (k + w) * d * 2 * 2
     gbs = bytes_step / (dev_us * 1e-6) / 1e9
     overflow = bool(spk.sparsek_decode_status(state).any())
-    return {
+    out = {
         "workload": "config 5: decode, B=64 H=32 d=128 k=w=1024 bf16, context 32768, %d steps, Gu=1" % steps,
-        "us_per_step": wall_us, "device_us_per_step": dev_us, "tokens_per_s": B / (wall_us * 1e-6),
-        "candidate_overflow": overflow,
-        "roofline": {"bound": "hbm", "kernel": "decode_attn_kernel", "achieved": gbs, "peak": HBM_PEAK_GBS,
+        "us_per_step": wall_us, "device_us_per_step": dev_us, "device_us_per_step_stats": per_step,
+        "tokens_per_s": B / (wall_us * 1e-6), "candidate_overflow": overflow,
+        "roofline": {"bound": "hbm", "kernel": "decode_update_kernel + decode_attn_kernel (the whole step)",
+                     "achieved": gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "algorithmic_bytes": bytes_step,
                      "traffic": read_traffic("decode_config5_counters.txt")},
     }
+    if with_cpu:
+        out["cpu_baseline"] = decode_cpu_baseline(hist, qs[warm:], ks[warm:], vs[warm:], us[warm:], n_ctx, k, w, B, H,
+                                                  steps)
+    return out
 
 
 def mask_bwd_leg(iters=20, warm=3):
@@ -292,16 +466,36 @@ def chunk_leg(n=131072, c=8192):
                          "frac": ach / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops": flops, "traffic": None}}
 
 
+def source_digest(files):
+    """sha256 (first 12 hex digits) over the kernel sources a counter summary was taken on."""
+    import hashlib
+
+    h = hashlib.sha256()
+    for f in files:
+        h.update(open(os.path.join(ROOT, "paper_2406_16747_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:12]
+
+
 def read_traffic(name):
-    """HBM bytes per launch of the dominant kernel, from the committed counter summary."""
+    """HBM bytes per launch of the dominant kernel (FETCH_SIZE / WRITE_SIZE counters, scaled by the copy-kernel
+    calibration) from the committed counter summary -- counters cannot be read inside this process.  The summary
+    names the kernel sources it was taken on and their digest; when the sources have changed since, the figure is
+    stale and None is returned."""
     path = os.path.join(ROOT, "profiles", name)
+    val, files, digest = None, None, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+                val = float(line.split(":")[1])
+            elif line.startswith("kernel_sources:"):
+                files = line.split(":")[1].split()
+            elif line.startswith("kernel_sources_sha256:"):
+                digest = line.split(":")[1].strip()
     except OSError:
-        pass
-    return None
+        return None
+    if val is None or not files or digest != source_digest(files):
+        return None
+    return val
 
 
 def main():
@@ -315,7 +509,8 @@ def main():
     ap.add_argument("--no-bwd", action="store_true")
     ap.add_argument("--no-scores", action="store_true")
     ap.add_argument("--no-chunk", action="store_true")
-    ap.add_argument("--only", choices=["chunk", "scores", "bwd", "decode"],
+    ap.add_argument("--no-prefill-configs", action="store_true", help="skip the config 1, 2, 3 prefill legs")
+    ap.add_argument("--only", choices=["chunk", "scores", "bwd", "decode", "prefill_c1", "prefill_c2", "prefill_c3"],
                     help="run one of the side legs alone and print its object (for profiling that leg)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (to calibrate FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
@@ -331,7 +526,11 @@ def main():
         sys.exit("bench.py needs a GPU")
     spk.lib()  # fail loudly if the HIP library is missing
     if args.only:
-        leg = {"chunk": chunk_leg, "scores": scores_leg, "bwd": mask_bwd_leg, "decode": decode_leg}[args.only]
+        cpu = not args.no_cpu_baseline
+        leg = {"chunk": chunk_leg, "scores": scores_leg, "bwd": mask_bwd_leg,
+               "decode": lambda: decode_leg(with_cpu=cpu),
+               "prefill_c1": lambda: prefill_leg(1, with_cpu=cpu), "prefill_c2": lambda: prefill_leg(2, with_cpu=cpu),
+               "prefill_c3": lambda: prefill_leg(3, with_cpu=cpu)}[args.only]
         print(json.dumps({"only": args.only, "result": leg()}))
         return
     if args.copy_calibration:
@@ -360,20 +559,24 @@ def main():
         step()
     torch.cuda.synchronize()
 
-    # whole-step time: exactly K steps between synchronisations; the dominant kernel's own
-    # duration from HIP events recorded on the launch stream around each attention call
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    # whole-step time: exactly K steps between synchronisations; the durations of the mask and of the dominant
+    # kernel's launch from HIP events recorded on the launch stream around each call
+    ev = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
-        tau, death = spk.sparsek_mask(u, cfg["k"])
         ev[i][0].record()
+        tau, death = spk.sparsek_mask(u, cfg["k"])
+        ev[i][1].record()
         spk.sparsek_attn_fwd(q, k, v, u, tau, death, cfg["k"], cfg["w"], args.gate_mode, 1.0, return_lse=True,
                              ws=ws)
-        ev[i][1].record()
+        ev[i][2].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
-    attn_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
+    attn_stats = stats([b.elapsed_time(c) for a, b, c in ev])
+    mask_stats = stats([a.elapsed_time(b) for a, b, c in ev])
+    step_stats = stats([a.elapsed_time(c) for a, b, c in ev])
+    attn_ms = attn_stats["mean"]
 
     flops = 4.0 * cfg["d"] * attended_pairs(cfg["n"], cfg["k"], cfg["w"]) * cfg["B"] * cfg["H"]
     achieved = flops / (attn_ms * 1e-3) / 1e12
@@ -397,7 +600,8 @@ def main():
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
                      "ms_per_launch": attn_ms, "algorithmic_flops": flops,
                      "traffic": read_traffic("attn_fwd_mfma_config4_counters.txt")},
-        "mask_ms": ms_per_step - attn_ms,
+        "mask_ms": mask_stats["mean"],
+        "device_ms": {"step": step_stats, "mask": mask_stats, "attn": attn_stats},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, u)
@@ -449,6 +653,10 @@ def main():
     del u_heads
     del q, k, v, ws
     torch.cuda.empty_cache()
+    if not args.no_prefill_configs:
+        for c in (1, 2, 3):
+            out["prefill_c%d" % c] = prefill_leg(c, with_cpu=not args.no_cpu_baseline)
+            torch.cuda.empty_cache()
     if not args.no_bwd:
         out["mask_bwd"] = mask_bwd_leg()
         torch.cuda.empty_cache()
@@ -459,7 +667,7 @@ def main():
         out["chunked_prefill"] = chunk_leg()
         torch.cuda.empty_cache()
     if not args.no_decode:
-        out["decode"] = decode_leg()
+        out["decode"] = decode_leg(with_cpu=not args.no_cpu_baseline)
     print(json.dumps(out))
 
 

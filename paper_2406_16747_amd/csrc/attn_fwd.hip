@@ -154,8 +154,11 @@ __global__ __launch_bounds__(64 * BL_WAVES) void block_lists_kernel(const int32_
 // ---------------------------------------------------------------------------------
 // Generic vector-ALU kernel (fp32 or bf16 storage, any d <= 128 that is a multiple of 4).
 // One wave per query, lanes over keys for the logits and over columns for the output.
-// Used for fp32 tensors and head dims the MFMA kernel does not cover.
+// Used for fp32 tensors and head dims the MFMA kernel does not cover.  A query block of QB
+// queries (the granularity of the lists) is spread over GEN_SPLIT workgroups of four waves, one
+// query per wave, so that small problems still fill the chip.
 // ---------------------------------------------------------------------------------
+constexpr int GEN_SPLIT = QB / 4;
 template <typename T>
 __device__ __forceinline__ float ld(const T* p);
 template <>
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(
     int q_begin, const int32_t* __restrict__ first_valid, int q_rows)
 {
     __shared__ float qs[4][128];
-    const int blk = blockIdx.x, bh = blockIdx.y;
+    const int blk = blockIdx.x / GEN_SPLIT, sub = blockIdx.x % GEN_SPLIT, bh = blockIdx.y;
     const int b = bh / H, h = bh % H;
     const int row = b * Gu + (Gu == 1 ? 0 : h);
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
@@ -198,9 +201,9 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(
     // keys before first_valid[row] (padding of a chunked prefill) are attended by nobody
     const int c0 = max(max(0, i0 - w + 1), first_valid ? first_valid[row] : 0);
 
-    for (int qi = wv; qi < QB; qi += 4) {
-        const int i = i0 + qi;
-        if (i >= n) break;
+    {
+        const int i = i0 + 4 * sub + wv;
+        if (i >= n || i < q_begin) return;
         for (int c = lane; c < d; c += 64) qs[wv][c] = ld(qh + (size_t)i * d + c);
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
         const int Tp = i - w;
@@ -832,7 +835,7 @@ int launch_attn_fwd(const sparsek_cfg& c, const void* q, const void* k, const vo
         return launch_status();
     }
     launch_block_lists(c, death, lists, counts, st);
-    dim3 grid(nb, c.B * c.H);
+    dim3 grid(nb * GEN_SPLIT, c.B * c.H);
     if (c.dtype == SPARSEK_F32) {
         hipLaunchKernelGGL(attn_fwd_generic_kernel<float>, grid, dim3(256), 0, st, (const float*)q,
                            (const float*)k, (const float*)v, u, tau, death, lists, counts, (float*)o, lse, c.H,
