@@ -109,3 +109,38 @@ def test_argument_validation_needs_no_gpu():
     assert L.sparsek_bwd_workspace_bytes(ctypes.byref(cfg)) > L.sparsek_attn_bwd_workspace_bytes(ctypes.byref(cfg))
     assert L.sparsek_bwd(ctypes.byref(cfg), *([one] * 9), one, one, one, null, one, 1 << 30, null) == -1  # du null
     assert L.sparsek_bwd(ctypes.byref(cfg), *([one] * 9), one, one, one, one, one, 8, null) == -3
+
+
+def test_toolchain_record_and_m0_check():
+    """Three kernels set the M0 register from inline assembly (direct-to-LDS loads the compiler does not track), which
+    is sound only while the compiler keeps nothing of its own in M0 inside those kernels.  The build checks the
+    generated assembly for that and records the compiler; a compiler other than the validated one calls for a fresh
+    run of the GPU parity tests (then update VALIDATED_HIPCC in build.py)."""
+    import json
+
+    from paper_2406_16747_amd import build
+
+    if not os.path.exists(build.SIDECAR) or os.path.getmtime(build.SIDECAR) < os.path.getmtime(spk.lib_path()) - 60:
+        build.build()
+    rec = json.load(open(build.SIDECAR))
+    assert rec["m0_check"] == "ok"
+    loads = rec["untracked_direct_to_lds_loads"]
+    assert set(loads) == {"attn_fwd.hip", "mask_bwd.hip", "attn_bwd.hip"}, loads
+    assert rec["hipcc_version"][0].startswith(build.VALIDATED_HIPCC), (
+        "libsparsek was built with %r, its hand-written M0 handling was validated with %r: run the GPU parity tests "
+        "with this compiler and update VALIDATED_HIPCC" % (rec["hipcc_version"][0], build.VALIDATED_HIPCC))
+    # the checker itself: a kernel that mixes hand-written and compiler-managed M0 is refused
+    import tempfile
+
+    bad = "k1:\n;;#ASMSTART\ns_mov_b32 m0, s3\ns_nop 0\nglobal_load_lds_dwordx4 v1, s[2:3]\n;;#ASMEND\ns_mov_b32 m0, s9\n.Lfunc_end0:\n"
+    good = "k1:\n;;#ASMSTART\ns_mov_b32 m0, s3\ns_nop 0\nglobal_load_lds_dwordx4 v1, s[2:3]\n;;#ASMEND\n.Lfunc_end0:\nk2:\ns_mov_b32 m0, s9\n.Lfunc_end1:\n"
+    with tempfile.NamedTemporaryFile("w", suffix=".s", delete=False) as f:
+        f.write(bad)
+    try:
+        build.check_m0(f.name)
+        raise AssertionError("a mixed kernel was accepted")
+    except RuntimeError:
+        pass
+    open(f.name, "w").write(good)
+    assert build.check_m0(f.name) == {"k1": 1}
+    os.remove(f.name)
