@@ -25,7 +25,8 @@ constexpr int CHUNK = 128;        // prefixes per workgroup of the chunk kernel
 constexpr int NT_CHUNK = 1024;    // threads of the chunk kernel (16 waves, 8 prefixes each)
 constexpr int NW_CHUNK = NT_CHUNK / 64;
 constexpr int SUPER = 2048;       // spacing of the coarse lower bounds
-constexpr int CAP = 8192;         // candidate capacity in LDS (64-bit keys: 64 KB, fp64 prefix sums: 64 KB)
+constexpr int CAP = 8192;         // candidate capacity in LDS (64-bit keys: 64 KB, fp64 prefix sums: 64 KB);
+                                  // CAP_SMALL halves it so that two workgroups share a compute unit
 constexpr int NT_COARSE = 1024;
 constexpr int NPROBE = 15;
 constexpr int NPASS = 3;
@@ -821,8 +822,10 @@ __device__ void bitonic_sort_desc(unsigned long long* key, int N)
 // bucket holds more than BUCKET_MAX elements (many equal or clustered scores): the caller then
 // sorts by comparison.  The result depends on the keys only, not on the order of the atomics.
 constexpr int NB = 2048;
+constexpr int CAP_SMALL = 4096, NB_SMALL = 1024;   // the variant for k small enough that 4096 candidates suffice
 constexpr int BUCKET_MAX = 96;
 
+template <int NB>
 __device__ bool bucket_sort_desc(unsigned long long* key, unsigned long long* tmp, int m, float vmin, float vmax,
                                  int* bcount /* [NB] */, int* boff /* [NB + 1] */, int* flag, int* wsum /* [NW_CHUNK] */)
 {
@@ -915,11 +918,10 @@ __device__ void sorted_prefix_sums(const unsigned long long* key, double* pref, 
     __syncthreads();
 }
 
-__global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __restrict__ u,
-                                                               const float* __restrict__ lo_in,
-                                                               float* __restrict__ tau,
-                                                               int32_t* __restrict__ death, int n, int k,
-                                                               int nsuper, int* __restrict__ status, int t_begin)
+template <int CAP, int NB>
+__global__ __launch_bounds__(NT_CHUNK, CAP <= CAP_SMALL ? 8 : 4) void mask_chunk_kernel(
+    const float* __restrict__ u, const float* __restrict__ lo_in, float* __restrict__ tau,
+    int32_t* __restrict__ death, int n, int k, int nsuper, int* __restrict__ status, int t_begin)
 {
     __shared__ __align__(16) unsigned long long skey[CAP];
     __shared__ __align__(16) double pref[CAP + 1];
@@ -941,12 +943,15 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
     int32_t* dr = death + (size_t)row * n;
     const float lo = lo_in[(size_t)row * nsuper + t0 / SUPER];
 
-    // ---- compaction of {j < t0 : u_j > lo} as selection keys: each wave owns a contiguous slice,
-    // read in segments of 64*SLICE_REG scores held in registers (independent loads, one latency) ----
+    // ---- compaction of {j < t0 : u_j > lo} as selection keys, in one pass: each wave owns a contiguous slice, read
+    // in segments of 64*SLICE_REG scores held in registers (independent loads, one latency); a segment reserves
+    // its room in the list with one LDS atomic.  The order in which the segments land does not matter: the list
+    // is sorted next, and the keys are distinct. ----
     const int per = ((t0 + NW_CHUNK - 1) / NW_CHUNK + 63) / 64 * 64;
     const int sb = min(t0, wv * per), se = min(t0, sb + per);
     constexpr int SEGN = 64 * SLICE_REG;
-    int cnt = 0;
+    if (tid == 0) wcount[NW_CHUNK] = 0;
+    __syncthreads();
     float cmin = INFINITY, cmax = -INFINITY;  // range of the candidates
     for (int g0 = sb; g0 < se; g0 += SEGN) {
         float z[SLICE_REG];
@@ -955,23 +960,29 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
             const int i = g0 + r * 64 + lane;
             z[r] = (i < se) ? ur[i] : -INFINITY;
         }
+        int seg_cnt = 0;
 #pragma unroll
         for (int r = 0; r < SLICE_REG; r++) {
             const bool p = z[r] > lo;
-            cnt += __popcll(__ballot(p));
+            seg_cnt += __popcll(__ballot(p));
             cmin = p ? fminf(cmin, z[r]) : cmin;
             cmax = p ? fmaxf(cmax, z[r]) : cmax;
+        }
+        int off = 0;
+        if (lane == 0 && seg_cnt > 0) off = atomicAdd(&wcount[NW_CHUNK], seg_cnt);
+        off = __builtin_amdgcn_readfirstlane(off);
+#pragma unroll
+        for (int r = 0; r < SLICE_REG; r++) {
+            const bool p = z[r] > lo;
+            const unsigned long long ball = __ballot(p);
+            const int pos = off + __popcll(ball & ((1ull << lane) - 1ull));
+            if (p && pos < CAP) skey[pos] = sel_key(z[r], g0 + r * 64 + lane);   // beyond CAP: the slow path below
+            off += __popcll(ball);
         }
     }
     cmin = wave_min_f32(cmin);
     cmax = wave_max_f32(cmax);
-    if (lane == 0) { wcount[wv] = cnt; wmin[wv] = cmin; wmax[wv] = cmax; }
-    __syncthreads();
-    if (tid == 0) {
-        int run = 0;
-        for (int i = 0; i < NW_CHUNK; i++) { int x = wcount[i]; wcount[i] = run; run += x; }
-        wcount[NW_CHUNK] = run;
-    }
+    if (lane == 0) { wmin[wv] = cmin; wmax[wv] = cmax; }
     __syncthreads();
     const int m_old = wcount[NW_CHUNK];
     // the list must hold the whole top-k of every prefix of the chunk (it does when lo is a lower
@@ -980,29 +991,13 @@ __global__ __launch_bounds__(NT_CHUNK) void mask_chunk_kernel(const float* __res
     if (fits) {
         int npad = 2 * NT_CHUNK;
         while (npad < m_old) npad <<= 1;
-        int off = wcount[wv];
-        for (int g0 = sb; g0 < se; g0 += SEGN) {
-            float z[SLICE_REG];
-#pragma unroll
-            for (int r = 0; r < SLICE_REG; r++) {
-                const int i = g0 + r * 64 + lane;
-                z[r] = (i < se) ? ur[i] : -INFINITY;
-            }
-#pragma unroll
-            for (int r = 0; r < SLICE_REG; r++) {
-                const bool p = z[r] > lo;
-                const unsigned long long ball = __ballot(p);
-                if (p) skey[off + __popcll(ball & ((1ull << lane) - 1ull))] = sel_key(z[r], g0 + r * 64 + lane);
-                off += __popcll(ball);
-            }
-        }
         for (int i = m_old + tid; i < npad; i += NT_CHUNK) skey[i] = 0ull;  // below every real key
         __syncthreads();
         if (m_old > 0) {
             float vmin = INFINITY, vmax = -INFINITY;
             for (int i = 0; i < NW_CHUNK; i++) { vmin = fminf(vmin, wmin[i]); vmax = fmaxf(vmax, wmax[i]); }
             // pref[] is free until the prefix sums are taken: scratch of the distribution sort
-            if (!bucket_sort_desc(skey, (unsigned long long*)pref, m_old, vmin, vmax, bcount, boff, &bflag, wsum))
+            if (!bucket_sort_desc<NB>(skey, (unsigned long long*)pref, m_old, vmin, vmax, bcount, boff, &bflag, wsum))
                 bitonic_sort_desc(skey, npad);
             sorted_prefix_sums(skey, pref, npad, m_old, wtot);
         }
@@ -1073,8 +1068,14 @@ int launch_mask(const sparsek_cfg& c, const float* u, float* tau, int32_t* death
     if (c.k == 0) return launch_status();
     if (c.k < c.n) {
         const int nchunks = (c.n + CHUNK - 1) / CHUNK;
-        hipLaunchKernelGGL(mask_chunk_kernel, dim3(nchunks, rows), dim3(NT_CHUNK), 0, st, u, lo, tau, death,
-                           c.n, c.k, nsuper, status, t_begin);
+        // the candidates of a chunk number about 2.5 k for scores of unit variance (the support of the threshold);
+        // up to k = 1280 the half-size lists do, and two workgroups then fit a compute unit
+        if (c.k <= 1280)
+            hipLaunchKernelGGL((mask_chunk_kernel<CAP_SMALL, NB_SMALL>), dim3(nchunks, rows), dim3(NT_CHUNK), 0, st, u, lo,
+                               tau, death, c.n, c.k, nsuper, status, t_begin);
+        else
+            hipLaunchKernelGGL((mask_chunk_kernel<CAP, NB>), dim3(nchunks, rows), dim3(NT_CHUNK), 0, st, u, lo, tau,
+                               death, c.n, c.k, nsuper, status, t_begin);
     }
     return launch_status();
 }
