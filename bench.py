@@ -367,12 +367,12 @@ def mask_bwd_leg(iters=20, warm=3):
                      "roofline": {"bound": "mfma", "kernel": "attn_bwd_dkv_kernel<128> + attn_bwd_dq_kernel<128> + merge",
                                   "achieved": abwd_ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                   "frac": abwd_ach / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops": abwd_flops,
-                                  "traffic": None}},
+                                  "traffic": read_traffic("attn_bwd_config3_counters.txt")}},
         "straight_through": {"gate_mode": 3, "attn_fwd_ms": st_fwd_ms, "mask_bwd_ms": st_bwd_ms,
                              "mask_bwd_tflops": flops / (st_bwd_ms * 1e-3) / 1e12},
         "roofline": {"bound": "mfma", "kernel": "mask_bwd_mfma_kernel<128> + epilogue", "achieved": ach,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                     "algorithmic_flops": flops, "traffic": None},
+                     "algorithmic_flops": flops, "traffic": read_traffic("mask_bwd_config3_counters.txt")},
     }
 
 
@@ -463,7 +463,8 @@ def chunk_leg(n=131072, c=8192):
             "state_bytes": int(st.buf.numel()), "workspace_bytes": int(st.ws.numel()),
             "roofline": {"bound": "mfma", "kernel": "whole chunk step (mask + attn_fwd_mfma_kernel<128> + state upkeep)",
                          "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                         "frac": ach / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops": flops, "traffic": None}}
+                         "frac": ach / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops": flops,
+                         "traffic": read_traffic("chunked_prefill_counters.txt")}}
 
 
 def source_digest(files):
