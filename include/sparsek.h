@@ -85,8 +85,9 @@ int sparsek_mask_status(const sparsek_cfg *cfg, const void *ws, size_t ws_bytes,
  * kernels and results as sparsek_mask, but the scratch (one fp32 lower bound per 2048 positions of every score row,
  * and the status word) lives in a 64 KiB device array built into the library, which each GPU holds until the process
  * ends.  The call allocates and frees nothing.  The current device must be the one that owns u, tau and death.
- * Limit: sparsek_mask_workspace_bytes(cfg) = B*Gu*ceil(n/2048)*4 (rounded up to 256) + 256 must not exceed
- * SPARSEK_MASK_STATIC_MAX_BYTES, e.g. 32 rows of 1 M scores;
+ * Limit: sparsek_mask_workspace_bytes(cfg) -- B*Gu*ceil(n/2048)*4 bytes of lower bounds, one bit per 128 positions
+ * of every score row, each rounded up to 256 bytes, plus 256 -- must not exceed SPARSEK_MASK_STATIC_MAX_BYTES, e.g. 32
+ * rows of 512 K scores;
  * beyond it nothing is enqueued and SPARSEK_ERR_TOO_LARGE is returned.  All calls on one GPU share the array: calls
  * that may overlap (different streams, or threads) race and must be ordered by the caller.  The status word of this
  * variant is not readable. */

@@ -36,7 +36,9 @@ size_t mask_ws_bytes(const sparsek_cfg& c)
 {
     size_t rows = (size_t)c.B * c.Gu;
     size_t nsuper = ((size_t)c.n + SUPER - 1) / SUPER;
-    return align_up(rows * nsuper * sizeof(float), 256) + 256;
+    // lower bounds, the status word, one bit per 128-prefix chunk (chunks that the half-capacity kernel hands on)
+    size_t nchunks = ((size_t)c.n + CHUNK - 1) / CHUNK;
+    return align_up(rows * nsuper * sizeof(float), 256) + 256 + align_up((rows * nchunks + 31) / 32 * 4, 256);
 }
 
 // ---------------------------------------------------------------------------------
@@ -84,7 +86,8 @@ __global__ __launch_bounds__(NT_COARSE) void mask_coarse_kernel(const float* __r
                                                                  float* __restrict__ lo_out,
                                                                  float* __restrict__ tau,
                                                                  int32_t* __restrict__ death, int n,
-                                                                 int k, int nsuper, int* __restrict__ status)
+                                                                 int k, int nsuper, int* __restrict__ status,
+                                                                 unsigned* __restrict__ handed_on, int nwords)
 {
     __shared__ double red[NT_COARSE / 64][NPROBE + 1];
     __shared__ double ftot[NPROBE];
@@ -96,6 +99,8 @@ __global__ __launch_bounds__(NT_COARSE) void mask_coarse_kernel(const float* __r
     int32_t* dr = death + (size_t)row * n;
     // the call's status word starts at 0; the chunk kernel, which sets bits in it, runs after this one on the stream
     if (s == 0 && row == 0 && tid == 0) *status = 0;
+    for (int i = (row * gridDim.x + s) * NT_COARSE + tid; i < nwords; i += gridDim.x * gridDim.y * NT_COARSE)
+        handed_on[i] = 0u;
     if (k > 0)
         for (int i = s * SUPER + tid; i < min(n, (s + 1) * SUPER); i += NT_COARSE) dr[i] = n;
     const int L = s * SUPER;
@@ -921,7 +926,8 @@ __device__ void sorted_prefix_sums(const unsigned long long* key, double* pref, 
 template <int CAP, int NB>
 __global__ __launch_bounds__(NT_CHUNK, CAP <= CAP_SMALL ? 8 : 4) void mask_chunk_kernel(
     const float* __restrict__ u, const float* __restrict__ lo_in, float* __restrict__ tau,
-    int32_t* __restrict__ death, int n, int k, int nsuper, int* __restrict__ status, int t_begin)
+    int32_t* __restrict__ death, int n, int k, int nsuper, int* __restrict__ status, int t_begin,
+    unsigned* __restrict__ handed_on, int only_handed_on)
 {
     __shared__ __align__(16) unsigned long long skey[CAP];
     __shared__ __align__(16) double pref[CAP + 1];
@@ -938,6 +944,11 @@ __global__ __launch_bounds__(NT_CHUNK, CAP <= CAP_SMALL ? 8 : 4) void mask_chunk
     const int t0 = c * CHUNK, t1 = min(n, t0 + CHUNK);
     if (t1 <= k) return;  // no prefix here is longer than k: tau is written elsewhere, nothing dies
     if (t1 <= t_begin) return;  // the caller needs neither these thresholds nor the deaths that fall here
+    // Two launches share the chunks when there are many: the half-capacity kernel (two workgroups per compute unit)
+    // takes them all and hands on, through one bit each, those whose candidates do not fit its lists; the
+    // full-capacity kernel then runs those alone.
+    const int chunk_id = row * gridDim.x + c;
+    if (only_handed_on && !((handed_on[chunk_id >> 5] >> (chunk_id & 31)) & 1u)) return;
     const float* ur = u + (size_t)row * n;
     float* tr = tau + (size_t)row * n;
     int32_t* dr = death + (size_t)row * n;
@@ -1005,6 +1016,8 @@ __global__ __launch_bounds__(NT_CHUNK, CAP <= CAP_SMALL ? 8 : 4) void mask_chunk
         ListSorted L{skey, pref, m_old, t0, (lane < cn) ? ur[t0 + lane] : -INFINITY,
                      (lane + 64 < cn) ? ur[t0 + lane + 64] : -INFINITY};
         chunk_body_sorted(L, ur, tr, dr, t0, t1, k, lo, th, status);
+    } else if (CAP <= CAP_SMALL && !only_handed_on) {
+        if (tid == 0) atomicOr(&handed_on[chunk_id >> 5], 1u << (chunk_id & 31));
     } else {
         ListGlobal L{ur, t1};
         chunk_body(L, ur, tr, dr, t0, t1, k, -INFINITY, hist, &bc, th, status);
@@ -1061,21 +1074,27 @@ int launch_mask(const sparsek_cfg& c, const float* u, float* tau, int32_t* death
 {
     const int rows = c.B * c.Gu;
     const int nsuper = (c.n + SUPER - 1) / SUPER;
+    const int nchunks = (c.n + CHUNK - 1) / CHUNK;
+    const size_t lo_bytes = align_up((size_t)rows * nsuper * sizeof(float), 256);
     float* lo = (float*)ws;
-    int* status = (int*)((char*)ws + align_up((size_t)rows * nsuper * sizeof(float), 256));
+    int* status = (int*)((char*)ws + lo_bytes);
+    unsigned* handed_on = (unsigned*)((char*)ws + lo_bytes + 256);
+    const int nwords = (int)(((size_t)rows * nchunks + 31) / 32);
     hipLaunchKernelGGL(mask_coarse_kernel, dim3(c.k == 0 ? 1 : nsuper, rows), dim3(NT_COARSE), 0, st, u, lo, tau,
-                       death, c.n, c.k, nsuper, status);
+                       death, c.n, c.k, nsuper, status, handed_on, nwords);
     if (c.k == 0) return launch_status();
     if (c.k < c.n) {
-        const int nchunks = (c.n + CHUNK - 1) / CHUNK;
-        // the candidates of a chunk number about 2.5 k for scores of unit variance (the support of the threshold);
-        // up to k = 1280 the half-size lists do, and two workgroups then fit a compute unit
-        if (c.k <= 1280)
+        // The candidates of a chunk number about 2.5 k for scores of unit variance (the support of the threshold), so
+        // up to k = 1280 the half-size lists usually do, and two workgroups then fit a compute unit: worth it when
+        // the chunks outnumber the compute units several times (many score rows).  Chunks whose candidates do not
+        // fit are handed on to the full-capacity kernel.  Not for the virtual sequences of the chunked prefill
+        // (t_begin > 0), whose padding scores all count as candidates at first.
+        const bool two_stage = c.k <= 1280 && t_begin == 0 && (long long)rows * nchunks >= 2048;
+        if (two_stage)
             hipLaunchKernelGGL((mask_chunk_kernel<CAP_SMALL, NB_SMALL>), dim3(nchunks, rows), dim3(NT_CHUNK), 0, st, u, lo,
-                               tau, death, c.n, c.k, nsuper, status, t_begin);
-        else
-            hipLaunchKernelGGL((mask_chunk_kernel<CAP, NB>), dim3(nchunks, rows), dim3(NT_CHUNK), 0, st, u, lo, tau,
-                               death, c.n, c.k, nsuper, status, t_begin);
+                               tau, death, c.n, c.k, nsuper, status, t_begin, handed_on, 0);
+        hipLaunchKernelGGL((mask_chunk_kernel<CAP, NB>), dim3(nchunks, rows), dim3(NT_CHUNK), 0, st, u, lo, tau,
+                           death, c.n, c.k, nsuper, status, t_begin, handed_on, two_stage ? 1 : 0);
     }
     return launch_status();
 }

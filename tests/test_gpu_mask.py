@@ -105,3 +105,29 @@ def test_mask_is_deterministic(oracle):
     a = spk.sparsek_mask(u, 200)
     b = spk.sparsek_mask(u, 200)
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_many_rows_take_the_two_stage_path_and_hand_on_what_does_not_fit(oracle):
+    """With many score rows the chunks first go to the half-capacity kernel, which hands the chunks whose candidates
+    do not fit its lists on to the full-capacity kernel: rows of unit-variance scores stay in the first stage, rows of
+    narrow scores (nearly every score in the support of the threshold) are handed on.  Both kinds must match the
+    oracle, and the call must clear the hand-on bits itself (the workspace starts as garbage)."""
+    require_gpu()
+    rng = np.random.default_rng(11)
+    rows, n, k = 20, 16384, 300   # 20 x 128 chunks >= 2048
+    u = rng.standard_normal((rows, n)).astype(np.float32)
+    u[3] *= 0.02
+    u[17] = (np.round(u[17] * 2) / 2).astype(np.float32) * 0.1   # narrow and full of ties
+    ud = dev(u.reshape(1, rows, n))
+    ws = spk.sparsek_mask_workspace(ud, k)
+    for fill in (0xFF, 0x00):
+        ws.fill_(fill)
+        tau_g, death_g = spk.sparsek_mask(ud, k, ws=ws)
+        assert spk.sparsek_mask_status(ud, k, ws) == 0
+        tau_g, death_g = host(tau_g).reshape(rows, n), host(death_g).reshape(rows, n)
+        for r in (0, 3, 17):
+            say("  two-stage mask, row", r)
+            tau_r = oracle.tau_incremental(u[r], k)   # pinned against the sort-based routine in the CPU tests
+            np.testing.assert_array_equal(death_g[r], oracle.death(u[r], k))
+            err = np.abs(tau_g[r].astype(np.float64) - tau_r) / np.maximum(1.0, np.abs(tau_r))
+            assert err.max() <= 1e-5, (r, err.max())
