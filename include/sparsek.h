@@ -83,7 +83,7 @@ int sparsek_mask_status(const sparsek_cfg *cfg, const void *ws, size_t ws_bytes,
 /* ---- stages 1+2 without a workspace, for callers that cannot allocate ----
  * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc: same inputs, outputs,
  * kernels and results as sparsek_mask, but the scratch (one fp32 lower bound per 2048 positions of every score row,
- * and the status word) lives in a 64 KiB device array built into the library, which each GPU holds until the process
+ * the status word and one bit per 128 positions) lives in a 64 KiB device array built into the library, which each GPU holds until the process
  * ends.  The call allocates and frees nothing.  The current device must be the one that owns u, tau and death.
  * Limit: sparsek_mask_workspace_bytes(cfg) -- B*Gu*ceil(n/2048)*4 bytes of lower bounds, one bit per 128 positions
  * of every score row, each rounded up to 256 bytes, plus 256 -- must not exceed SPARSEK_MASK_STATIC_MAX_BYTES, e.g. 32
