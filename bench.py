@@ -53,6 +53,23 @@ def timed(fn, iters=20, warm=3):
     return [a.elapsed_time(b) for a, b in ev]
 
 
+def graph_timed(fn, iters=20, warm=3):
+    """fn captured once as a HIP graph (the entry points are plain launches on the caller's stream) and replayed:
+    per-replay device times (ms).  For the launch-bound legs this is what a serving loop would see."""
+    import torch
+
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        fn()
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        fn()
+    return timed(g.replay, iters, warm)
+
+
 def attended_pairs(n, k, w):
     """Number of (query, key) pairs one head attends: window part + selected part."""
     win = n * w - w * (w - 1) // 2 if n >= w else n * (n + 1) // 2
@@ -153,6 +170,7 @@ def prefill_leg(config, iters=20, warm=3, with_cpu=True):
         spk.sparsek_attn_fwd(q, kk, v, u, t, dth, k, w, 0, 1.0)
 
     step_ms = stats(timed(step, iters, warm))
+    graph_ms = stats(graph_timed(step, iters, warm))
     pairs = attended_pairs(n, k, w) * B * H
     flops = 4.0 * d * pairs
     nbytes = 4.0 * B * H * n * d * (2 if bf16 else 4) + B * H * n * 4 + 3.0 * B * Gu * n * 4
@@ -176,6 +194,7 @@ def prefill_leg(config, iters=20, warm=3, with_cpu=True):
         "workload": "config %d: prefill fwd, B=%d H=%d n=%d d=%d k=%d w=%d %s, Gu=%d, gate_mode=0, mask+select+attention "
                     "per step" % (config, B, H, n, d, k, w, inp["dtype"], Gu),
         "ms_per_step": step_ms, "mask_ms": mask_ms, "attn_ms": attn_ms,
+        "ms_per_step_as_hip_graph": graph_ms,
         "tokens_per_s": B * n / (step_ms["mean"] * 1e-3), "us_per_step": step_ms["mean"] * 1e3,
         "roofline": roof,
     }

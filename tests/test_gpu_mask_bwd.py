@@ -91,3 +91,27 @@ def test_straight_through_forward_is_the_ungated_forward_and_has_a_gradient(orac
     o0, lse0 = spk.sparsek_attn_fwd(Q, K, V, u, tau, death, k, w, 0, 1.0)
     du0 = host(spk.sparsek_mask_bwd(Q, K, V, u, tau, death, o0, lse0, dO, k, w, 0, 1.0))
     assert np.abs(du3 - du0).max() > 1e-2 * scale3
+
+
+def test_two_runs_agree_du_at_rounding_level_the_other_gradients_bitwise():
+    """du adds the heads of a score group and the query blocks with fp32 atomics, so its bits depend on the order
+    in which workgroups arrive: two runs may differ at rounding level (1e-5 of the gradient's scale allowed).  dq,
+    dk and dv use no atomics and must be bitwise equal."""
+    require_gpu()
+    say("backward run twice")
+    inp = synth.make(3, with_dO=True, B=2, H=4, n=2048, k=128, w=128, seed=21)
+    k, w = inp["k"], inp["w"]
+    u = dev(inp["u"])
+    Q, K, V, dO = (dev(inp[x], True) for x in ("Q", "K", "V", "dO"))
+    tau, death = spk.sparsek_mask(u, k)
+    o, lse = spk.sparsek_attn_fwd(Q, K, V, u, tau, death, k, w, 0, 1.0)
+    du_a = spk.sparsek_mask_bwd(Q, K, V, u, tau, death, o, lse, dO, k, w, 0, 1.0).clone()
+    g_a = [t.clone() for t in spk.sparsek_attn_bwd(Q, K, V, u, tau, death, o, lse, dO, k, w, 0, 1.0)]
+    du_b = spk.sparsek_mask_bwd(Q, K, V, u, tau, death, o, lse, dO, k, w, 0, 1.0)
+    g_b = spk.sparsek_attn_bwd(Q, K, V, u, tau, death, o, lse, dO, k, w, 0, 1.0)
+    torch.cuda.synchronize()
+    scale = float(du_a.abs().max())
+    assert scale > 0
+    assert float((du_a - du_b).abs().max()) <= 1e-5 * scale
+    for a, b in zip(g_a, g_b):
+        assert torch.equal(a, b)
