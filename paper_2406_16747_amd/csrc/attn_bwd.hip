@@ -552,13 +552,27 @@ __global__ __launch_bounds__(1024) void abwd_elist_kernel(const int32_t* __restr
     }
 }
 
+// One Q and one dO tile (64 rows) serve two kinds of LDS reads: 16-byte row reads (A operand of S and dO.V) and
+// transposing 8-byte reads (A operand of dV and dK).  Each row lands once, unpadded, with its 16-byte chunks
+// permuted: chunk c of tile row R sits at chunk position c ^ swz(R).  swz is chosen so that both read patterns
+// touch every bank once per pass:
+//   row reads take one chunk column of 16 consecutive rows per 16 lanes  -> swz must differ on those rows
+//   transposing reads take 4 neighbouring chunks of 4 consecutive rows per 32 lanes -> swz / 4 must differ on those rows
+// (head dim 64: a row is half of the 64 banks, two rows share a pass, and the row's parity takes the place of one bit).
+template <int D>
+__device__ __forceinline__ int dkv_swz(int R)
+{
+    if constexpr (D == 128) return 4 * (R & 3) + ((R >> 2) & 3);
+    else return 4 * ((R >> 1) & 1) + ((R >> 2) & 3);
+}
+
+constexpr int DKV_NBUF = 2;  // tiles in LDS: one in use, one being filled
 template <int D>
 struct DkvSmem {
-    using S = MfmaSmem<D, 64>;
-    unsigned char qr[2][S::NL * S::GSK];   // Q rows of the tile, padded for row reads
-    unsigned char qt[2][S::NL * S::GSV];   // ... for transposing reads
-    unsigned char gr[2][S::NL * S::GSK];   // dO rows, row reads
-    unsigned char gt[2][S::NL * S::GSV];   // dO rows, transposing reads
+    struct Tile {
+        unsigned char q[KT * D * 2];   // Q rows of a tile
+        unsigned char g[KT * D * 2];   // dO rows
+    } t[DKV_NBUF];
     int red[2][4];
 };
 
@@ -572,11 +586,11 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int H, int Gu, int n, int w, float scale, int nb,
     int q_begin, int q_rows)
 {
-    using S = MfmaSmem<D, 64>;
+    using S = MfmaTileBufs<D, 64>;  // (tile geometry only)
     __shared__ __align__(16) DkvSmem<D> sm;
     // per query of a tile: lse * log2(e), D_i, tau_{i-w} (and a fourth row that only keeps the loads branch-free)
-    __shared__ __align__(16) float meta[2][4][KT];
-    constexpr int DS = D / 16, DB = D / 32, NX = S::NL / 4, LPR = S::RB / 16;
+    __shared__ __align__(16) float meta[DKV_NBUF][4][KT];
+    constexpr int DS = D / 16, DB = D / 32, NX = S::NL / 4, LPR = S::RB / 16, RB = S::RB, RPL = S::RPL;
     const int bh = blockIdx.x;
     const int b = bh / H, h = bh % H;
     const int row = b * Gu + (Gu == 1 ? 0 : h);
@@ -641,30 +655,50 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     const unsigned char* qh = (const unsigned char*)(q + qo * D);
     const unsigned char* gh = (const unsigned char*)(dO + qo * D);
 
+    // LDS byte offsets of this lane's operand reads (see dkv_swz):
+    //   row reads: tile row 32 * run + col, chunk 2 * step + half          -> roff[run][step]
+    //   transposing reads: rows 16 g + 4 half + r16 / 4 (+ 8), chunk 4 x + 2 grp2 + (r16 % 4) / 2, 8-byte half r16 % 2
+    //                                                                      -> toff[0 / 1][x] + 16 g rows
     const int r16 = lane & 15, grp2 = (lane >> 4) & 1;
-    const int tcol = (16 * grp2 + 4 * (r16 & 3)) * 2;
-    const int trow = 4 * half + (r16 >> 2);
+    int roff[2][DS], toff[2][DB];
+#pragma unroll
+    for (int run = 0; run < 2; run++) {
+        const int R = 32 * run + col, sw = dkv_swz<D>(R);
+#pragma unroll
+        for (int st = 0; st < DS; st++) roff[run][st] = R * RB + (((2 * st + half) ^ sw) << 4);
+    }
+#pragma unroll
+    for (int hl = 0; hl < 2; hl++) {
+        const int R = 4 * half + (r16 >> 2) + 8 * hl, sw = dkv_swz<D>(R);  // (swz has period 16 in R)
+#pragma unroll
+        for (int x = 0; x < DB; x++)
+            toff[hl][x] = R * RB + (((4 * x + 2 * grp2 + ((r16 & 3) >> 1)) ^ sw) << 4) + 8 * (r16 & 1);
+    }
     auto t_operand = [&](const unsigned char* tbuf, int g, int x) -> bf16x8 {
-        const int row0 = 16 * g + trow, row1 = row0 + 8;
-        const unsigned char* p0 = tbuf + (row0 % S::NL) * S::GSV + (row0 / S::NL) * S::RB + tcol + 64 * x;
-        const unsigned char* p1 = tbuf + (row1 % S::NL) * S::GSV + (row1 / S::NL) * S::RB + tcol + 64 * x;
+        const unsigned char* p0 = tbuf + 16 * g * RB + toff[0][x];
+        const unsigned char* p1 = tbuf + 16 * g * RB + toff[1][x];
         const i16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)p0);
         const i16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)p1);
         const bf16x4 l4 = __builtin_bit_cast(bf16x4, lo4), h4 = __builtin_bit_cast(bf16x4, hi4);
         return __builtin_shufflevector(l4, h4, 0, 1, 2, 3, 4, 5, 6, 7);
     };
-    // the gather of one tile (64 consecutive queries from i_first, clamped to the last row)
+    // The gather of one tile (64 consecutive queries from i_first, clamped to the last row): a wave-load fills RPL
+    // consecutive tile rows; lane l delivers position l % LPR of row l / LPR, i.e. chunk (l % LPR) ^ swz(row).
+    int goff[NX];  // byte offset of this lane's chunk inside a tile whose first row is at 0
+#pragma unroll
+    for (int x = 0; x < NX; x++) {
+        const int R = RPL * (wv * NX + x) + lane / LPR;
+        goff[x] = R * RB + (((lane % LPR) ^ dkv_swz<D>(R)) << 4);
+    }
     auto issue = [&](int buf, int i_first) {
-        const int c = lane % LPR;
 #pragma unroll
         for (int x = 0; x < NX; x++) {
-            const int L = wv * NX + x;
-            const int rr = min(i_first + L + S::NL * (lane / LPR), n - 1);  // tile row L + NL * jrow
-            const uint32_t off = (uint32_t)rr * (uint32_t)S::RB + 16u * (uint32_t)c;
-            async_load_lds16(qh, off, &sm.qr[buf][L * S::GSK]);
-            async_load_lds16(qh, off, &sm.qt[buf][L * S::GSV]);
-            async_load_lds16(gh, off, &sm.gr[buf][L * S::GSK]);
-            async_load_lds16(gh, off, &sm.gt[buf][L * S::GSV]);
+            const int R = RPL * (wv * NX + x) + lane / LPR;
+            // rows past the end of the sequence repeat the last row (their pairs are masked)
+            const int over = max(i_first + R - (n - 1), 0);
+            const uint32_t off = (uint32_t)i_first * (uint32_t)RB + (uint32_t)(goff[x] - over * RB);
+            async_load_lds16(qh, off, &sm.t[buf].q[(wv * NX + x) * 1024]);
+            async_load_lds16(gh, off, &sm.t[buf].g[(wv * NX + x) * 1024]);
         }
     };
     // the tile's per-query values: waves 0, 1, 2 load one row each (wave 3 a copy of tau into the spare row)
@@ -692,24 +726,24 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     constexpr int NS = 2 * DS, EPM = 16 / NS, DEPTH = 4;
     static_assert(NS == 4 * DB && EPM * NS == 16, "stage lengths");
     const unsigned char* mbase = (const unsigned char*)&meta[0][0][0];
-    auto tile = [&](auto gated_c, auto check_c, int buf, int i_first) {
+    // (the buffer number is a compile-time constant, so that every LDS address is a per-lane register plus an immediate)
+    auto tile = [&](auto gated_c, auto check_c, auto buf_c, int i_first) {
         constexpr bool GATED = decltype(gated_c)::value, CHECK = decltype(check_c)::value;
+        constexpr int buf = decltype(buf_c)::value;
         constexpr bool GK = GATED && MODE == 0, GV = GATED && MODE != 2;
         const f32x16 zero = {0};
         f32x16 s0 = zero, d0 = zero, s1 = zero, d1 = zero;
         u32x4 pb0[2], dsb0[2], pb1[2], dsb1[2];
-        const int off0 = (col % S::NL) * S::GSK + (col / S::NL) * S::RB + 16 * half;
-        const int off1 = ((32 + col) % S::NL) * S::GSK + ((32 + col) / S::NL) * S::RB + 16 * half;
         const int rel0 = i_first + 4 * half - lo_eff;
         // operand idx of the tile's 4 * NS MFMAs, in issue order
         auto operand = [&](auto ic) -> bf16x8 {
             constexpr int idx = decltype(ic)::value, run = idx / NS, m = idx % NS;
             if constexpr (run < 2) {
-                const unsigned char* base = (m & 1) ? sm.gr[buf] : sm.qr[buf];
-                return *(const bf16x8*)(base + (run ? off1 : off0) + 32 * (m / 2));
+                const unsigned char* base = (m & 1) ? sm.t[buf].g : sm.t[buf].q;
+                return *(const bf16x8*)(base + roff[run][m / 2]);
             } else {
                 constexpr int qb = run - 2, i2 = m / 2, g = 2 * qb + i2 / DB, x = i2 % DB;
-                return t_operand((m & 1) ? sm.qt[buf] : sm.gt[buf], g, x);
+                return t_operand((m & 1) ? sm.t[buf].q : sm.t[buf].g, g, x);
             }
         };
         bf16x8 ring[DEPTH];
@@ -790,9 +824,8 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
             __builtin_amdgcn_sched_barrier(0);
         });
     };
-    auto tiles = [&](auto gated_c) {
-    for (int t = 0; t < ntiles; t++) {
-        const int buf = t & 1;
+    auto step = [&](auto gated_c, auto buf_c, int t) {
+        constexpr int buf = decltype(buf_c)::value;
         const int i_first = blo + t * KT;
         // the dK / dV accumulators stay in the accumulation registers: only MFMAs touch them until the end
 #pragma unroll
@@ -805,10 +838,15 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
         }
         if (i_first <= whi && i_first + KT - 1 >= wlo) {  // some key of this wave is attended from this tile
             const bool full = i_first >= wfull_lo && i_first + KT - 1 <= wfull_hi;
-            if (full) tile(gated_c, std::false_type{}, buf, i_first);
-            else tile(gated_c, std::true_type{}, buf, i_first);
+            if (full) tile(gated_c, std::false_type{}, buf_c, i_first);
+            else tile(gated_c, std::true_type{}, buf_c, i_first);
         }
-    }
+    };
+    auto tiles = [&](auto gated_c) {
+        for (int t = 0; t < ntiles; t += 2) {
+            step(gated_c, std::integral_constant<int, 0>{}, t);
+            if (t + 1 < ntiles) step(gated_c, std::integral_constant<int, 1>{}, t + 1);
+        }
     };
     if (selected_kind && MODE != 2) tiles(std::true_type{});
     else tiles(std::false_type{});
