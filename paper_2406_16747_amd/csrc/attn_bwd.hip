@@ -16,7 +16,7 @@ void launch_block_lists(const sparsek_cfg& c, const int32_t* death, int32_t* lis
 size_t block_lists_bytes(const sparsek_cfg& c, size_t* counts_offset);
 
 struct AbwdWs {
-    size_t lists, counts, delta, lse2, elist, ecount, eslot, dk32, dv32, sk32, sv32, total;
+    size_t lists, counts, xpos, xdeath, xu, delta, lse2, elist, ecount, eslot, dk32, dv32, sk32, sv32, total;
 };
 static AbwdWs abwd_ws(const sparsek_cfg& c)
 {
@@ -27,6 +27,9 @@ static AbwdWs abwd_ws(const sparsek_cfg& c)
     W.lists = 0;
     W.counts = coff;
     size_t off = align_up(lb, 256);
+    W.xpos = off; off += ext_array_bytes(c);
+    W.xdeath = off; off += ext_array_bytes(c);
+    W.xu = off; off += ext_array_bytes(c);
     W.delta = off; off += align_up(BH * c.n * 4, 256);
     W.lse2 = off; off += align_up(BH * c.n * 4, 256);
     W.elist = off; off += align_up((size_t)c.B * c.Gu * c.n * 4, 256);
@@ -207,13 +210,13 @@ __global__ __launch_bounds__(256) void attn_bwd_generic_kernel(
 }
 
 // ---------------------------------------------------------------------------------
-// MFMA kernel for dQ (bf16, D = 64 or 128).  Same blocking as the forward: 128 queries x 4 waves,
-// 64-key tiles (the block's top-k list, then the contiguous keys up to the block's last query)
-// gathered straight into LDS.  Per 32-key half: S^T = K.Q^T and DV^T = V.dO^T (row reads), the
-// elementwise step to ds_ij scale gk_ij in bf16, then dQ^T += K^T.dS^T with K^T read through
-// transposing LDS loads.  Row reads and transposing reads want different paddings of the tile, so K
-// lands in LDS twice (a second direct-to-LDS load of rows that are in cache by then); the tile is
-// single-buffered and the two workgroups of a CU cover each other's gathers.
+// MFMA kernel for dQ (bf16, D = 64 or 128).  Same blocking and the same walk over a query block's key set as the
+// forward (attn_fwd.hip): 128 queries x 4 waves, 64-key tiles (the block's top-k list, then the contiguous keys up
+// to the block's last query) in runs of one kind per wave, so that only the tiles that need a test or a gate pay
+// for it; metadata staged in segments, tiles gathered straight into LDS one tile ahead.  Per 32-key half:
+// S^T = K.Q^T and DV^T = V.dO^T (row reads of the K and V tiles), the elementwise step to ds_ij gk_ij in bf16, then
+// dQ^T += K^T.dS^T with K^T through transposing reads of the same K tile (see tile_swz).  The softmax scale is
+// applied once, to the finished dQ.
 // ---------------------------------------------------------------------------------
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2v __attribute__((ext_vector_type(2)));
@@ -225,28 +228,173 @@ __device__ __forceinline__ unsigned pack_bf16x2(float a, float b)
     return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2v));
 }
 
+// A 64-row tile in LDS (K rows in the dQ kernel, Q and dO rows in the dK/dV kernel) serves two kinds of reads: 16-byte
+// row reads (A operand of the contractions over the head dimension) and transposing 8-byte reads (A operand of the
+// contractions over the tile's rows).  Each row lands once, unpadded, with its 16-byte chunks
+// permuted: chunk c of tile row R sits at chunk position c ^ swz(R).  swz is chosen so that both read patterns
+// touch every bank once per pass:
+//   row reads take one chunk column of 16 consecutive rows per 16 lanes  -> swz must differ on those rows
+//   transposing reads take 4 neighbouring chunks of 4 consecutive rows per 32 lanes -> swz / 4 must differ on those rows
+// (head dim 64: a row is half of the 64 banks, two rows share a pass, and the row's parity takes the place of one bit).
 template <int D>
-struct DqSmem {
-    using S = MfmaSmem<D, 64>;
+__device__ __forceinline__ int tile_swz(int R)
+{
+    if constexpr (D == 128) return 4 * (R & 3) + ((R >> 2) & 3);
+    else return 4 * ((R >> 1) & 1) + ((R >> 2) & 3);
+}
+
+// K lands twice, once per padding (row reads and transposing reads of one padded copy would conflict; the
+// chunk-permuted single copy the dK/dV kernel uses needs 16 more address registers than this kernel has at two
+// workgroups per compute unit); the tile is single-buffered and the two workgroups of a compute unit cover each
+// other's gathers.
+template <int D>
+struct DqSmem : TileMeta {
+    using S = MfmaTileBufs<D, 64>;
     unsigned char kr[S::NL * S::GSK];  // K rows, padded for row reads
     unsigned char kt[S::NL * S::GSV];  // K rows, padded for transposing reads
     unsigned char vr[S::NL * S::GSK];  // V rows, padded for row reads
-    int32_t jpos[SEG];
-    int32_t jlast[SEG];  // last query that attends the key: w - 1 + death[j]; -1 = filler
-    float ju[SEG];
 };
+static_assert(sizeof(DqSmem<128>) <= 80 * 1024, "two workgroups per CU");
+
+// What a lane of the dQ kernel keeps for the whole block.
+struct DqLane {
+    float tau_q, lse2, Di; // threshold of the query's prefix, lse * log2(e), dO.o
+    int qi;
+};
+
+// The gather of one tile: K (twice) and V rows at the positions jp[0..63].
+template <int D>
+__device__ __forceinline__ void dq_issue(DqSmem<D>& sm, const int32_t* jp, const unsigned char* kh,
+                                         const unsigned char* vh, int wv, int lane)
+{
+    using S = MfmaTileBufs<D, 64>;
+    constexpr int NX = S::NL / 4, LPR = S::RB / 16;
+    const TileRows<D, 64> rows = tile_rows<D, 64>(jp, wv, lane);
+    const int c = lane % LPR;
+#pragma unroll
+    for (int x = 0; x < NX; x++) {
+        const int L = wv * NX + x;
+        const uint32_t off = (uint32_t)rows.j[x] * (uint32_t)S::RB + 16u * (uint32_t)c;
+        async_load_lds16(kh, off, &sm.kr[L * S::GSK]);
+        async_load_lds16(vh, off, &sm.vr[L * S::GSK]);
+        async_load_lds16(kh, off, &sm.kt[L * S::GSV]);
+    }
+}
+
+// One 64-key tile for one wave.  jbase: position of the tile's first key if the key set were contiguous.
+template <int D, int MODE, int KIND>
+__device__ __forceinline__ void dq_tile_body(DqSmem<D>& sm, const int32_t* jdeath, const float* ju, int jbase,
+                                             const DqLane& ln, int lane, int w, float c2,
+                                             const bf16x8 (&qreg)[D / 16], const bf16x8 (&dreg)[D / 16],
+                                             f32x16 (&acc_q)[D / 32])
+{
+    using TT = TileTraits<MODE, KIND>;
+    using S = MfmaTileBufs<D, 64>;
+    constexpr int DS = D / 16, DB = D / 32;
+    const int half = lane >> 5, col = lane & 31;
+    const int qw = ln.qi - (w - 1);
+    const int dqh = ln.qi - jbase - 4 * half;  // contiguous tiles: key number cst + 4*half sits dqh - cst behind the query
+    const int dqw = dqh - w;                   // in the window  <=>  cst > dqw
+    // transposing reads of K^T (see the forward's V^T operand): lane -> (row, column block)
+    const int r16 = lane & 15, grp2 = (lane >> 4) & 1;
+    const int tcol = (16 * grp2 + 4 * (r16 & 3)) * 2;
+    const int trow = 4 * half + (r16 >> 2);
+    auto kt_operand = [&](int g, int x) -> bf16x8 {
+        const int row0 = 16 * g + trow, row1 = row0 + 8;
+        const unsigned char* p0 = sm.kt + (row0 % S::NL) * S::GSV + (row0 / S::NL) * S::RB + tcol + 64 * x;
+        const unsigned char* p1 = sm.kt + (row1 % S::NL) * S::GSV + (row1 / S::NL) * S::RB + tcol + 64 * x;
+        const i16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)p0);
+        const i16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)p1);
+        const bf16x4 lo = __builtin_bit_cast(bf16x4, lo4), hi = __builtin_bit_cast(bf16x4, hi4);
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+#pragma unroll
+    for (int mb = 0; mb < 2; mb++) {
+        const int trw = 32 * mb + col;
+        const int off = (trw % S::NL) * S::GSK + (trw / S::NL) * S::RB + 16 * half;
+        const f32x16 zero = {0};
+        f32x16 acc_s = zero, acc_d = zero;
+        __builtin_amdgcn_sched_barrier(0);  // one half at a time: there are no registers for two in flight
+#pragma unroll
+        for (int s = 0; s < DS; s++) {
+            const bf16x8 ka = *(const bf16x8*)(sm.kr + off + 32 * s);
+            const bf16x8 va = *(const bf16x8*)(sm.vr + off + 32 * s);
+            acc_s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], s == 0 ? zero : acc_s, 0, 0, 0);
+            acc_d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dreg[s], s == 0 ? zero : acc_d, 0, 0, 0);
+        }
+        // ds_ij gk_ij without the softmax scale; a pair that is not attended gets p = 0 through the exponent
+        u32x4 dsb[2];
+        float hold = 0.0f;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; g4++) {
+            const int kb = 32 * mb + 8 * g4 + 4 * half;
+            float4 U4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            int4 L4 = make_int4(0, 0, 0, 0);
+            if (TT::GATED) U4 = *(const float4*)&ju[kb];
+            if (TT::MASKL) L4 = *(const int4*)&jdeath[kb];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                const int r = 4 * g4 + e;
+                const int cst = 32 * mb + 8 * g4 + e;  // key number in the tile minus the lane's 4 * half (folded into dqh, dqw)
+                const int Lj = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
+                const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
+                const float qk = acc_s[r], dov = acc_d[r];
+                float gate = 1.0f;
+                if (TT::GATED) {
+                    gate = clip01(uj - ln.tau_q);
+                    if (TT::SELECT) gate = (cst > dqw) ? 1.0f : gate;
+                }
+                float arg = TT::KGATE ? fmaf(qk, gate * c2, -ln.lse2) : fmaf(qk, c2, -ln.lse2);
+                // key j is attended by query i while j <= i and i - (w - 1) <= death[j]
+                if (TT::MASKL && TT::MASKC) arg = (cst <= dqh && qw <= Lj) ? arg : -INFINITY;
+                else if (TT::MASKL) arg = (qw <= Lj) ? arg : -INFINITY;
+                else if (TT::MASKC) arg = (cst <= dqh) ? arg : -INFINITY;
+                const float p = __builtin_amdgcn_exp2f(arg);
+                float ds = p * (TT::GATED ? fmaf(gate, dov, -ln.Di) : dov - ln.Di);
+                if (TT::KGATE) ds *= gate;
+                if ((r & 1) == 0) hold = ds;
+                else dsb[r >> 3][(r & 7) >> 1] = pack_bf16x2(hold, ds);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 2 * DB; i++)
+            acc_q[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt_operand(2 * mb + i / DB, i % DB),
+                                                                    __builtin_bit_cast(bf16x8, dsb[i / DB]),
+                                                                    acc_q[i % DB], 0, 0, 0);
+    }
+}
+
+// The tiles [T, T_end) of the block's key set, all of one kind; the metadata of tile T sits in segment T / TPS.
+template <int D, int MODE, int KIND>
+__device__ __forceinline__ void dq_run_tiles(DqSmem<D>& sm, const StageSrc& src, int& T, int T_end, int jbase0,
+                                             const unsigned char* kh, const unsigned char* vh, int wv, int lane,
+                                             const DqLane& ln, int w, float c2, const bf16x8 (&qreg)[D / 16],
+                                             const bf16x8 (&dreg)[D / 16], f32x16 (&acc_q)[D / 32])
+{
+    for (; T < T_end; T++) {
+        const int sg = T / TPS, lt = T - sg * TPS;
+        __syncthreads();  // everybody is done with tile T-1 (and, at the first tile of a segment, with the segment before)
+        if (lt == 0 && (sg + 1) * TPS < src.nt) stage_meta(sm, src, sg + 1, wv, lane);
+        dq_issue<D>(sm, sm.jpos[sg & 1] + lt * KT, kh, vh, wv, lane);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();  // the tile (and any metadata staged above) has landed
+        if (KIND != TILE_SKIP)
+            dq_tile_body<D, MODE, KIND>(sm, sm.jdeath[sg & 1] + lt * KT, sm.ju[sg & 1] + lt * KT, jbase0 + T * KT, ln,
+                                        lane, w, c2, qreg, dreg, acc_q);
+    }
+}
 
 template <int D, int MODE>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ kk, const uint16_t* __restrict__ v,
     const float* __restrict__ u, const float* __restrict__ tau, const int32_t* __restrict__ death,
-    const int32_t* __restrict__ lists, const int32_t* __restrict__ counts, const float* __restrict__ lse,
-    const uint16_t* __restrict__ dO, const float* __restrict__ delta, uint16_t* __restrict__ dq, int H, int Gu, int n,
-    int k, int w, float scale, int nb, int BH, int q_begin, const int32_t* __restrict__ first_valid, int q_rows)
+    const int32_t* __restrict__ xpos, const int32_t* __restrict__ xdeath, const float* __restrict__ xu, int KP,
+    const int32_t* __restrict__ counts, const float* __restrict__ lse, const uint16_t* __restrict__ dO,
+    const float* __restrict__ delta, uint16_t* __restrict__ dq, int H, int Gu, int n, int k, int w, float scale,
+    int nb, int BH, int nrows, int q_begin, const int32_t* __restrict__ first_valid, int q_rows)
 {
-    using S = MfmaSmem<D, 64>;
     __shared__ __align__(16) DqSmem<D> sm;
-    constexpr int DS = D / 16, DB = D / 32, NX = S::NL / 4, LPR = S::RB / 16;
+    constexpr int DS = D / 16, DB = D / 32;
     int bh, blk;
     {
         const int id = blockIdx.x;
@@ -269,25 +417,38 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const ptrdiff_t qo = q_rows ? (ptrdiff_t)bh * q_rows - q_begin : (ptrdiff_t)bh * n;
     const unsigned char* kh = (const unsigned char*)(kk + (size_t)bh * n * D);
     const unsigned char* vh = (const unsigned char*)(v + (size_t)bh * n * D);
-    const float* ur = u + (size_t)row * n;
     const float* tr = tau + (size_t)row * n;
-    const int32_t* dr = death + (size_t)row * n;
-    const int32_t* list = lists + ((size_t)row * nb + blk) * (size_t)(k > 0 ? k : 1);
-    const int cnt = counts[(size_t)row * nb + blk];
+    const int nstay = counts[(size_t)nrows * nb + (size_t)row * nb + blk];
     const int c0 = max(max(0, i0 - w + 1), first_valid ? first_valid[row] : 0);
     const int c_end = min(n - 1, i0 + QB - 1);
-    const int nkl = (cnt + KT - 1) / KT * KT;
-    const int nkc = (c_end - c0 + 1 + KT - 1) / KT * KT;
-    const int nk_total = nkl + nkc;
+    // the list part is laid out for min(k, T0 + 1) keys, the length of a complete top-k list (see the forward)
+    const int T0 = i0 - w;
+    const int nkl = (T0 >= 0 && k > 0) ? (min(k, T0 + 1) + KT - 1) / KT * KT : 0;
+    const int nkc = max(0, (c_end - c0 + 1 + KT - 1) / KT * KT);
+    const int NT = (nkl + nkc) / KT;
+    StageSrc src;
+    {
+        const size_t xo = ((size_t)row * nb + blk) * (size_t)KP;
+        src.xpos = xpos + xo;
+        src.xdeath = xdeath + xo;
+        src.xu = xu + xo;
+        src.dr = death + (size_t)row * n;
+        src.ur = u + (size_t)row * n;
+        src.nkl = nkl;
+        src.c0 = c0;
+        src.c_end = c_end;
+        src.nt = NT;
+    }
 
     const int qa = i0 + 32 * wv;
-    const int qi = qa + col;
-    const int qrow = min(qi, n - 1);
+    const int qb = min(qa + 31, n - 1);
     const bool wave_live = qa < n;
-    const int qv = qi < n ? qi : -1;  // -1: no key passes "j <= query"
-    const float tau_q = (qi < n && qi - w >= 0) ? tr[qi - w] : 0.0f;
-    const float lse2 = lse[qo + qrow] * 1.4426950408889634f;
-    const float Di = delta[qo + qrow];
+    DqLane ln;
+    ln.qi = qa + col;
+    const int qrow = min(ln.qi, n - 1);
+    ln.tau_q = (ln.qi < n && ln.qi - w >= 0) ? tr[ln.qi - w] : 0.0f;
+    ln.lse2 = lse[qo + qrow] * 1.4426950408889634f;
+    ln.Di = delta[qo + qrow];
     bf16x8 qreg[DS], dreg[DS];
 #pragma unroll
     for (int s = 0; s < DS; s++) {
@@ -295,123 +456,37 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
         qreg[s] = *(const bf16x8*)(q + off);
         dreg[s] = *(const bf16x8*)(dO + off);
     }
+    stage_meta(sm, src, 0, wv, lane);
+    const WaveRuns wr = wave_runs(wave_live, nkl, nkc, nstay, qa, qb, w, c0);
     f32x16 acc_q[DB];
 #pragma unroll
     for (int x = 0; x < DB; x++)
 #pragma unroll
         for (int r = 0; r < 16; r++) acc_q[x][r] = 0.0f;
     const float c2 = scale * 1.4426950408889634f;
-
-    // transposing reads of K^T (see the forward's V^T operand): lane -> (row, column block)
-    const int r16 = lane & 15, grp2 = (lane >> 4) & 1;
-    const int tcol = (16 * grp2 + 4 * (r16 & 3)) * 2;
-    const int trow = 4 * half + (r16 >> 2);
-    auto kt_operand = [&](int g, int x) -> bf16x8 {
-        const int row0 = 16 * g + trow, row1 = row0 + 8;
-        const unsigned char* p0 = sm.kt + (row0 % S::NL) * S::GSV + (row0 / S::NL) * S::RB + tcol + 64 * x;
-        const unsigned char* p1 = sm.kt + (row1 % S::NL) * S::GSV + (row1 / S::NL) * S::RB + tcol + 64 * x;
-        const i16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)p0);
-        const i16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((i16x4 __attribute__((address_space(3)))*)p1);
-        const bf16x4 lo = __builtin_bit_cast(bf16x4, lo4), hi = __builtin_bit_cast(bf16x4, hi4);
-        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    };
-
-    for (int seg0 = 0; seg0 < nk_total; seg0 += SEG) {
-        const int seg_n = min(SEG, nk_total - seg0);
-        __syncthreads();  // previous segment fully consumed
-        for (int e = tid; e < seg_n; e += 256) {
-            const int E = seg0 + e;
-            int j = 0;
-            bool real;
-            if (E < nkl) {
-                real = E < cnt;
-                if (real) j = list[E];
-            } else {
-                j = c0 + (E - nkl);
-                real = j <= c_end;
-                if (!real) j = 0;
-            }
-            sm.jpos[e] = j;
-            sm.jlast[e] = real ? (w - 1 + dr[j]) : -1;
-            sm.ju[e] = real ? ur[j] : 0.0f;
-        }
-        const int ntiles = seg_n / KT;
-        for (int t = 0; t < ntiles; t++) {
-            __syncthreads();  // metadata staged / everybody done with the previous tile
-            {
-                const TileRows<D, 64> rows = tile_rows<D, 64>(sm.jpos + t * KT, wv, lane);
-                const int c = lane % LPR;
+    // Everything the compiler tracks must have arrived before the first untracked load (see the forward).
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-                for (int x = 0; x < NX; x++) {
-                    const int L = wv * NX + x;
-                    const uint32_t off = (uint32_t)rows.j[x] * (uint32_t)S::RB + 16u * (uint32_t)c;
-                    __builtin_amdgcn_global_load_lds((glb_void_t*)(kh + off), (lds_void_t*)&sm.kr[L * S::GSK], 16, 0, 0);
-                    __builtin_amdgcn_global_load_lds((glb_void_t*)(vh + off), (lds_void_t*)&sm.vr[L * S::GSK], 16, 0, 0);
-                    __builtin_amdgcn_global_load_lds((glb_void_t*)(kh + off), (lds_void_t*)&sm.kt[L * S::GSV], 16, 0, 0);
-                }
-            }
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();  // the tile has landed
-            if (!wave_live) continue;
-            const int base = t * KT;
-#pragma unroll
-            for (int mb = 0; mb < 2; mb++) {
-                const int trw = 32 * mb + col;
-                const int off = (trw % S::NL) * S::GSK + (trw / S::NL) * S::RB + 16 * half;
-                f32x16 acc_s, acc_d;
-#pragma unroll
-                for (int r = 0; r < 16; r++) { acc_s[r] = 0.0f; acc_d[r] = 0.0f; }
-#pragma unroll
-                for (int s = 0; s < DS; s++) {
-                    const bf16x8 ka = *(const bf16x8*)(sm.kr + off + 32 * s);
-                    const bf16x8 va = *(const bf16x8*)(sm.vr + off + 32 * s);
-                    acc_s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], acc_s, 0, 0, 0);
-                    acc_d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dreg[s], acc_d, 0, 0, 0);
-                }
-                // ds_ij without the softmax scale (applied once to the finished dQ); a pair that is not attended
-                // gets p = 0 through the exponent
-                u32x4 dsb[2];
-                float hold = 0.0f;
-#pragma unroll
-                for (int g4 = 0; g4 < 4; g4++) {
-                    const int kb = base + 32 * mb + 8 * g4 + 4 * half;
-                    const int4 J4 = *(const int4*)&sm.jpos[kb];
-                    const int4 L4 = *(const int4*)&sm.jlast[kb];
-                    const float4 U4 = *(const float4*)&sm.ju[kb];
-#pragma unroll
-                    for (int e = 0; e < 4; e++) {
-                        const int r = 4 * g4 + e;
-                        const int Jj = e == 0 ? J4.x : e == 1 ? J4.y : e == 2 ? J4.z : J4.w;
-                        const int Lj = e == 0 ? L4.x : e == 1 ? L4.y : e == 2 ? L4.z : L4.w;
-                        const float uj = e == 0 ? U4.x : e == 1 ? U4.y : e == 2 ? U4.z : U4.w;
-                        // attended  <=>  j <= i <= w - 1 + death_j; inside the window the gate is 1
-                        const bool valid = (Jj <= qv) && (qv <= Lj);
-                        const float qk = acc_s[r], dov = acc_d[r];
-                        float ds;
-                        if (MODE == 2) {
-                            const float arg = fmaf(qk, c2, -lse2);
-                            ds = __builtin_amdgcn_exp2f(valid ? arg : -INFINITY) * (dov - Di);
-                        } else {
-                            const float gate = (qv - Jj < w) ? 1.0f : clip01(uj - tau_q);
-                            const float arg = MODE == 0 ? fmaf(qk, gate * c2, -lse2) : fmaf(qk, c2, -lse2);
-                            const float p = __builtin_amdgcn_exp2f(valid ? arg : -INFINITY);
-                            ds = p * fmaf(gate, dov, -Di);
-                            if (MODE == 0) ds *= gate;
-                        }
-                        if ((r & 1) == 0) hold = ds;
-                        else dsb[r >> 3][(r & 7) >> 1] = pack_bf16x2(hold, ds);
-                    }
-                }
-#pragma unroll
-                for (int i = 0; i < 2 * DB; i++)
-                    acc_q[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt_operand(2 * mb + i / DB, i % DB),
-                                                                            __builtin_bit_cast(bf16x8, dsb[i / DB]),
-                                                                            acc_q[i % DB], 0, 0, 0);
-            }
-        }
+    for (int s = 0; s < DS; s++) asm volatile("" ::"v"(qreg[s]), "v"(dreg[s]));
+    asm volatile("" ::"v"(ln.tau_q), "v"(ln.lse2), "v"(ln.Di));
+    // (segment 0 of the metadata is published by the first tile's barriers: each wave waits for its own copies
+    //  before the second one)
+    {
+        const int jbase0 = c0 - nkl;
+        int T = 0;
+#define SPK_RUN(KIND, bound) \
+    dq_run_tiles<D, MODE, KIND>(sm, src, T, min(NT, (bound)), jbase0, kh, vh, wv, lane, ln, w, c2, qreg, dreg, acc_q)
+        SPK_RUN(TILE_LIST, wr.b0);
+        SPK_RUN(TILE_LIST_MASK, wr.b1);
+        if (wr.narrow) SPK_RUN(TILE_CONT, wr.b2);
+        else SPK_RUN(TILE_EDGE, wr.b2);
+        SPK_RUN(TILE_FAST, wr.b3);
+        SPK_RUN(TILE_DIAG, wr.b4);
+        SPK_RUN(TILE_SKIP, NT);
+#undef SPK_RUN
     }
-    if (qi < n) {
-        uint16_t* orow = dq + (size_t)(qo + qi) * D;
+    if (ln.qi < n) {
+        uint16_t* orow = dq + (size_t)(qo + ln.qi) * D;
 #pragma unroll
         for (int x = 0; x < DB; x++) {
 #pragma unroll
@@ -427,7 +502,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
 
 template <int D>
 static void launch_dq_mfma(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
-                           const float* tau, const int32_t* death, const int32_t* lists, const int32_t* counts,
+                           const float* tau, const int32_t* death, const ExtLists& x, const int32_t* counts,
                            const float* lse, const void* dO, const float* delta, void* dq, int nb, hipStream_t st,
                            int q_begin, const int32_t* first_valid, int q_rows)
 {
@@ -435,8 +510,9 @@ static void launch_dq_mfma(const sparsek_cfg& c, const void* q, const void* k, c
     dim3 grid(nb * BH);
 #define SPK_LAUNCH_DQ(MODE)                                                                                        \
     hipLaunchKernelGGL((attn_bwd_dq_kernel<D, MODE>), grid, dim3(256), 0, st, (const uint16_t*)q, (const uint16_t*)k, \
-                       (const uint16_t*)v, u, tau, death, lists, counts, lse, (const uint16_t*)dO, delta,          \
-                       (uint16_t*)dq, c.H, c.Gu, c.n, c.k, c.w, c.softmax_scale, nb, BH, q_begin, first_valid, q_rows)
+                       (const uint16_t*)v, u, tau, death, (const int32_t*)x.pos, (const int32_t*)x.death,          \
+                       (const float*)x.u, x.KP, counts, lse, (const uint16_t*)dO, delta, (uint16_t*)dq, c.H, c.Gu, \
+                       c.n, c.k, c.w, c.softmax_scale, nb, BH, c.B * c.Gu, q_begin, first_valid, q_rows)
     if (c.gate_mode == 0) SPK_LAUNCH_DQ(0);
     else if (c.gate_mode == 1) SPK_LAUNCH_DQ(1);
     else SPK_LAUNCH_DQ(2);
@@ -552,20 +628,6 @@ __global__ __launch_bounds__(1024) void abwd_elist_kernel(const int32_t* __restr
     }
 }
 
-// One Q and one dO tile (64 rows) serve two kinds of LDS reads: 16-byte row reads (A operand of S and dO.V) and
-// transposing 8-byte reads (A operand of dV and dK).  Each row lands once, unpadded, with its 16-byte chunks
-// permuted: chunk c of tile row R sits at chunk position c ^ swz(R).  swz is chosen so that both read patterns
-// touch every bank once per pass:
-//   row reads take one chunk column of 16 consecutive rows per 16 lanes  -> swz must differ on those rows
-//   transposing reads take 4 neighbouring chunks of 4 consecutive rows per 32 lanes -> swz / 4 must differ on those rows
-// (head dim 64: a row is half of the 64 banks, two rows share a pass, and the row's parity takes the place of one bit).
-template <int D>
-__device__ __forceinline__ int dkv_swz(int R)
-{
-    if constexpr (D == 128) return 4 * (R & 3) + ((R >> 2) & 3);
-    else return 4 * ((R >> 1) & 1) + ((R >> 2) & 3);
-}
-
 constexpr int DKV_NBUF = 2;  // tiles in LDS: one in use, one being filled
 template <int D>
 struct DkvSmem {
@@ -655,7 +717,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     const unsigned char* qh = (const unsigned char*)(q + qo * D);
     const unsigned char* gh = (const unsigned char*)(dO + qo * D);
 
-    // LDS byte offsets of this lane's operand reads (see dkv_swz):
+    // LDS byte offsets of this lane's operand reads (see tile_swz):
     //   row reads: tile row 32 * run + col, chunk 2 * step + half          -> roff[run][step]
     //   transposing reads: rows 16 g + 4 half + r16 / 4 (+ 8), chunk 4 x + 2 grp2 + (r16 % 4) / 2, 8-byte half r16 % 2
     //                                                                      -> toff[0 / 1][x] + 16 g rows
@@ -663,13 +725,13 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
     int roff[2][DS], toff[2][DB];
 #pragma unroll
     for (int run = 0; run < 2; run++) {
-        const int R = 32 * run + col, sw = dkv_swz<D>(R);
+        const int R = 32 * run + col, sw = tile_swz<D>(R);
 #pragma unroll
         for (int st = 0; st < DS; st++) roff[run][st] = R * RB + (((2 * st + half) ^ sw) << 4);
     }
 #pragma unroll
     for (int hl = 0; hl < 2; hl++) {
-        const int R = 4 * half + (r16 >> 2) + 8 * hl, sw = dkv_swz<D>(R);  // (swz has period 16 in R)
+        const int R = 4 * half + (r16 >> 2) + 8 * hl, sw = tile_swz<D>(R);  // (swz has period 16 in R)
 #pragma unroll
         for (int x = 0; x < DB; x++)
             toff[hl][x] = R * RB + (((4 * x + 2 * grp2 + ((r16 & 3) >> 1)) ^ sw) << 4) + 8 * (r16 & 1);
@@ -688,7 +750,7 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
 #pragma unroll
     for (int x = 0; x < NX; x++) {
         const int R = RPL * (wv * NX + x) + lane / LPR;
-        goff[x] = R * RB + (((lane % LPR) ^ dkv_swz<D>(R)) << 4);
+        goff[x] = R * RB + (((lane % LPR) ^ tile_swz<D>(R)) << 4);
     }
     auto issue = [&](int buf, int i_first) {
 #pragma unroll
@@ -955,7 +1017,14 @@ int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
     if (q_begin % 128 != 0) return SPARSEK_ERR_INVALID_ARG;
     if (!mfma)  // the generic kernel accumulates dk, dv with atomics
         hipLaunchKernelGGL(abwd_zero_kernel, dim3(2048), dim3(256), 0, st, (uint4*)(base + W.dk32), (W.sk32 - W.dk32) / 16);
-    launch_block_lists(c, death, lists, counts, st);
+    ExtLists x{nullptr, nullptr, nullptr, 0};
+    if (mfma) {
+        x.pos = (int32_t*)(base + W.xpos);
+        x.death = (int32_t*)(base + W.xdeath);
+        x.u = (float*)(base + W.xu);
+        x.KP = (int)ext_stride(c);
+    }
+    launch_block_lists_ext(c, death, lists, counts, u, x, st);
     dim3 grid(nb, c.B * c.H);
     if (c.dtype == SPARSEK_F32) {
         hipLaunchKernelGGL(abwd_delta_kernel<float>, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, (const float*)o,
@@ -984,12 +1053,12 @@ int launch_attn_bwd(const sparsek_cfg& c, const void* q, const void* k, const vo
             hipLaunchKernelGGL(abwd_elist_kernel, dim3(c.B * c.Gu), dim3(1024), 0, st, death, c.n, q_begin, elist, ecount,
                                eslot);
             if (c.d == 64) {
-                launch_dq_mfma<64>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st, q_begin, first_valid,
+                launch_dq_mfma<64>(c, q, k, v, u, tau, death, x, counts, lse, dO, delta, dq, nb, st, q_begin, first_valid,
                                    q_rows);
                 launch_dkv_mfma<64>(c, q, k, v, u, tau, death, elist, ecount, lse2, dO, delta, dk32, dv32, sk32, sv32, eslot,
                                     dk, dv, nb, st, q_begin, q_rows);
             } else {
-                launch_dq_mfma<128>(c, q, k, v, u, tau, death, lists, counts, lse, dO, delta, dq, nb, st, q_begin, first_valid,
+                launch_dq_mfma<128>(c, q, k, v, u, tau, death, x, counts, lse, dO, delta, dq, nb, st, q_begin, first_valid,
                                     q_rows);
                 launch_dkv_mfma<128>(c, q, k, v, u, tau, death, elist, ecount, lse2, dO, delta, dk32, dv32, sk32, sv32, eslot,
                                      dk, dv, nb, st, q_begin, q_rows);

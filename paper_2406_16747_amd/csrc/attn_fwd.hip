@@ -16,8 +16,6 @@
 namespace spk {
 
 
-static inline int nblocks(int n) { return (n + QB - 1) / QB; }
-
 // Workspace of the per-block top-k lists: lists [rows][nb][max(k,1)] int32, then counts [rows][nb]
 // (list lengths) and stays [rows][nb] (lengths of the first partitions).
 size_t block_lists_bytes(const sparsek_cfg& c, size_t* counts_offset)
@@ -28,16 +26,6 @@ size_t block_lists_bytes(const sparsek_cfg& c, size_t* counts_offset)
     size_t counts = align_up(2 * rows * nb * sizeof(int32_t), 256);
     if (counts_offset) *counts_offset = lists;
     return lists + counts;
-}
-
-// The MFMA forward kernel reads a second form of the lists: per (row, block) three parallel arrays of KP entries --
-// position, lifetime death[j] and score u[j] of every listed key -- so that it stages a segment of metadata with
-// plain copies (no gather by position).  Entries from the list length up to the next multiple of the tile size are
-// padding (position 0, lifetime INT_MIN: attended by nobody, score 0).
-static inline size_t ext_stride(const sparsek_cfg& c) { return align_up((size_t)(c.k > 0 ? c.k : 1), KT); }
-static inline size_t ext_array_bytes(const sparsek_cfg& c)
-{
-    return align_up((size_t)c.B * c.Gu * nblocks(c.n) * ext_stride(c) * sizeof(int32_t), 256);
 }
 
 size_t attn_fwd_ws_bytes(const sparsek_cfg& c) { return block_lists_bytes(c, nullptr) + 3 * ext_array_bytes(c); }
@@ -283,41 +271,10 @@ __global__ __launch_bounds__(256) void attn_fwd_generic_kernel(
 // with one MFMA followed by a slice of the softmax work, the slices fenced with sched_barrier
 // so that the compiler keeps the order.
 // ---------------------------------------------------------------------------------
-// Metadata (position, lifetime, score of every key of the block's key set) is staged in segments of TPS tiles, double
-// buffered: while the tiles of one segment run, the next segment is copied into the other buffer.
-constexpr int TPS = 9;
-constexpr int SEGN = TPS * KT;
-
+// The forward's LDS: the double-buffered K and V tiles and the staged metadata.
 template <int D>
-struct FwdSmem : MfmaTileBufs<D, 64> {
-    int32_t jpos[2][SEGN];    // key position
-    int32_t jdeath[2][SEGN];  // death[j]: the key is attended by query i while i <= w - 1 + death[j]; INT_MIN = padding
-    float ju[2][SEGN];        // key score
-};
+struct FwdSmem : MfmaTileBufs<D, 64>, TileMeta {};
 static_assert(sizeof(FwdSmem<128>) <= 80 * 1024, "two workgroups per CU");
-
-// Tile kinds.  Along a block's key set they come in runs (per wave), so the tile loop is a
-// sequence of loops, one per kind, and each loop body is straight-line code:
-//   LIST       selected keys that stay selected for every query of the block: gates, no mask
-//   LIST_MASK  selected keys some of which expire inside the block (the tail of the list), and
-//              contiguous keys that are behind every window of the wave: gates, lifetime test
-//   EDGE       contiguous keys at the trailing edge of the wave's windows: gate 1 inside the
-//              window, lifetime test (always true inside the window)
-//   FAST       contiguous keys inside every query's window and not in its future: nothing
-//   DIAG       contiguous keys inside every window, at the causal diagonal: causal test
-//   CONT       everything at once (narrow windows, where EDGE and DIAG overlap)
-//   SKIP       keys in the future of the whole wave: loads and barriers only
-enum { TILE_FAST = 0, TILE_LIST = 1, TILE_LIST_MASK = 2, TILE_CONT = 3, TILE_EDGE = 4, TILE_DIAG = 5, TILE_SKIP = 6 };
-
-template <int MODE, int KIND>
-struct TileTraits {
-    static constexpr bool SEL = KIND == TILE_LIST || KIND == TILE_LIST_MASK || KIND == TILE_CONT || KIND == TILE_EDGE;
-    static constexpr bool GATED = SEL && MODE != 2;   // the value gate applies
-    static constexpr bool KGATE = SEL && MODE == 0;   // the key gate applies
-    static constexpr bool SELECT = KIND == TILE_CONT || KIND == TILE_EDGE;  // window keys mixed in: gate 1
-    static constexpr bool MASKL = KIND == TILE_LIST_MASK || KIND == TILE_CONT || KIND == TILE_EDGE;
-    static constexpr bool MASKC = KIND == TILE_CONT || KIND == TILE_DIAG;
-};
 
 template <int D>
 __device__ __forceinline__ void rescale_o(f32x16 (&acc_o)[D / 32], float alpha)
@@ -547,50 +504,6 @@ __device__ __forceinline__ void tile_body(FwdSmem<D>& sm, int buf, const int32_t
     });
 }
 
-// What a wave needs to stage a segment of metadata (see FwdSmem).
-struct StageSrc {
-    const int32_t* xpos;    // extended list of this (row, block): positions, lifetimes, scores
-    const int32_t* xdeath;
-    const float* xu;
-    const int32_t* dr;      // lifetimes and scores of the score row, for the contiguous keys
-    const float* ur;
-    int nkl, c0, c_end, nt; // list part in keys (whole tiles), first and last contiguous key, tiles in all
-};
-
-// Segment sg of the block's key set (tiles sg*TPS .. ) goes to metadata buffer sg & 1.  Each wave copies the tiles
-// wv, wv + 4, ...: plain copies that land in LDS without passing through registers and that the compiler does not
-// track (the per-tile s_waitcnt vmcnt(0) + barrier publishes them).  A tile lies entirely in the list part or
-// entirely in the contiguous part.
-template <int D>
-__device__ __forceinline__ void stage_meta(FwdSmem<D>& sm, const StageSrc& src, int sg, int wv, int lane)
-{
-    const int mb = sg & 1;
-    const int t_end = min(TPS, src.nt - sg * TPS);
-    for (int lt = wv; lt < t_end; lt += 4) {
-        const int E0 = (sg * TPS + lt) * KT;
-        int32_t* dp = sm.jpos[mb] + lt * KT;
-        int32_t* dd = sm.jdeath[mb] + lt * KT;
-        float* du = sm.ju[mb] + lt * KT;
-        if (E0 < src.nkl) {
-            const uint32_t off = 4u * (uint32_t)(E0 + lane);
-            async_load_lds4(src.xpos, off, dp);
-            async_load_lds4(src.xdeath, off, dd);
-            async_load_lds4(src.xu, off, du);
-        } else {
-            const int j = src.c0 + (E0 - src.nkl) + lane;
-            const bool real = j <= src.c_end;
-            dp[lane] = real ? j : 0;
-            if (real) {
-                async_load_lds4(src.dr, 4u * (uint32_t)j, dd);
-                async_load_lds4(src.ur, 4u * (uint32_t)j, du);
-            } else {   // beyond the block's last key: always behind the causal test; any finite value will do
-                dd[lane] = INT32_MIN;
-                du[lane] = 0.0f;
-            }
-        }
-    }
-}
-
 // The tiles [T, T_end) of the block's key set, all of one kind.  T counts the block's tiles; tile T uses K/V buffer
 // T & 1 and the metadata of segment T / TPS.
 template <int D, int MODE, int KIND>
@@ -607,7 +520,7 @@ __device__ __forceinline__ void run_tiles(FwdSmem<D>& sm, const StageSrc& src, i
         __syncthreads();
         const int sg = T / TPS, lt = T - sg * TPS;
         // first tile of a segment: everybody has left the segment before, so its metadata buffer takes the next one
-        if (lt == 0 && (sg + 1) * TPS < src.nt) stage_meta<D>(sm, src, sg + 1, wv, lane);
+        if (lt == 0 && (sg + 1) * TPS < src.nt) stage_meta(sm, src, sg + 1, wv, lane);
         const int sgn = (T + 1) / TPS;
         const int32_t* jp_next = sm.jpos[sgn & 1] + (T + 1 - sgn * TPS) * KT;
         const bool more = T + 1 < src.nt;
@@ -696,30 +609,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     for (int s = 0; s < DS; s++)
         qreg[s] = *(const bf16x8*)(qh + (size_t)qrow * D + 16 * s + 8 * half);
     // the first segment of metadata: its copies need nothing that is loaded above, so they fly together
-    stage_meta<D>(sm, src, 0, wv, lane);
+    stage_meta(sm, src, 0, wv, lane);
 
     // ---- the runs of tile kinds for this wave, as tile numbers (all wave-uniform) ----
-    //   [0,b0) LIST  [b0,b1) LIST_MASK  [b1,b2) EDGE or CONT  [b2,b3) FAST  [b3,b4) DIAG  [b4,..) SKIP
-    int b0 = 0, b1 = 0, b2 = 0, b3 = 0, b4 = 0;
-    bool narrow = false;
-    if (wave_live) {
-        const int TL = nkl / KT, NC = nkc / KT;
-        b0 = min(nstay / KT, TL);
-        // contiguous tile m covers positions c0 + 64m .. c0 + 64m + 63
-        const int x_sel = qa - w - c0 - (KT - 1);     // m <= x_sel/64: behind every window of the wave
-        const int x_fb = qb - w - c0;                 // m >  x_fb/64:  inside every window of the wave
-        const int x_fe = qa - c0 - (KT - 1);          // m <= x_fe/64:  in nobody's future
-        const int m_sel = x_sel >= 0 ? x_sel / KT + 1 : 0;
-        const int m_fb = x_fb >= 0 ? x_fb / KT + 1 : 0;
-        const int m_fe = x_fe >= 0 ? x_fe / KT + 1 : 0;
-        const int m_skip = (qb - c0) / KT + 1;        // first tile entirely in the wave's future
-        narrow = m_fb >= m_fe;                        // no tile is both inside every window and in the past
-        b1 = TL + min(m_sel, NC);
-        b4 = TL + min(m_skip, NC);
-        b2 = narrow ? b4 : TL + min(m_fb, NC);
-        b3 = narrow ? b4 : TL + min(m_fe, NC);
-        b1 = min(b1, b2);
-    }
+    const WaveRuns wr = wave_runs(wave_live, nkl, nkc, nstay, qa, qb, w, c0);
+    const int b0 = wr.b0, b1 = wr.b1, b2 = wr.b2, b3 = wr.b3, b4 = wr.b4;
+    const bool narrow = wr.narrow;
 
     f32x16 acc_o[DB];
 #pragma unroll
@@ -773,13 +668,6 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma_kernel(
     }
 }
 
-struct ExtLists {
-    int32_t* pos;
-    int32_t* death;
-    float* u;
-    int KP;
-};
-
 template <int D>
 static void launch_mfma(const sparsek_cfg& c, const void* q, const void* k, const void* v, const float* u,
                         const float* tau, const int32_t* death, const ExtLists& x, const int32_t* counts,
@@ -799,7 +687,7 @@ static void launch_mfma(const sparsek_cfg& c, const void* q, const void* k, cons
 #undef SPK_LAUNCH
 }
 
-static void launch_block_lists_ext(const sparsek_cfg& c, const int32_t* death, int32_t* lists, int32_t* counts,
+void launch_block_lists_ext(const sparsek_cfg& c, const int32_t* death, int32_t* lists, int32_t* counts,
                                    const float* u, const ExtLists& x, hipStream_t st)
 {
     const int nb = nblocks(c.n);

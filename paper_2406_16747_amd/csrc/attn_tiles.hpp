@@ -1,5 +1,6 @@
-// Shared by the attention forward and the mask-backward MFMA kernels: vector types, tile
-// geometry, the LDS staging area and the direct-to-LDS gather of one K/V tile.
+// Shared by the MFMA kernels of the attention forward, the attention backward and the mask backward: vector
+// types, tile geometry, LDS staging areas, the direct-to-LDS gather of one K/V tile, the per-block key lists and
+// the classification of a query block's tiles into kinds.
 #pragma once
 #include "common.hpp"
 #include <type_traits>
@@ -116,6 +117,138 @@ __device__ __forceinline__ void issue_tile_loads(MfmaTileBufs<D, VPAD>& sm, int 
     const TileRows<D, VPAD> rows = tile_rows<D, VPAD>(jp, wv, lane);
 #pragma unroll
     for (int x = 0; x < MfmaTileBufs<D, VPAD>::NL / 4; x++) tile_load_step<D, VPAD>(sm, buf, rows, x, kh, vh, wv, lane);
+}
+
+inline int nblocks(int n) { return (n + QB - 1) / QB; }
+
+// The MFMA forward kernel reads a second form of the lists: per (row, block) three parallel arrays of KP entries --
+// position, lifetime death[j] and score u[j] of every listed key -- so that it stages a segment of metadata with
+// plain copies (no gather by position).  Entries from the list length up to the next multiple of the tile size are
+// padding (position 0, lifetime INT_MIN: attended by nobody, score 0).
+inline size_t ext_stride(const sparsek_cfg& c) { return align_up((size_t)(c.k > 0 ? c.k : 1), KT); }
+inline size_t ext_array_bytes(const sparsek_cfg& c)
+{
+    return align_up((size_t)c.B * c.Gu * nblocks(c.n) * ext_stride(c) * sizeof(int32_t), 256);
+}
+
+struct ExtLists {
+    int32_t* pos;
+    int32_t* death;
+    float* u;
+    int KP;
+};
+
+// Builds the per-block lists (and, with x.pos != nullptr, their extended form) of every score row.
+void launch_block_lists_ext(const sparsek_cfg& c, const int32_t* death, int32_t* lists, int32_t* counts,
+                            const float* u, const ExtLists& x, hipStream_t st);
+
+// Metadata (position, lifetime, score of every key of the block's key set) is staged in segments of TPS tiles, double
+// buffered: while the tiles of one segment run, the next segment is copied into the other buffer.
+constexpr int TPS = 9;
+constexpr int SEGN = TPS * KT;
+
+struct TileMeta {
+    int32_t jpos[2][SEGN];    // key position
+    int32_t jdeath[2][SEGN];  // death[j]: the key is attended by query i while i <= w - 1 + death[j]; INT_MIN = padding
+    float ju[2][SEGN];        // key score
+};
+
+// Tile kinds.  Along a block's key set they come in runs (per wave), so the tile loop is a
+// sequence of loops, one per kind, and each loop body is straight-line code:
+//   LIST       selected keys that stay selected for every query of the block: gates, no mask
+//   LIST_MASK  selected keys some of which expire inside the block (the tail of the list), and
+//              contiguous keys that are behind every window of the wave: gates, lifetime test
+//   EDGE       contiguous keys at the trailing edge of the wave's windows: gate 1 inside the
+//              window, lifetime test (always true inside the window)
+//   FAST       contiguous keys inside every query's window and not in its future: nothing
+//   DIAG       contiguous keys inside every window, at the causal diagonal: causal test
+//   CONT       everything at once (narrow windows, where EDGE and DIAG overlap)
+//   SKIP       keys in the future of the whole wave: loads and barriers only
+enum { TILE_FAST = 0, TILE_LIST = 1, TILE_LIST_MASK = 2, TILE_CONT = 3, TILE_EDGE = 4, TILE_DIAG = 5, TILE_SKIP = 6 };
+
+template <int MODE, int KIND>
+struct TileTraits {
+    static constexpr bool SEL = KIND == TILE_LIST || KIND == TILE_LIST_MASK || KIND == TILE_CONT || KIND == TILE_EDGE;
+    static constexpr bool GATED = SEL && MODE != 2;   // the value gate applies
+    static constexpr bool KGATE = SEL && MODE == 0;   // the key gate applies
+    static constexpr bool SELECT = KIND == TILE_CONT || KIND == TILE_EDGE;  // window keys mixed in: gate 1
+    static constexpr bool MASKL = KIND == TILE_LIST_MASK || KIND == TILE_CONT || KIND == TILE_EDGE;
+    static constexpr bool MASKC = KIND == TILE_CONT || KIND == TILE_DIAG;
+};
+
+// What a wave needs to stage a segment of metadata (see TileMeta).
+struct StageSrc {
+    const int32_t* xpos;    // extended list of this (row, block): positions, lifetimes, scores
+    const int32_t* xdeath;
+    const float* xu;
+    const int32_t* dr;      // lifetimes and scores of the score row, for the contiguous keys
+    const float* ur;
+    int nkl, c0, c_end, nt; // list part in keys (whole tiles), first and last contiguous key, tiles in all
+};
+
+// Segment sg of the block's key set (tiles sg*TPS .. ) goes to metadata buffer sg & 1.  Each wave copies the tiles
+// wv, wv + 4, ...: plain copies that land in LDS without passing through registers and that the compiler does not
+// track (the per-tile s_waitcnt vmcnt(0) + barrier publishes them).  A tile lies entirely in the list part or
+// entirely in the contiguous part.
+__device__ __forceinline__ void stage_meta(TileMeta& sm, const StageSrc& src, int sg, int wv, int lane)
+{
+    const int mb = sg & 1;
+    const int t_end = min(TPS, src.nt - sg * TPS);
+    for (int lt = wv; lt < t_end; lt += 4) {
+        const int E0 = (sg * TPS + lt) * KT;
+        int32_t* dp = sm.jpos[mb] + lt * KT;
+        int32_t* dd = sm.jdeath[mb] + lt * KT;
+        float* du = sm.ju[mb] + lt * KT;
+        if (E0 < src.nkl) {
+            const uint32_t off = 4u * (uint32_t)(E0 + lane);
+            async_load_lds4(src.xpos, off, dp);
+            async_load_lds4(src.xdeath, off, dd);
+            async_load_lds4(src.xu, off, du);
+        } else {
+            const int j = src.c0 + (E0 - src.nkl) + lane;
+            const bool real = j <= src.c_end;
+            dp[lane] = real ? j : 0;
+            if (real) {
+                async_load_lds4(src.dr, 4u * (uint32_t)j, dd);
+                async_load_lds4(src.ur, 4u * (uint32_t)j, du);
+            } else {   // beyond the block's last key: always behind the causal test; any finite value will do
+                dd[lane] = INT32_MIN;
+                du[lane] = 0.0f;
+            }
+        }
+    }
+}
+
+// The runs of tile kinds for one wave (queries qa .. qb) along its block's key set, as tile numbers (wave-uniform):
+//   [0,b0) LIST  [b0,b1) LIST_MASK  [b1,b2) EDGE or CONT  [b2,b3) FAST  [b3,b4) DIAG  [b4,..) SKIP
+// nkl, nkc: list part and contiguous part in keys (whole tiles); nstay: listed keys that stay selected for the whole
+// block; c0: first contiguous key.
+struct WaveRuns {
+    int b0, b1, b2, b3, b4;
+    bool narrow;
+};
+__device__ __forceinline__ WaveRuns wave_runs(bool wave_live, int nkl, int nkc, int nstay, int qa, int qb, int w, int c0)
+{
+    WaveRuns r{0, 0, 0, 0, 0, false};
+    if (wave_live) {
+        const int TL = nkl / KT, NC = nkc / KT;
+        r.b0 = min(nstay / KT, TL);
+        // contiguous tile m covers positions c0 + 64m .. c0 + 64m + 63
+        const int x_sel = qa - w - c0 - (KT - 1);     // m <= x_sel/64: behind every window of the wave
+        const int x_fb = qb - w - c0;                 // m >  x_fb/64:  inside every window of the wave
+        const int x_fe = qa - c0 - (KT - 1);          // m <= x_fe/64:  in nobody's future
+        const int m_sel = x_sel >= 0 ? x_sel / KT + 1 : 0;
+        const int m_fb = x_fb >= 0 ? x_fb / KT + 1 : 0;
+        const int m_fe = x_fe >= 0 ? x_fe / KT + 1 : 0;
+        const int m_skip = (qb - c0) / KT + 1;        // first tile entirely in the wave's future
+        r.narrow = m_fb >= m_fe;                      // no tile is both inside every window and in the past
+        r.b1 = TL + min(m_sel, NC);
+        r.b4 = TL + min(m_skip, NC);
+        r.b2 = r.narrow ? r.b4 : TL + min(m_fb, NC);
+        r.b3 = r.narrow ? r.b4 : TL + min(m_fe, NC);
+        r.b1 = min(r.b1, r.b2);
+    }
+    return r;
 }
 
 // Compile-time loop: f(integral_constant<int, I>) for I = 0 .. N-1.
