@@ -769,14 +769,15 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_kernel(
         const int i = min(i_first + lane, n - 1);
         async_load_lds4(msrc, 4u * (uint32_t)(wv >= 2 ? max(i - w, 0) : i), &meta[buf][wv][0]);
     };
-    // The K / V fragments must have arrived before the first untracked load is issued: the compiler's own
-    // wait for them would otherwise sit at their first use, inside the loop, and count the prefetches too.
-#pragma unroll
-    for (int s = 0; s < DS; s++) asm volatile("" ::"v"(kreg[s]), "v"(vreg[s]));
     if (ntiles > 0) {
         issue_meta(0, blo);
         issue(0, blo);
     }
+    // The K / V fragments must have arrived before the tile loop: the compiler's own wait for them would otherwise
+    // sit at their first use, inside the loop, and count the prefetches of every iteration too.  (The first tile's
+    // gather is already in flight beside them; the loop waits for it anyway.)
+#pragma unroll
+    for (int s = 0; s < DS; s++) asm volatile("" ::"v"(kreg[s]), "v"(vreg[s]));
     // One tile for this wave, as four runs of NS MFMAs:
     //   1: S and dO.V of queries 0..31            2: the same for queries 32..63, under it the elementwise
     //   3: dV, dK += from queries 0..31, under        work (P, dS) of queries 0..31
